@@ -1,0 +1,122 @@
+"""ctypes front end of the CPU oracle (oracle/laser_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg; never by the GPU package.  This module marshals
+numpy arrays and nothing else; every routing step runs in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "laser_oracle.c")
+_LIB = os.path.join(_HERE, "liblaser_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off: the binary32 decision
+    arithmetic must not be fused behind the code's back."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+               "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32, f32, f64, vp = ctypes.c_int32, ctypes.c_float, ctypes.c_double, ctypes.c_void_p
+        lib.laser_oracle_gate.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        lib.laser_oracle_gate.restype = ctypes.c_int
+        lib.laser_oracle_exp.argtypes = [f32]
+        lib.laser_oracle_exp.restype = f32
+        lib.laser_oracle_tree_sum.argtypes = [vp, i32]
+        lib.laser_oracle_tree_sum.restype = f32
+        lib.laser_oracle_route.argtypes = [vp, i32, i32, i32, i32, f32, f32, i32,
+                                           vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.laser_oracle_route.restype = ctypes.c_int
+        lib.laser_oracle_route_literal.argtypes = [vp, i32, i32, i32, i32, f64, f64, i32,
+                                                   vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.laser_oracle_route_literal.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def gate(hidden: np.ndarray, w_gate: np.ndarray, dtype: int) -> np.ndarray:
+    """fp64 logits [T,E].  dtype 0: float32 arrays; 1: uint16 bf16 bit patterns."""
+    want = np.uint16 if dtype == 1 else np.float32
+    hidden = np.ascontiguousarray(hidden, dtype=want)
+    w_gate = np.ascontiguousarray(w_gate, dtype=want)
+    T, H = hidden.shape
+    E = w_gate.shape[0]
+    assert w_gate.shape[1] == H
+    out = np.empty((T, E), dtype=np.float64)
+    rc = _load().laser_oracle_gate(_ptr(hidden), _ptr(w_gate), T, H, E, dtype, _ptr(out))
+    if rc:
+        raise ValueError(f"laser_oracle_gate: {rc}")
+    return out
+
+
+def exp_canon(x: float) -> float:
+    return float(_load().laser_oracle_exp(np.float32(x)))
+
+
+def tree_sum(v: np.ndarray) -> float:
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    return float(_load().laser_oracle_tree_sum(_ptr(v), v.size))
+
+
+def _route(fn, logits, ldtype, k, c, eps_high, t_fix, loads_in, renormalize):
+    logits = np.ascontiguousarray(logits, dtype=ldtype)
+    T, E = logits.shape
+    loads_in = np.ascontiguousarray(loads_in, dtype=np.int32)
+    assert loads_in.shape == (E,)
+    out = {
+        "loads": np.empty(E, dtype=np.int32),
+        "expert_ids": np.empty((T, k), dtype=np.int32),
+        "weights": np.empty((T, k), dtype=np.float64),
+        "permutation": np.empty(T * k, dtype=np.int32),
+        "expert_offsets": np.empty(E + 1, dtype=np.int32),
+        "expanded": np.empty(T, dtype=np.uint8),
+        "cstar": np.empty(T, dtype=np.int32),
+    }
+    rc = fn(_ptr(logits), T, E, k, c, eps_high, t_fix, int(bool(renormalize)),
+            _ptr(loads_in), _ptr(out["loads"]), _ptr(out["expert_ids"]),
+            _ptr(out["weights"]), _ptr(out["permutation"]), _ptr(out["expert_offsets"]),
+            _ptr(out["expanded"]), _ptr(out["cstar"]))
+    if rc:
+        raise ValueError(f"oracle route: bad arguments ({rc})")
+    return out
+
+
+def route(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
+    """Router with binary32 decisions on fp32 logits [T,E]; returns a dict."""
+    return _route(_load().laser_oracle_route, logits, np.float32, k, c,
+                  float(np.float32(eps_high)), float(np.float32(t_fix)), loads_in, renormalize)
+
+
+def route_literal(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
+    """Router in fp64 with the paper's formulas as printed, on fp64 logits."""
+    return _route(_load().laser_oracle_route_literal, logits, np.float64, k, c,
+                  float(eps_high), float(t_fix), loads_in, renormalize)
+
+
+def route_from_hidden(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True):
+    """Gate in fp64, rounded once to fp32, then route()."""
+    z = gate(hidden, w_gate, dtype)
+    out = route(z.astype(np.float32), k, c, eps_high, t_fix, loads_in, renormalize)
+    out["logits"] = z
+    return out

@@ -1,0 +1,329 @@
+/*
+ * CPU oracle for the per-layer LASER routing step.  TEST INFRASTRUCTURE ONLY:
+ * slow, single-threaded, written to be checked against the paper by eye.  It
+ * shares no code, header, table or constant with the GPU library and must never
+ * be called from the product path.
+ *
+ * What it computes (paper: section "The Method", appendix "Pseudo Code",
+ * Algorithm 1 "per token, per layer"):
+ *   gate projection   z[t,e] = sum_h hidden[t,h] * W[e,h]            (fp64)
+ *   scores            s = softmax(z)        ("s_i >= 0, sum_i s_i = 1")
+ *   top-k mass        M_k = s_(1) + ... + s_(k)
+ *   expansion rule    M_k >= eps_high  ->  A = top-k, stop
+ *   candidate pool    T = { i : s_i >= t_fix * s_(1) }  union  top-k
+ *   trimming (TOP)    Cand = the c* = min(c, |T|) highest-scoring members of T
+ *   final assignment  sort Cand by (load ascending, score descending); A = first k
+ * applied to tokens 0..T-1 in index order, each expert of A getting load += 1
+ * before the next token is routed (the paper's "current load" L_e; Algorithm 1
+ * itself has no update line -- this is the reading taken here), followed by the
+ * token-to-expert dispatch tables (per-expert counts, their exclusive prefix
+ * sums, and the stable counting-sort permutation of the T*k assignments).
+ *
+ * Two routers live here:
+ *   laser_oracle_route          decisions in binary32 under the fixed operation
+ *                               order documented at exp_canon()/route below (the
+ *                               precision the GPU kernels decide in), weights in
+ *                               fp64.
+ *   laser_oracle_route_literal  everything in fp64 with libm, formulas exactly as
+ *                               printed in the paper; used to check that the
+ *                               binary32 reading has the paper's meaning.
+ *
+ * Pins (tests/test_oracle_*.py): hand-worked cases, reduction to a library top-k
+ * (c = k, small eps_high, t_fix = 1), brute-force subset enumeration, the
+ * load-only closed form (equal final loads), counting invariants, split-call
+ * equivalence, numpy stable argsort for the dispatch, numpy fp64 matmul for the
+ * gate, libm exp for exp_canon.  No function here is "parity unpinned"; what is
+ * unpinned is agreement with the paper's own runs, which print no routing values.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_E_ARG (-1)
+#define ORACLE_E_MEM (-2)
+
+/* ------------------------------------------------------------------ gate -- */
+
+static double bf16_to_double(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+/* Gate function: the learned linear map from a token's hidden state to one
+ * logit per expert (Introduction: "a lightweight gating network produces a score
+ * distribution over experts").  dtype 0 = fp32 inputs, 1 = bf16 bit patterns.
+ * hidden [T,H] row-major, w [E,H] row-major, logits [T,E] fp64. */
+int laser_oracle_gate(const void* hidden, const void* w, int32_t T, int32_t H,
+                      int32_t E, int32_t dtype, double* logits) {
+  if (T < 0 || H < 1 || E < 1 || (dtype != 0 && dtype != 1)) return ORACLE_E_ARG;
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t e = 0; e < E; ++e) {
+      double acc = 0.0;
+      for (int32_t h = 0; h < H; ++h) {
+        double x, y;
+        if (dtype == 1) {
+          x = bf16_to_double(((const uint16_t*)hidden)[(size_t)t * H + h]);
+          y = bf16_to_double(((const uint16_t*)w)[(size_t)e * H + h]);
+        } else {
+          x = (double)((const float*)hidden)[(size_t)t * H + h];
+          y = (double)((const float*)w)[(size_t)e * H + h];
+        }
+        acc += x * y;
+      }
+      logits[(size_t)t * E + e] = acc;
+    }
+  }
+  return ORACLE_OK;
+}
+
+/* ------------------------------------------------- binary32 building blocks -- */
+
+/* exp(x) for x in [-80, 0] as a fixed sequence of binary32 operations, so that
+ * two independent implementations return the same bits:
+ *   n = rint(x * fl(log2 e));  r = x - n*ln2 (two-constant Cody-Waite, fused);
+ *   q = degree-7 Taylor polynomial of exp(r) in Horner form with fused
+ *   multiply-adds, coefficients fl(1/j!);  result = q * 2^n (exact scaling).
+ * exp_canon(0) is exactly 1. */
+float laser_oracle_exp(float x) {
+  const float log2e = 0x1.715476p+0f;
+  const float ln2_hi = 0x1.62e4p-1f;
+  const float ln2_lo = 0x1.7f7d1cp-20f;
+  float n = rintf(x * log2e);
+  float r = fmaf(n, -ln2_hi, x);
+  r = fmaf(n, -ln2_lo, r);
+  float q = 0x1.a01a02p-13f;          /* 1/7! */
+  q = fmaf(q, r, 0x1.6c16c2p-10f);    /* 1/6! */
+  q = fmaf(q, r, 0x1.111112p-7f);     /* 1/5! */
+  q = fmaf(q, r, 0x1.555556p-5f);     /* 1/4! */
+  q = fmaf(q, r, 0x1.555556p-3f);     /* 1/3! */
+  q = fmaf(q, r, 0.5f);               /* 1/2! */
+  q = fmaf(q, r, 1.0f);
+  q = fmaf(q, r, 1.0f);
+  return ldexpf(q, (int)n);
+}
+
+/* Sum of v[0..n) in binary32 by the fixed tree: pad with +0 to a power of two P,
+ * then for s = P/2, P/4, ..., 1 add element i+s onto element i for all i < s. */
+float laser_oracle_tree_sum(const float* v, int32_t n) {
+  int32_t P = 1;
+  while (P < n) P *= 2;
+  float* b = (float*)calloc((size_t)P, sizeof(float));
+  if (!b) return NAN;
+  for (int32_t i = 0; i < n; ++i) b[i] = v[i];
+  for (int32_t s = P / 2; s >= 1; s /= 2)
+    for (int32_t i = 0; i < s; ++i) b[i] = b[i] + b[i + s];
+  float r = b[0];
+  free(b);
+  return r;
+}
+
+/* Descending order of experts by logit, equal logits by lower index first: the one
+ * total order used wherever the paper says "s_(1) >= s_(2) >= ...", "highest
+ * scores" or "tiebreak: descending s_e".  Softmax is monotone, so ordering logits
+ * orders scores, without merging scores that round to the same value. */
+static void order_desc_f32(const float* z, int32_t E, int32_t* ord) {
+  for (int32_t i = 0; i < E; ++i) ord[i] = i;
+  for (int32_t i = 1; i < E; ++i) {            /* insertion sort, stable */
+    int32_t x = ord[i];
+    int32_t j = i - 1;
+    while (j >= 0 && z[ord[j]] < z[x]) { ord[j + 1] = ord[j]; --j; }
+    ord[j + 1] = x;
+  }
+}
+
+static void order_desc_f64(const double* z, int32_t E, int32_t* ord) {
+  for (int32_t i = 0; i < E; ++i) ord[i] = i;
+  for (int32_t i = 1; i < E; ++i) {
+    int32_t x = ord[i];
+    int32_t j = i - 1;
+    while (j >= 0 && z[ord[j]] < z[x]) { ord[j + 1] = ord[j]; --j; }
+    ord[j + 1] = x;
+  }
+}
+
+/* "StableSortByLoad(Cand; L)": primary key ascending load, ties by position in the
+ * score-descending candidate list; returns the first k in `chosen` as positions
+ * into cand[], then re-listed in score order (the output lists A by descending
+ * score). */
+static void pick_least_loaded(const int32_t* cand, int32_t cstar, int32_t k,
+                              const int64_t* L, int32_t* chosen_pos) {
+  int32_t pos[256];
+  for (int32_t i = 0; i < cstar; ++i) pos[i] = i;
+  for (int32_t i = 1; i < cstar; ++i) {        /* stable insertion sort by load */
+    int32_t x = pos[i];
+    int32_t j = i - 1;
+    while (j >= 0 && L[cand[pos[j]]] > L[cand[x]]) { pos[j + 1] = pos[j]; --j; }
+    pos[j + 1] = x;
+  }
+  for (int32_t i = 0; i < k; ++i) chosen_pos[i] = pos[i];
+  for (int32_t i = 1; i < k; ++i) {            /* back to score order */
+    int32_t x = chosen_pos[i];
+    int32_t j = i - 1;
+    while (j >= 0 && chosen_pos[j] > x) { chosen_pos[j + 1] = chosen_pos[j]; --j; }
+    chosen_pos[j + 1] = x;
+  }
+}
+
+/* Dispatch tables from the final assignment (the paper only says tokens are then
+ * routed to experts "via all-to-all"; this is the index structure that move
+ * needs): counts per expert, exclusive prefix sums, and the flat assignment slots
+ * t*k+j listed expert by expert, ascending slot order inside an expert. */
+static void build_dispatch(const int32_t* ids, int32_t T, int32_t k, int32_t E,
+                           int32_t* permutation, int32_t* offsets) {
+  int64_t n = (int64_t)T * k;
+  int32_t pos = 0;
+  for (int32_t e = 0; e < E; ++e) {
+    offsets[e] = pos;
+    for (int64_t s = 0; s < n; ++s)
+      if (ids[s] == e) permutation[pos++] = (int32_t)s;
+  }
+  offsets[E] = pos;
+}
+
+static int check_args(int32_t T, int32_t E, int32_t k, int32_t c, double eps, double tfix) {
+  if (T < 0 || E < 1 || E > 256 || k < 1 || c < k || c > E) return ORACLE_E_ARG;
+  if (!(eps > 0.0) || !(tfix > 0.0) || tfix > 1.0) return ORACLE_E_ARG;
+  if ((int64_t)T * k > 0x7fffffff) return ORACLE_E_ARG;
+  return ORACLE_OK;
+}
+
+/* ------------------------------------------------- the router, binary32 ---- */
+
+/* logits [T,E] fp32.  Outputs: expert_ids [T,k] (score-descending inside a
+ * token), weights [T,k] fp64, loads_out [E], permutation [T*k], offsets [E+1];
+ * optional diagnostics expanded [T] (1 = took the load-aware branch) and
+ * cstar [T] (size of the working set; k on the top-k branch).
+ *
+ * Decision arithmetic, all binary32, round-to-nearest-even, no contraction:
+ *   d_i = z_i - z_(1);  p_i = exp_canon(max(d_i, -80));  Z = tree_sum(p);
+ *   S_k = ((p_(1) + p_(2)) + ...) + p_(k);
+ *   top-k branch  <=>  S_k >= fl(eps_high * Z)          [M_k >= eps_high]
+ *   pool member   <=>  d_i >= fl32(ln t_fix)            [s_i >= t_fix * s_(1)]
+ * The pool test is monotone in the ordering, so the pool is a prefix of it and
+ * "the c* highest-scoring members" are the first c* of the ordering. */
+int laser_oracle_route(const float* logits, int32_t T, int32_t E, int32_t k, int32_t c,
+                       float eps_high, float t_fix, int32_t renormalize,
+                       const int32_t* loads_in, int32_t* loads_out,
+                       int32_t* expert_ids, double* weights,
+                       int32_t* permutation, int32_t* offsets,
+                       uint8_t* expanded, int32_t* cstar_out) {
+  int rc = check_args(T, E, k, c, eps_high, t_fix);
+  if (rc) return rc;
+  const float tau_ln = (float)log((double)t_fix);
+  int64_t L[256];
+  int32_t ord[256], chosen[256];
+  float d[256], p[256];
+  for (int32_t e = 0; e < E; ++e) L[e] = loads_in[e];
+
+  for (int32_t t = 0; t < T; ++t) {
+    const float* z = logits + (size_t)t * E;
+    order_desc_f32(z, E, ord);
+    const float zmax = z[ord[0]];
+    for (int32_t i = 0; i < E; ++i) {
+      d[i] = z[i] - zmax;
+      p[i] = laser_oracle_exp(d[i] < -80.0f ? -80.0f : d[i]);
+    }
+    const float Z = laser_oracle_tree_sum(p, E);
+    float Sk = p[ord[0]];
+    for (int32_t i = 1; i < k; ++i) Sk = Sk + p[ord[i]];
+
+    int32_t cstar = k;
+    int took_branch = 0;
+    if (Sk >= eps_high * Z) {
+      for (int32_t i = 0; i < k; ++i) chosen[i] = i;          /* A = top-k */
+    } else {
+      took_branch = 1;
+      int32_t in_pool = 0;
+      for (int32_t i = 0; i < E; ++i) in_pool += (d[i] >= tau_ln);
+      int32_t m = in_pool > k ? in_pool : k;                   /* pool union top-k */
+      cstar = c < m ? c : m;
+      pick_least_loaded(ord, cstar, k, L, chosen);             /* Cand = ord[0..c*) */
+    }
+
+    /* weights: in fp64 from the same logits (the GPU's are checked to tolerance) */
+    double denom = 0.0;
+    if (renormalize) {
+      for (int32_t i = 0; i < k; ++i) denom += exp((double)z[ord[chosen[i]]] - (double)zmax);
+    } else {
+      for (int32_t i = 0; i < E; ++i) denom += exp((double)z[i] - (double)zmax);
+    }
+    for (int32_t i = 0; i < k; ++i) {
+      int32_t e = ord[chosen[i]];
+      expert_ids[(size_t)t * k + i] = e;
+      weights[(size_t)t * k + i] = exp((double)z[e] - (double)zmax) / denom;
+    }
+    for (int32_t i = 0; i < k; ++i) L[ord[chosen[i]]] += 1;    /* load update */
+    if (expanded) expanded[t] = (uint8_t)took_branch;
+    if (cstar_out) cstar_out[t] = cstar;
+  }
+  for (int32_t e = 0; e < E; ++e) loads_out[e] = (int32_t)L[e];
+  build_dispatch(expert_ids, T, k, E, permutation, offsets);
+  return ORACLE_OK;
+}
+
+/* ------------------------------------------------- the router, literal fp64 -- */
+
+/* Same interface on fp64 logits, formulas as printed: s = softmax(z) with libm
+ * exp, M_k = sum of the k largest s, M_k >= eps_high, t = t_fix * s_(1),
+ * pool = {s_i >= t} union top-k, Cand = c* largest, stable sort by load. */
+int laser_oracle_route_literal(const double* logits, int32_t T, int32_t E, int32_t k,
+                               int32_t c, double eps_high, double t_fix,
+                               int32_t renormalize, const int32_t* loads_in,
+                               int32_t* loads_out, int32_t* expert_ids, double* weights,
+                               int32_t* permutation, int32_t* offsets,
+                               uint8_t* expanded, int32_t* cstar_out) {
+  int rc = check_args(T, E, k, c, eps_high, t_fix);
+  if (rc) return rc;
+  int64_t L[256];
+  int32_t ord[256], chosen[256], cand[256];
+  double s[256];
+  for (int32_t e = 0; e < E; ++e) L[e] = loads_in[e];
+
+  for (int32_t t = 0; t < T; ++t) {
+    const double* z = logits + (size_t)t * E;
+    order_desc_f64(z, E, ord);
+    double sum = 0.0;
+    for (int32_t i = 0; i < E; ++i) { s[i] = exp(z[i] - z[ord[0]]); sum += s[i]; }
+    for (int32_t i = 0; i < E; ++i) s[i] /= sum;
+
+    double Mk = 0.0;
+    for (int32_t i = 0; i < k; ++i) Mk += s[ord[i]];
+
+    int32_t cstar = k;
+    int took_branch = 0;
+    if (Mk >= eps_high) {
+      for (int32_t i = 0; i < k; ++i) chosen[i] = i;
+      for (int32_t i = 0; i < k; ++i) cand[i] = ord[i];
+    } else {
+      took_branch = 1;
+      const double cut = t_fix * s[ord[0]];
+      /* pool, kept in score order: members are those with s_i >= cut, plus the
+       * top-k; walk the ordering and keep what qualifies */
+      int32_t m = 0;
+      for (int32_t r = 0; r < E; ++r) {
+        int32_t i = ord[r];
+        if (s[i] >= cut || r < k) cand[m++] = i;
+      }
+      cstar = c < m ? c : m;                                   /* keep c* largest */
+      pick_least_loaded(cand, cstar, k, L, chosen);
+    }
+    double denom = 0.0;
+    if (renormalize) for (int32_t i = 0; i < k; ++i) denom += s[cand[chosen[i]]];
+    else denom = 1.0;
+    for (int32_t i = 0; i < k; ++i) {
+      int32_t e = cand[chosen[i]];
+      expert_ids[(size_t)t * k + i] = e;
+      weights[(size_t)t * k + i] = s[e] / denom;
+    }
+    for (int32_t i = 0; i < k; ++i) L[cand[chosen[i]]] += 1;
+    if (expanded) expanded[t] = (uint8_t)took_branch;
+    if (cstar_out) cstar_out[t] = cstar;
+  }
+  for (int32_t e = 0; e < E; ++e) loads_out[e] = (int32_t)L[e];
+  build_dispatch(expert_ids, T, k, E, permutation, offsets);
+  return ORACLE_OK;
+}

@@ -1,0 +1,367 @@
+"""Pins for the CPU oracle: each checks oracle/ against something the paper or
+the mathematics fixes, never against the oracle's own formula or the GPU path."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from synth import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.json")
+ROUTERS = [("binary32", oracle.route, np.float32), ("literal", oracle.route_literal, np.float64)]
+
+
+def _cases():
+    with open(GOLDEN) as f:
+        return json.load(f)["cases"]
+
+
+# ---------------------------------------------------------------- hand cases --
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c["name"])
+@pytest.mark.parametrize("router", ROUTERS, ids=lambda r: r[0])
+def test_hand_cases(case, router):
+    _, fn, dt = router
+    logits = np.log(np.array(case["p"], dtype=np.float64)).astype(dt)
+    out = fn(logits, case["k"], case["c"], case["eps_high"], case["t_fix"],
+             np.array(case["loads_in"], dtype=np.int32))
+    assert out["expert_ids"].tolist() == case["expert_ids"]
+    assert out["loads"].tolist() == case["loads_out"]
+    assert out["expanded"].tolist() == case["expanded"]
+    assert out["cstar"].tolist() == case["cstar"]
+    np.testing.assert_allclose(out["weights"], np.array(case["weights"]), atol=1e-6)
+
+
+# ------------------------------------------------------ reductions to top-k --
+
+def _numpy_topk(logits, k):
+    order = np.argsort(-logits.astype(np.float64), axis=1, kind="stable")
+    return order[:, :k].astype(np.int32)
+
+
+@pytest.mark.parametrize("E,k", [(8, 2), (64, 6), (5, 1), (16, 16), (256, 8)])
+@pytest.mark.parametrize("how", ["c_equals_k", "eps_small", "t_fix_one"])
+@pytest.mark.parametrize("router", ROUTERS, ids=lambda r: r[0])
+def test_reduces_to_library_topk(E, k, how, router):
+    """c = k, a small eps_high, or t_fix = 1 (distinct scores) all give vanilla
+    top-k routing whatever the loads are (Method, Final assignment; Evaluation:
+    'when c = k the curves coincide')."""
+    _, fn, dt = router
+    T = 300
+    logits = wl.random_logits(11 + E + k, T, E, scale=1.5).astype(dt)
+    loads_in = np.random.default_rng(5).integers(0, 1000, size=E).astype(np.int32)
+    c, eps, tfix = min(E, k + 3), 0.9999, 0.3
+    if how == "c_equals_k":
+        c = k
+    elif how == "eps_small":
+        eps = 1e-6
+    else:
+        tfix = 1.0
+    out = fn(logits, k, c, eps, tfix, loads_in)
+    want = _numpy_topk(logits, k)
+    assert np.array_equal(out["expert_ids"], want)
+    assert np.array_equal(out["loads"], loads_in + np.bincount(want.ravel(), minlength=E))
+    z = logits.astype(np.float64)
+    sm = np.exp(z - z.max(1, keepdims=True))
+    w = np.take_along_axis(sm, want.astype(np.int64), 1)
+    np.testing.assert_allclose(out["weights"], w / w.sum(1, keepdims=True), atol=1e-12)
+
+
+def test_peaked_tokens_keep_topk_whatever_the_loads():
+    """A token whose top-k mass clears eps_high is routed to its top-k even if those
+    experts are the most loaded (Method, Expansion rule)."""
+    E, k, T = 16, 2, 200
+    rng = np.random.default_rng(3)
+    logits = (rng.standard_normal((T, E)) * 0.1).astype(np.float32)
+    hot = rng.integers(0, E, size=(T, 2))
+    hot[:, 1] = (hot[:, 0] + 1 + rng.integers(0, E - 1, size=T)) % E
+    logits[np.arange(T), hot[:, 0]] += 9.0
+    logits[np.arange(T), hot[:, 1]] += 8.0
+    loads_in = np.full(E, 10_000, dtype=np.int32)
+    for _, fn, dt in ROUTERS:
+        out = fn(logits.astype(dt), k, E, 0.9, 0.01, loads_in)
+        assert not out["expanded"].any()
+        assert np.array_equal(out["expert_ids"], hot)
+
+
+# ------------------------------------------------------------- brute force --
+
+def _brute_force_route(z, k, c, eps, tfix, loads_in):
+    """Independent restatement for tiny inputs: softmax with numpy, the pool from
+    the printed set definition, and the final assignment by enumerating every
+    k-subset of the working set and keeping the one whose sorted (load, -score,
+    index) keys are lexicographically least."""
+    T, E = z.shape
+    L = loads_in.astype(np.int64).copy()
+    ids = np.zeros((T, k), dtype=np.int32)
+    for t in range(T):
+        s = np.exp(z[t] - z[t].max())
+        s = s / s.sum()
+        ranked = sorted(range(E), key=lambda i: (-z[t, i], i))
+        topk = ranked[:k]
+        if sum(s[i] for i in topk) >= eps:
+            A = topk
+        else:
+            cut = tfix * s[ranked[0]]
+            pool = sorted(set(i for i in range(E) if s[i] >= cut) | set(topk),
+                          key=lambda i: (-z[t, i], i))
+            work = pool[: min(c, len(pool))]
+            best = None
+            for sub in itertools.combinations(work, k):
+                keys = sorted((L[i], -z[t, i], i) for i in sub)
+                if best is None or keys < best[0]:
+                    best = (keys, sub)
+            A = sorted(best[1], key=lambda i: (-z[t, i], i))
+        ids[t] = A
+        for i in A:
+            L[i] += 1
+    return ids, L
+
+
+def _margin_safe(z, k, eps, tfix, margin=1e-4):
+    """Tokens whose decisions do not hinge on rounding: distinct logits, top-k mass
+    and pool cut both away from their thresholds."""
+    z = z.astype(np.float64)
+    s = np.exp(z - z.max(1, keepdims=True))
+    s /= s.sum(1, keepdims=True)
+    srt = -np.sort(-s, axis=1)
+    ok = np.abs(srt[:, :k].sum(1) - eps) > margin
+    ok &= np.all(np.abs(s / srt[:, :1] - tfix) > margin, axis=1)
+    zs = np.sort(z, axis=1)
+    ok &= np.all(np.diff(zs, axis=1) > 1e-6, axis=1)
+    return ok
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_brute_force_tiny(seed):
+    rng = np.random.default_rng(100 + seed)
+    E = int(rng.integers(2, 9))
+    k = int(rng.integers(1, E + 1))
+    c = int(rng.integers(k, E + 1))
+    eps = float(rng.uniform(0.3, 1.05))
+    tfix = float(rng.uniform(0.05, 1.0))
+    T = 60
+    z = (rng.standard_normal((T, E)) * rng.uniform(0.05, 2.0)).astype(np.float32)
+    z = z[_margin_safe(z, k, eps, tfix)]
+    loads_in = rng.integers(0, 4, size=E).astype(np.int32)
+    want_ids, want_L = _brute_force_route(z.astype(np.float64), k, c, eps, tfix, loads_in)
+    for _, fn, dt in ROUTERS:
+        out = fn(z.astype(dt), k, c, eps, tfix, loads_in)
+        assert np.array_equal(out["expert_ids"], want_ids)
+        assert np.array_equal(out["loads"], want_L)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_brute_force_with_exact_ties(seed):
+    """Equal logits: the lower expert index ranks first everywhere (top-k membership,
+    trimming, and the score tie-break of the load sort)."""
+    rng = np.random.default_rng(200 + seed)
+    E, k, c = 6, 2, 4
+    z = wl.random_logits(300 + seed, 80, E, kind="ties", tie_levels=3, scale=0.5)
+    eps, tfix = 0.999, 0.37
+    loads_in = rng.integers(0, 3, size=E).astype(np.int32)
+    keep = np.ones(len(z), dtype=bool)          # ties are the point: only guard the thresholds
+    s = np.exp(z.astype(np.float64) - z.max(1, keepdims=True))
+    keep &= np.all(np.abs(s / s.max(1, keepdims=True) - tfix) > 1e-4, axis=1)
+    z = z[keep]
+    want_ids, want_L = _brute_force_route(z.astype(np.float64), k, c, eps, tfix, loads_in)
+    for _, fn, dt in ROUTERS:
+        out = fn(z.astype(dt), k, c, eps, tfix, loads_in)
+        assert np.array_equal(out["expert_ids"], want_ids)
+        assert np.array_equal(out["loads"], want_L)
+
+
+# ------------------------------------------------------ load-only closed form --
+
+@pytest.mark.parametrize("E,k,T", [(8, 2, 400), (64, 6, 640), (5, 3, 100)])
+def test_load_only_is_perfectly_balanced(E, k, T):
+    """Ignoring scores (every expert a candidate) gives imbalance 1 / max violation 0
+    (Evaluation, Baselines: 'load-only ... perfect balance')."""
+    logits = wl.random_logits(7, T, E, scale=2.0)
+    for _, fn, dt in ROUTERS:
+        for t_stop in (T, T // 3):
+            out = fn(logits[:t_stop].astype(dt), k, E, 2.0, 1e-30, np.zeros(E, np.int32))
+            assert out["expanded"].all()
+            assert out["loads"].max() - out["loads"].min() <= 1
+            if (t_stop * k) % E == 0:
+                assert np.all(out["loads"] == t_stop * k // E)
+
+
+# -------------------------------------------------------------- invariants ---
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants(seed):
+    rng = np.random.default_rng(400 + seed)
+    E = int(rng.choice([4, 8, 16, 64, 100]))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    c = int(rng.integers(k, min(E, 16) + 1))
+    T = 500
+    z = wl.random_logits(500 + seed, T, E, scale=float(rng.uniform(0.2, 3)))
+    loads_in = rng.integers(0, 50, size=E).astype(np.int32)
+    eps, tfix = float(rng.uniform(0.2, 1.0)), float(rng.uniform(0.1, 1.0))
+    out = oracle.route(z, k, c, eps, tfix, loads_in)
+    ids = out["expert_ids"]
+    assert ids.min() >= 0 and ids.max() < E
+    assert all(len(set(r)) == k for r in ids.tolist())                 # |A| = k distinct
+    np.testing.assert_allclose(out["weights"].sum(1), 1.0, atol=1e-12)  # renormalised
+    assert out["loads"].sum() - loads_in.sum() == T * k                 # loads sum to T*k
+    assert np.array_equal(out["loads"] - loads_in, np.bincount(ids.ravel(), minlength=E))
+    assert np.all(out["cstar"] >= k) and np.all(out["cstar"] <= c)
+    # ids listed by descending score; top-k branch rows equal the library top-k
+    zz = np.take_along_axis(z, ids.astype(np.int64), 1)
+    assert np.all(np.diff(zz, axis=1) <= 0)
+    fixed = out["expanded"] == 0
+    assert np.array_equal(ids[fixed], _numpy_topk(z, k)[fixed])
+    # every chosen expert is among the c highest-scoring ones
+    rank = np.argsort(np.argsort(-z.astype(np.float64), axis=1, kind="stable"), axis=1)
+    assert np.all(np.take_along_axis(rank, ids.astype(np.int64), 1) < out["cstar"][:, None])
+    # non-renormalised weights are the plain softmax scores
+    raw = oracle.route(z, k, c, eps, tfix, loads_in, renormalize=False)
+    sm = np.exp(z.astype(np.float64) - z.max(1, keepdims=True).astype(np.float64))
+    sm /= sm.sum(1, keepdims=True)
+    np.testing.assert_allclose(raw["weights"], np.take_along_axis(sm, ids.astype(np.int64), 1),
+                               atol=1e-12)
+    assert np.array_equal(raw["expert_ids"], ids)
+
+
+def test_separation_chosen_before_unchosen():
+    """Inside the working set every chosen expert sorts before every unchosen one
+    under (load at that moment, score rank)."""
+    E, k, c, T = 8, 2, 5, 300
+    z = wl.random_logits(77, T, E, scale=0.3)
+    out = oracle.route(z, k, c, 2.0, 0.2, np.zeros(E, np.int32))
+    L = np.zeros(E, dtype=np.int64)
+    for t in range(T):
+        ranked = sorted(range(E), key=lambda i: (-float(z[t, i]), i))
+        work = ranked[: out["cstar"][t]]
+        chosen = set(out["expert_ids"][t].tolist())
+        key = {e: (L[e], work.index(e)) for e in work}
+        assert chosen <= set(work)
+        assert max(key[e] for e in chosen) < min([key[e] for e in work if e not in chosen],
+                                                 default=(math.inf, 0))
+        for e in chosen:
+            L[e] += 1
+
+
+def test_split_call_equals_one_call():
+    """Routing tokens [0,a) then [a,T) with the counters carried over equals one call."""
+    E, k, c, T = 64, 6, 8, 700
+    z = wl.random_logits(9, T, E, scale=0.8)
+    L0 = np.arange(E, dtype=np.int32) % 5
+    whole = oracle.route(z, k, c, 0.6, 0.5, L0)
+    a = 233
+    first = oracle.route(z[:a], k, c, 0.6, 0.5, L0)
+    second = oracle.route(z[a:], k, c, 0.6, 0.5, first["loads"])
+    assert np.array_equal(np.vstack([first["expert_ids"], second["expert_ids"]]), whole["expert_ids"])
+    assert np.array_equal(second["loads"], whole["loads"])
+
+
+def test_adjacent_tokens_with_disjoint_working_sets_commute():
+    E, k, c = 8, 2, 3
+    za = np.array([[5, 4.9, 4.8, 0, 0, 0, 0, 0]], dtype=np.float32)
+    zb = np.array([[0, 0, 0, 0, 0, 4.8, 4.9, 5]], dtype=np.float32)
+    L0 = np.array([2, 0, 1, 0, 0, 1, 0, 2], dtype=np.int32)
+    ab = oracle.route(np.vstack([za, zb]), k, c, 0.99, 0.5, L0)
+    ba = oracle.route(np.vstack([zb, za]), k, c, 0.99, 0.5, L0)
+    assert np.array_equal(ab["loads"], ba["loads"])
+    assert np.array_equal(ab["expert_ids"][0], ba["expert_ids"][1])
+    assert ab["expert_ids"][0].tolist() == [1, 2]      # lighter experts of {0,1,2}
+
+
+# ----------------------------------------------------------------- dispatch --
+
+@pytest.mark.parametrize("E,k,T", [(8, 2, 1000), (64, 6, 777), (3, 1, 1), (4, 2, 0)])
+def test_dispatch_is_the_stable_counting_sort(E, k, T):
+    z = wl.random_logits(21, T, E)
+    out = oracle.route(z, k, min(E, k + 2), 0.7, 0.5, np.zeros(E, np.int32))
+    flat = out["expert_ids"].ravel()
+    assert np.array_equal(out["permutation"], np.argsort(flat, kind="stable").astype(np.int32))
+    counts = np.bincount(flat, minlength=E)
+    assert np.array_equal(out["expert_offsets"], np.concatenate([[0], np.cumsum(counts)]))
+    assert out["expert_offsets"][E] == T * k
+
+
+# --------------------------------------------------------------------- gate --
+
+@pytest.mark.parametrize("dtype", [wl.DTYPE_F32, wl.DTYPE_BF16])
+def test_gate_matches_numpy_fp64_matmul(dtype):
+    rng = np.random.default_rng(31)
+    hidden, w = wl.make_gate(rng, 37, 200, 11, dtype, bias=np.linspace(-2, 2, 11))
+    z = oracle.gate(hidden, w, dtype)
+    if dtype == wl.DTYPE_BF16:
+        h64, w64 = wl.bf16_bits_to_f32(hidden).astype(np.float64), wl.bf16_bits_to_f32(w).astype(np.float64)
+    else:
+        h64, w64 = hidden.astype(np.float64), w.astype(np.float64)
+    np.testing.assert_allclose(z, h64 @ w64.T, rtol=0, atol=1e-12)
+    # orientation: expert e uses row e of W (a transposed operand would fail here)
+    assert abs(z[3, 5] - float(h64[3] @ w64[5])) < 1e-12
+
+
+def test_gate_bias_recipe_places_the_bias():
+    """The generator's pinv construction really lands the requested bias on the logits."""
+    rng = np.random.default_rng(32)
+    bias = np.array([3.0, 0, 0, -2.0, 0, 0, 0, 0])
+    hidden, w = wl.make_gate(rng, 4000, 256, 8, wl.DTYPE_F32, bias=bias)
+    z = oracle.gate(hidden, w, wl.DTYPE_F32)
+    np.testing.assert_allclose(z.mean(0), bias, atol=0.03)
+
+
+# ------------------------------------------------- binary32 building blocks --
+
+def test_exp_canon_against_libm():
+    xs = np.concatenate([np.linspace(-80, 0, 4001), -np.logspace(-8, 1.9, 500)]).astype(np.float32)
+    got = np.array([oracle.exp_canon(x) for x in xs], dtype=np.float64)
+    want = np.exp(xs.astype(np.float64))
+    assert np.max(np.abs(got / want - 1.0)) < 2.5e-7
+    assert oracle.exp_canon(0.0) == 1.0
+    assert oracle.exp_canon(-80.0) > 0.0
+    # monotone on a fine grid near 0 (ordering of scores follows ordering of logits)
+    fine = -np.arange(0, 2000, dtype=np.float32) * np.float32(1e-4)
+    vals = [oracle.exp_canon(x) for x in fine]
+    assert all(a >= b for a, b in zip(vals, vals[1:]))
+
+
+def test_tree_sum_shape():
+    # integers: any order gives the exact sum
+    v = np.arange(1, 12, dtype=np.float32)
+    assert oracle.tree_sum(v) == 66.0
+    # the stated tree for 4 values is (v0+v2)+(v1+v3); these values tell it apart
+    # from left-to-right and from (v0+v1)+(v2+v3)
+    v = np.array([1.0, 2.0 ** -24, 2.0 ** -24, 2.0 ** -24], dtype=np.float32)
+    f = np.float32
+    assert oracle.tree_sum(v) == float((f(v[0]) + f(v[2])) + (f(v[1]) + f(v[3])))
+    w = np.array([2.0 ** 24, 1.0, -(2.0 ** 24), 1.0], dtype=np.float32)
+    assert oracle.tree_sum(w) == 2.0          # (w0+w2)+(w1+w3); left-to-right gives 1
+    # padding with zeros does not change the result
+    assert oracle.tree_sum(np.concatenate([w, np.zeros(3, np.float32)])) == oracle.tree_sum(
+        np.concatenate([w, np.zeros(4, np.float32)]))
+
+
+@pytest.mark.parametrize("shape", ["mixtral", "deepseek"])
+def test_binary32_reading_agrees_with_literal_fp64(shape):
+    """On tokens whose thresholds are not within rounding distance, the binary32
+    decision arithmetic and the paper's formulas in fp64 route identically."""
+    s = wl.SHAPES[shape]
+    z = wl.random_logits(55, 3000, s.E, scale=0.9)
+    for layer in (0, s.layers // 2):
+        eps, tfix = wl.thresholds(shape, layer)
+        ok = _margin_safe(z, s.k, eps, tfix, margin=1e-5)
+        a = oracle.route(z[ok], s.k, s.c, eps, tfix, np.zeros(s.E, np.int32))
+        b = oracle.route_literal(z[ok].astype(np.float64), s.k, s.c, eps, tfix, np.zeros(s.E, np.int32))
+        for key in ("expert_ids", "loads", "expanded", "cstar", "permutation", "expert_offsets"):
+            assert np.array_equal(a[key], b[key]), key
+        np.testing.assert_allclose(a["weights"], b["weights"], atol=1e-12)
+        assert 0 < a["expanded"].mean() < 1          # both branches exercised
+
+
+def test_argument_errors():
+    z = np.zeros((2, 4), dtype=np.float32)
+    L = np.zeros(4, np.int32)
+    for k, c, eps, tfix in [(0, 2, .5, .5), (3, 2, .5, .5), (2, 5, .5, .5), (2, 3, 0.0, .5),
+                            (2, 3, .5, 0.0), (2, 3, .5, 1.5)]:
+        with pytest.raises(ValueError):
+            oracle.route(z, k, c, eps, tfix, L)
