@@ -1,0 +1,128 @@
+/*
+ * laser.h -- C ABI of the MI355X (gfx950) LASER routing library.
+ *
+ * One call routes the T tokens of one MoE layer: gate projection of the hidden
+ * states to expert logits, softmax scores, the top-k-mass test that either keeps
+ * the k strongest experts or widens to a thresholded candidate set, selection of
+ * the k least-loaded candidates against running per-expert load counters that
+ * advance after every token, and the token-to-expert dispatch tables.
+ * (Paper: section "The Method" -- Problem Formulation, Expansion rule, Final
+ * assignment; appendix "Pseudo Code", Algorithm 1 "per token, per layer".)
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless marked host.  The caller
+ *     allocates and owns all buffers, including the workspace.  The library
+ *     allocates nothing, frees nothing, never synchronises and never prints:
+ *     all work is enqueued on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and the call returns at once.
+ *   - Return value: LASER_OK (0) or a negative LASER_E_* code.  Arguments are
+ *     validated on the host before anything is enqueued; on error nothing was
+ *     enqueued and no buffer was touched.  laser_strerror() names a code.
+ *   - Tokens are routed in row order 0..T-1; the load counters a token sees are
+ *     loads_inout as passed in plus one per expert for every earlier token that
+ *     was assigned to it (both branches of the expansion rule count).
+ *   - Scores are ordered by logit, equal logits by lower expert index first.
+ *     That one order decides top-k membership, trimming to c, the score tie-break
+ *     of the load sort, and the order in which a token's k experts are listed.
+ *   - Inputs must be finite; loads_inout[e] + T must stay below 2^27.
+ *   - Limits: 1 <= k <= c <= min(E, 16); E <= 64; bf16 needs H % 8 == 0 and
+ *     16-byte aligned hidden / w_gate; fp32 needs H % 4 == 0.
+ */
+#ifndef LASER_H_
+#define LASER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LASER_OK 0
+#define LASER_E_NULL (-1)        /* a required pointer is NULL                    */
+#define LASER_E_RANGE (-2)       /* T, H, E, k, c, eps_high or t_fix out of range */
+#define LASER_E_ALIGN (-3)       /* row length or pointer alignment not supported */
+#define LASER_E_WORKSPACE (-4)   /* workspace smaller than laser_workspace_bytes  */
+#define LASER_E_UNSUPPORTED (-5) /* E or c above the built limit, RANDOM trimming */
+#define LASER_E_STRUCT (-6)      /* params->struct_bytes does not match           */
+#define LASER_E_LAUNCH (-7)      /* the HIP runtime refused a kernel launch       */
+
+#define LASER_DTYPE_F32 0
+#define LASER_DTYPE_BF16 1
+
+#define LASER_TRIM_TOP 0    /* keep the c highest-scoring pool members (built)       */
+#define LASER_TRIM_RANDOM 1 /* uniform sample of the pool: returns E_UNSUPPORTED     */
+
+#define LASER_MAX_E 64
+#define LASER_MAX_C 16
+
+/* Parameters of Algorithm 1 plus the storage type of the gate operands. */
+typedef struct laser_params {
+  uint32_t struct_bytes; /* = sizeof(laser_params_t)                                */
+  int32_t k;             /* experts per token                                       */
+  int32_t c;             /* trimming size, k <= c <= E                              */
+  float eps_high;        /* top-k mass threshold; > 0.  The paper uses (0,1); a     */
+                         /* value above 1 sends every token to the load-aware branch */
+  float t_fix;           /* pool cut-off relative to the best score, in (0, 1]      */
+  int32_t trim_mode;     /* LASER_TRIM_*                                            */
+  int32_t renormalize;   /* 1: weights sum to 1 over the k chosen; 0: raw scores    */
+  int32_t dtype;         /* LASER_DTYPE_* of hidden and w_gate (laser_route only)   */
+} laser_params_t;
+
+/* Bytes of device workspace a call with these sizes needs (0 on bad arguments).
+ * H may be 0 when only laser_route_from_logits will be called. */
+size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params_t* params);
+
+/*
+ * The whole routing step of one layer (gate function + Algorithm 1 per token in
+ * token order + dispatch tables).
+ *   hidden         [T,H] row-major, dtype per params           in
+ *   w_gate         [E,H] row-major (one row per expert)        in
+ *   loads_inout    [E] int32: loads before token 0 / after token T-1
+ *   expert_ids     [T,k] int32: the chosen experts, best score first      out
+ *   weights        [T,k] fp32: combine weights of those experts           out
+ *   permutation    [T*k] int32: flat assignment slots t*k+j grouped by    out
+ *                  expert, ascending slot order inside an expert (the stable
+ *                  counting sort of expert_ids)
+ *   expert_offsets [E+1] int32: exclusive prefix sums of the per-expert   out
+ *                  assignment counts; [E] = T*k
+ *   logits_out     [T,E] fp32 gate logits, or NULL if not wanted          out
+ *   workspace      >= laser_workspace_bytes(T,H,E,params) bytes, 256-byte aligned
+ * T = 0 is valid (offsets are zeroed, loads untouched).
+ */
+int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                float* weights, int32_t* permutation, int32_t* expert_offsets,
+                float* logits_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream);
+
+/*
+ * The same step starting after the gate function, from given fp32 logits [T,E]
+ * (Algorithm 1's input is the score vector; scores are softmax(logits)).
+ * params->dtype is ignored.
+ */
+int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
+                            const laser_params_t* params, int32_t* loads_inout,
+                            int32_t* expert_ids, float* weights, int32_t* permutation,
+                            int32_t* expert_offsets, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
+
+/* Static, NUL-terminated description of a return code (host pointer). */
+const char* laser_strerror(int code);
+
+/*
+ * Stage timing for benchmarks.  While enabled, laser_route brackets its gate
+ * kernel with HIP events on the caller's stream (events come from a pool created
+ * by laser_profile_enable; at most `max_calls` calls are recorded, later ones
+ * are not bracketed).  laser_profile_read synchronises on the recorded events
+ * and returns the summed gate-kernel time in milliseconds and the number of
+ * launches it covers (both host pointers), then clears the record.
+ * laser_profile_enable(0) turns it off and destroys the pool.  Not thread-safe.
+ */
+int laser_profile_enable(int32_t max_calls);
+int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASER_H_ */

@@ -1,0 +1,165 @@
+"""Thin ctypes binding of liblaser_route.so (the C ABI in include/laser.h).
+
+Argument marshalling only: torch supplies device memory and the stream; every
+step of the routing path runs in the library's HIP kernels.  There is no CPU
+fallback: if the library has not been built, importing the binding raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblaser_route.so")
+
+DTYPE_F32 = 0
+DTYPE_BF16 = 1
+TRIM_TOP = 0
+TRIM_RANDOM = 1
+
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_from_logits",
+           "laser_strerror", "laser_profile_enable", "laser_profile_read")
+
+
+class LaserParams(ctypes.Structure):
+    _fields_ = [
+        ("struct_bytes", ctypes.c_uint32),
+        ("k", ctypes.c_int32),
+        ("c", ctypes.c_int32),
+        ("eps_high", ctypes.c_float),
+        ("t_fix", ctypes.c_float),
+        ("trim_mode", ctypes.c_int32),
+        ("renormalize", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
+class LaserError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"laser: {text} (code {code})")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2510_03293_amd.build "
+            "or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    pp = ctypes.POINTER(LaserParams)
+    lib.laser_workspace_bytes.argtypes = [i32, i32, i32, pp]
+    lib.laser_workspace_bytes.restype = sz
+    lib.laser_route.argtypes = [vp, vp, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.laser_route.restype = ctypes.c_int
+    lib.laser_route_from_logits.argtypes = [vp, i32, i32, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.laser_route_from_logits.restype = ctypes.c_int
+    lib.laser_strerror.argtypes = [ctypes.c_int]
+    lib.laser_strerror.restype = ctypes.c_char_p
+    lib.laser_profile_enable.argtypes = [i32]
+    lib.laser_profile_enable.restype = ctypes.c_int
+    lib.laser_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.laser_profile_read.restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def make_params(k: int, c: int, eps_high: float, t_fix: float, dtype: int = DTYPE_BF16,
+                renormalize: bool = True, trim_mode: int = TRIM_TOP) -> LaserParams:
+    return LaserParams(ctypes.sizeof(LaserParams), k, c, eps_high, t_fix, trim_mode,
+                       1 if renormalize else 0, dtype)
+
+
+def laser_strerror(code: int) -> str:
+    return _lib.laser_strerror(code).decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise LaserError(code, laser_strerror(code))
+
+
+def laser_workspace_bytes(T: int, H: int, E: int, params: LaserParams) -> int:
+    return int(_lib.laser_workspace_bytes(T, H, E, ctypes.byref(params)))
+
+
+def _ptr(t: torch.Tensor | None):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def laser_route(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights,
+                permutation, expert_offsets, logits_out, workspace, stream=None) -> None:
+    """Enqueue one layer's routing step; tensors are device tensors (see laser.h)."""
+    _check(_lib.laser_route(_ptr(hidden), _ptr(w_gate), T, H, E, ctypes.byref(params),
+                            _ptr(loads_inout), _ptr(expert_ids), _ptr(weights), _ptr(permutation),
+                            _ptr(expert_offsets), _ptr(logits_out), _ptr(workspace),
+                            workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def laser_route_from_logits(logits, T, E, params, loads_inout, expert_ids, weights,
+                            permutation, expert_offsets, workspace, stream=None) -> None:
+    _check(_lib.laser_route_from_logits(_ptr(logits), T, E, ctypes.byref(params),
+                                        _ptr(loads_inout), _ptr(expert_ids), _ptr(weights),
+                                        _ptr(permutation), _ptr(expert_offsets), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(),
+                                        _stream_handle(stream)))
+
+
+def laser_profile_enable(max_calls: int) -> None:
+    _check(_lib.laser_profile_enable(max_calls))
+
+
+def laser_profile_read() -> tuple[float, int]:
+    ms = ctypes.c_double(0.0)
+    n = ctypes.c_int64(0)
+    _check(_lib.laser_profile_read(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
+
+
+class RouteBuffers:
+    """Output and workspace tensors for calls of one size, allocated once."""
+
+    def __init__(self, T: int, H: int, E: int, params: LaserParams, device="cuda",
+                 want_logits: bool = False):
+        self.T, self.H, self.E, self.k = T, H, E, params.k
+        nbytes = laser_workspace_bytes(T, H, E, params)
+        if nbytes == 0:
+            raise LaserError(-2, "laser_workspace_bytes rejected the arguments")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.expert_ids = torch.empty((T, params.k), dtype=torch.int32, device=device)
+        self.weights = torch.empty((T, params.k), dtype=torch.float32, device=device)
+        self.permutation = torch.empty(T * params.k, dtype=torch.int32, device=device)
+        self.expert_offsets = torch.empty(E + 1, dtype=torch.int32, device=device)
+        self.logits = torch.empty((T, E), dtype=torch.float32, device=device) if want_logits else None
+
+
+def route(hidden, w_gate, params: LaserParams, loads_inout, buffers: RouteBuffers | None = None,
+          want_logits: bool = False, stream=None) -> RouteBuffers:
+    """Convenience wrapper: shapes from the tensors, buffers allocated if not given."""
+    T, H = hidden.shape
+    E = w_gate.shape[0]
+    if buffers is None:
+        buffers = RouteBuffers(T, H, E, params, device=hidden.device, want_logits=want_logits)
+    laser_route(hidden, w_gate, T, H, E, params, loads_inout, buffers.expert_ids, buffers.weights,
+                buffers.permutation, buffers.expert_offsets, buffers.logits, buffers.workspace,
+                stream)
+    return buffers
+
+
+def route_from_logits(logits, params: LaserParams, loads_inout,
+                      buffers: RouteBuffers | None = None, stream=None) -> RouteBuffers:
+    T, E = logits.shape
+    if buffers is None:
+        buffers = RouteBuffers(T, 0, E, params, device=logits.device)
+    laser_route_from_logits(logits, T, E, params, loads_inout, buffers.expert_ids, buffers.weights,
+                            buffers.permutation, buffers.expert_offsets, buffers.workspace, stream)
+    return buffers

@@ -1,0 +1,215 @@
+// C ABI of the routing library: argument validation, workspace layout and the
+// launch sequence.  Declarations and their contracts are in include/laser.h.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/laser.h"
+#include "laser_internal.h"
+
+namespace laser {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_out,
+      total;
+};
+
+static Layout layout(int T, int E, bool need_logits) {
+  Layout L;
+  const size_t ntiles = ((size_t)T + kTile - 1) / kTile;
+  const size_t slots = ntiles * kTile;
+  const size_t EP = (size_t)padded_experts(E);
+  size_t off = 0;
+  L.logits = off;     off += align_up(need_logits ? (size_t)T * E * 4 : 0);
+  L.rec_cstar = off;  off += align_up((size_t)T);
+  L.rec_ids = off;    off += align_up((size_t)T * 16);
+  L.rec_p = off;      off += align_up((size_t)T * 16 * 4);
+  L.rec_Z = off;      off += align_up((size_t)T * 4);
+  L.rec_lane = off;   off += align_up(slots * EP * 2);
+  L.flexmask = off;   off += align_up(ntiles * 8);
+  L.fixed_cnt = off;  off += align_up(ntiles * 64 * 4);
+  L.base = off;       off += align_up(ntiles * 64 * 4);
+  L.chain_out = off;  off += align_up(slots * 8);
+  L.total = off + 256;
+  return L;
+}
+
+size_t workspace_bytes(int T, int E, bool need_logits) { return layout(T, E, need_logits).total; }
+
+Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
+  const Layout L = layout(T, E, need_logits);
+  char* b = static_cast<char*>(base);
+  Workspace w;
+  w.logits = reinterpret_cast<float*>(b + L.logits);
+  w.rec_cstar = reinterpret_cast<uint8_t*>(b + L.rec_cstar);
+  w.rec_ids = reinterpret_cast<uint8_t*>(b + L.rec_ids);
+  w.rec_p = reinterpret_cast<float*>(b + L.rec_p);
+  w.rec_Z = reinterpret_cast<float*>(b + L.rec_Z);
+  w.rec_lane = reinterpret_cast<uint16_t*>(b + L.rec_lane);
+  w.flexmask = reinterpret_cast<unsigned long long*>(b + L.flexmask);
+  w.tile_fixed_cnt = reinterpret_cast<int32_t*>(b + L.fixed_cnt);
+  w.tile_base = reinterpret_cast<int32_t*>(b + L.base);
+  w.chain_out = reinterpret_cast<unsigned long long*>(b + L.chain_out);
+  return w;
+}
+
+// ------------------------------------------------------- stage timing pool ----
+struct Profile {
+  std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after the gate kernel
+  int used = 0;                // pairs recorded
+};
+static Profile g_profile;
+
+static int check_params(int32_t T, int32_t E, const laser_params_t* p) {
+  if (!p) return LASER_E_NULL;
+  if (p->struct_bytes != sizeof(laser_params_t)) return LASER_E_STRUCT;
+  if (T < 0 || E < 1) return LASER_E_RANGE;
+  if (p->k < 1 || p->c < p->k || p->c > E) return LASER_E_RANGE;
+  if (!(p->eps_high > 0.0f) || !(p->t_fix > 0.0f) || !(p->t_fix <= 1.0f)) return LASER_E_RANGE;
+  if ((int64_t)T * p->k > 0x7fffffffLL) return LASER_E_RANGE;
+  if (p->trim_mode != LASER_TRIM_TOP) return LASER_E_UNSUPPORTED;
+  if (E > LASER_MAX_E || p->c > LASER_MAX_C) return LASER_E_UNSUPPORTED;
+  return LASER_OK;
+}
+
+static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
+  RouteArgs a;
+  a.T = T;
+  a.E = E;
+  a.EP = padded_experts(E);
+  a.k = p->k;
+  a.c = p->c;
+  a.ntiles = (T + kTile - 1) / kTile;
+  a.renormalize = p->renormalize ? 1 : 0;
+  a.eps_high = p->eps_high;
+  a.tau_ln = (float)log((double)p->t_fix);
+  return a;
+}
+
+static int route_tail(const float* logits, const RouteArgs& a, const Workspace& ws,
+                      int32_t* loads_inout, int32_t* expert_ids, float* weights,
+                      int32_t* permutation, int32_t* expert_offsets, hipStream_t s) {
+  if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+  if (launch_chain(a, ws, loads_inout, expert_offsets, s) != hipSuccess) return LASER_E_LAUNCH;
+  if (launch_finish(a, ws, expert_offsets, expert_ids, weights, permutation, s) != hipSuccess)
+    return LASER_E_LAUNCH;
+  return LASER_OK;
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" {
+
+size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params_t* params) {
+  if (check_params(T, E, params) != LASER_OK || H < 0) return 0;
+  return workspace_bytes(T, E, true);
+}
+
+int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                float* weights, int32_t* permutation, int32_t* expert_offsets,
+                float* logits_out, void* workspace, size_t workspace_bytes_given,
+                void* hip_stream) {
+  int rc = check_params(T, E, params);
+  if (rc != LASER_OK) return rc;
+  if (!w_gate || !loads_inout || !expert_offsets || !workspace) return LASER_E_NULL;
+  if (T > 0 && (!hidden || !expert_ids || !weights || !permutation)) return LASER_E_NULL;
+  if (H < 1) return LASER_E_RANGE;
+  if (params->dtype != LASER_DTYPE_F32 && params->dtype != LASER_DTYPE_BF16) return LASER_E_RANGE;
+  if (params->dtype == LASER_DTYPE_BF16) {
+    if (H % 8 != 0 || ((uintptr_t)hidden & 15) || ((uintptr_t)w_gate & 15)) return LASER_E_ALIGN;
+  } else {
+    if (H % 4 != 0 || ((uintptr_t)hidden & 15) || ((uintptr_t)w_gate & 15)) return LASER_E_ALIGN;
+  }
+  if ((uintptr_t)workspace & 255) return LASER_E_ALIGN;
+  const bool need_logits = true;  // the layout always reserves the logits block
+  if (workspace_bytes_given < workspace_bytes(T, E, need_logits)) return LASER_E_WORKSPACE;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const RouteArgs a = make_args(T, E, params);
+  const Workspace ws = carve_workspace(workspace, T, E, need_logits);
+  float* logits = logits_out ? logits_out : ws.logits;
+
+  const bool timed = !g_profile.ev.empty() && (size_t)(2 * g_profile.used + 1) < g_profile.ev.size() && T > 0;
+  if (timed && hipEventRecord(g_profile.ev[2 * g_profile.used], s) != hipSuccess) return LASER_E_LAUNCH;
+  hipError_t he = params->dtype == LASER_DTYPE_BF16
+                      ? launch_gate_bf16(hidden, w_gate, T, H, E, logits, s)
+                      : launch_gate_f32(static_cast<const float*>(hidden),
+                                        static_cast<const float*>(w_gate), T, H, E, logits, s);
+  if (he != hipSuccess) return LASER_E_LAUNCH;
+  if (timed) {
+    if (hipEventRecord(g_profile.ev[2 * g_profile.used + 1], s) != hipSuccess) return LASER_E_LAUNCH;
+    ++g_profile.used;
+  }
+  return route_tail(logits, a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
+}
+
+int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
+                            const laser_params_t* params, int32_t* loads_inout,
+                            int32_t* expert_ids, float* weights, int32_t* permutation,
+                            int32_t* expert_offsets, void* workspace,
+                            size_t workspace_bytes_given, void* hip_stream) {
+  int rc = check_params(T, E, params);
+  if (rc != LASER_OK) return rc;
+  if (!loads_inout || !expert_offsets || !workspace) return LASER_E_NULL;
+  if (T > 0 && (!logits || !expert_ids || !weights || !permutation)) return LASER_E_NULL;
+  if ((uintptr_t)workspace & 255) return LASER_E_ALIGN;
+  if (workspace_bytes_given < workspace_bytes(T, E, true)) return LASER_E_WORKSPACE;
+  const RouteArgs a = make_args(T, E, params);
+  const Workspace ws = carve_workspace(workspace, T, E, true);
+  return route_tail(logits, a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets,
+                    static_cast<hipStream_t>(hip_stream));
+}
+
+const char* laser_strerror(int code) {
+  switch (code) {
+    case LASER_OK: return "ok";
+    case LASER_E_NULL: return "a required pointer is NULL";
+    case LASER_E_RANGE: return "argument out of range (T, H, E, k, c, eps_high, t_fix or dtype)";
+    case LASER_E_ALIGN: return "unsupported row length or pointer alignment";
+    case LASER_E_WORKSPACE: return "workspace too small";
+    case LASER_E_UNSUPPORTED: return "not built: E > 64, c > 16, or RANDOM trimming";
+    case LASER_E_STRUCT: return "laser_params_t.struct_bytes mismatch";
+    case LASER_E_LAUNCH: return "HIP kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int laser_profile_enable(int32_t max_calls) {
+  for (hipEvent_t e : g_profile.ev) (void)hipEventDestroy(e);
+  g_profile.ev.clear();
+  g_profile.used = 0;
+  if (max_calls <= 0) return LASER_OK;
+  g_profile.ev.resize((size_t)max_calls * 2);
+  for (size_t i = 0; i < g_profile.ev.size(); ++i) {
+    if (hipEventCreate(&g_profile.ev[i]) != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_profile.ev[j]);
+      g_profile.ev.clear();
+      return LASER_E_LAUNCH;
+    }
+  }
+  return LASER_OK;
+}
+
+int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches) {
+  if (!gate_ms_sum || !gate_launches) return LASER_E_NULL;
+  double sum = 0.0;
+  for (int i = 0; i < g_profile.used; ++i) {
+    if (hipEventSynchronize(g_profile.ev[2 * i + 1]) != hipSuccess) return LASER_E_LAUNCH;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, g_profile.ev[2 * i], g_profile.ev[2 * i + 1]) != hipSuccess)
+      return LASER_E_LAUNCH;
+    sum += ms;
+  }
+  *gate_ms_sum = sum;
+  *gate_launches = g_profile.used;
+  g_profile.used = 0;
+  return LASER_OK;
+}
+
+}  // extern "C"

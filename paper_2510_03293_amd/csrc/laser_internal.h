@@ -1,0 +1,63 @@
+// Internal declarations shared by the HIP translation units of the routing
+// library: workspace layout, per-call parameters, kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace laser {
+
+constexpr int kTile = 64;        // tokens per tile (one wave-wide bit mask per tile)
+constexpr int kMaxE = 64;        // experts: one lane of a wavefront per expert
+constexpr int kMaxC = 16;        // trimming size limit (candidate ranks fit 4 bits)
+
+// Per-call scalars handed to every kernel by value.
+struct RouteArgs {
+  int T;            // tokens
+  int E;            // experts
+  int EP;           // experts padded to 8/16/32/64 (4 lanes per token x EP/4 each)
+  int k;            // experts per token
+  int c;            // trimming size
+  int ntiles;       // ceil(T / kTile)
+  int renormalize;  // weights over the chosen k (1) or raw softmax scores (0)
+  float eps_high;   // top-k mass threshold
+  float tau_ln;     // fl32(ln t_fix): pool cut-off in the logit domain
+};
+
+// Device workspace carved out of the caller's buffer.  Records are written by
+// the per-token analysis, consumed by the load-ordered chain and the finishing
+// pass.  "slot" = tile * kTile + (rank of the token among its tile's flexible
+// tokens), so a tile's flexible records are contiguous.
+struct Workspace {
+  float* logits;               // [T,E]   gate logits (unless the caller gave a buffer)
+  uint8_t* rec_cstar;          // [T]     working-set size of a flexible token, else 0
+  uint8_t* rec_ids;            // [T,16]  experts by descending score
+  float* rec_p;                // [T,16]  their softmax numerators exp(z - z_max)
+  float* rec_Z;                // [T]     softmax normaliser
+  uint16_t* rec_lane;          // [slot,EP] per expert: (fixed-prefix << 4 | rank) or 0xFFFF
+  unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
+  int32_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens
+  int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
+  unsigned long long* chain_out;   // [slot] chosen-expert bit mask of a flexible token
+};
+
+size_t workspace_bytes(int T, int E, bool need_logits);
+Workspace carve_workspace(void* base, int T, int E, bool need_logits);
+
+inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
+
+// Launchers (enqueue only; return the HIP error of the launch).
+hipError_t launch_gate_bf16(const void* hidden, const void* w, int T, int H, int E,
+                            float* logits, hipStream_t s);
+hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E,
+                           float* logits, hipStream_t s);
+hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
+                          int32_t* expert_ids, float* weights, hipStream_t s);
+hipError_t launch_chain(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                        int32_t* expert_offsets, hipStream_t s);
+hipError_t launch_finish(const RouteArgs& a, const Workspace& ws, const int32_t* expert_offsets,
+                         int32_t* expert_ids, float* weights, int32_t* permutation,
+                         hipStream_t s);
+
+}  // namespace laser

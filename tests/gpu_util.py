@@ -1,0 +1,93 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI binding and
+compare with the CPU oracle on the same seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2510_03293_amd import binding as B
+from synth import workloads as wl
+
+TOL_LOGIT = {wl.DTYPE_BF16: 2e-3, wl.DTYPE_F32: 1e-5}   # max abs error, logits and weights
+
+
+def to_device(arr: np.ndarray, dtype: int | None = None) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(arr))
+    if arr.dtype == np.uint16:
+        t = torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).view(torch.bfloat16)
+    return t.cuda()
+
+
+def run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True):
+    """GPU laser_route on numpy inputs; returns a dict of numpy outputs incl. logits."""
+    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, renormalize=renormalize)
+    hd, wd = to_device(hidden), to_device(w_gate)
+    loads = torch.from_numpy(np.ascontiguousarray(loads_in, dtype=np.int32)).cuda()
+    buf = B.route(hd, wd, params, loads, want_logits=True)
+    torch.cuda.synchronize()
+    return _collect(buf, loads, buf.logits)
+
+
+def run_route_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
+    params = B.make_params(k, c, eps_high, t_fix, renormalize=renormalize)
+    ld = torch.from_numpy(np.ascontiguousarray(logits, dtype=np.float32)).cuda()
+    loads = torch.from_numpy(np.ascontiguousarray(loads_in, dtype=np.int32)).cuda()
+    buf = B.route_from_logits(ld, params, loads)
+    torch.cuda.synchronize()
+    return _collect(buf, loads, None)
+
+
+def _collect(buf, loads, logits):
+    out = {
+        "expert_ids": buf.expert_ids.cpu().numpy(),
+        "weights": buf.weights.cpu().numpy(),
+        "permutation": buf.permutation.cpu().numpy(),
+        "expert_offsets": buf.expert_offsets.cpu().numpy(),
+        "loads": loads.cpu().numpy(),
+    }
+    if logits is not None:
+        out["logits"] = logits.cpu().numpy()
+    return out
+
+
+def assert_discrete_equal(gpu: dict, ref: dict, label: str = ""):
+    """Bit-exact comparison of every integer output."""
+    for key in ("expert_ids", "loads", "expert_offsets", "permutation"):
+        a, b = gpu[key], ref[key]
+        if not np.array_equal(a, b):
+            bad = np.argwhere(a != b)
+            raise AssertionError(f"{label}: {key} differs at {len(bad)} places, first {bad[0].tolist()}: "
+                                 f"gpu {a[tuple(bad[0])]} oracle {b[tuple(bad[0])]}")
+
+
+def check_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize=True, tol=1e-5,
+                      label=""):
+    gpu = run_route_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize)
+    ref = oracle.route(logits, k, c, eps_high, t_fix, loads_in, renormalize)
+    assert_discrete_equal(gpu, ref, label)
+    if gpu["weights"].size:
+        err = np.abs(gpu["weights"].astype(np.float64) - ref["weights"]).max()
+        assert err <= tol, f"{label}: weights max abs err {err}"
+    return gpu, ref
+
+
+def check_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True,
+                label="", logit_rows=None):
+    """Full path.  Logits against the fp64 gate (all rows, or a sample of rows);
+    discrete outputs against the oracle routed on the GPU's own fp32 logits."""
+    gpu = run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize)
+    tol = TOL_LOGIT[dtype]
+    if logit_rows is None:
+        z = oracle.gate(hidden, w_gate, dtype)
+        err = np.abs(gpu["logits"].astype(np.float64) - z).max() if z.size else 0.0
+    else:
+        z = oracle.gate(hidden[logit_rows], w_gate, dtype)
+        err = np.abs(gpu["logits"][logit_rows].astype(np.float64) - z).max()
+    assert err <= tol, f"{label}: logits max abs err {err} > {tol}"
+    ref = oracle.route(gpu["logits"], k, c, eps_high, t_fix, loads_in, renormalize)
+    assert_discrete_equal(gpu, ref, label)
+    if gpu["weights"].size:
+        werr = np.abs(gpu["weights"].astype(np.float64) - ref["weights"]).max()
+        assert werr <= tol, f"{label}: weights max abs err {werr} > {tol}"
+    return gpu, ref

@@ -1,0 +1,85 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "laser.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2510_03293_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(laser_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_and_struct_size(B):
+    assert B.laser_strerror(0) == "ok"
+    assert "NULL" in B.laser_strerror(-1)
+    assert ctypes.sizeof(B.LaserParams) == 32
+
+
+def test_workspace_query(B):
+    p = B.make_params(6, 8, 0.4, 0.8)
+    small = B.laser_workspace_bytes(64, 2048, 64, p)
+    big = B.laser_workspace_bytes(16384, 2048, 64, p)
+    assert 0 < small < big < 64 << 20
+    assert B.laser_workspace_bytes(0, 2048, 64, p) > 0
+    assert B.laser_workspace_bytes(-1, 2048, 64, p) == 0
+    assert B.laser_workspace_bytes(64, 2048, 65, p) == 0          # E above the limit
+
+
+def test_argument_errors_before_any_device_work(B):
+    """Fake non-null addresses are safe: validation fails before anything is enqueued."""
+    fake = ctypes.c_void_p(0x1000)
+    ws = ctypes.c_void_p(0x10000)
+    lib = B._lib
+
+    def route(p, T=64, H=2048, E=64, hidden=fake, wsz=1 << 30, wsp=ws):
+        return lib.laser_route(hidden, fake, T, H, E, ctypes.byref(p), fake, fake, fake, fake, fake,
+                               None, wsp, wsz, None)
+
+    ok = dict(k=6, c=8, eps_high=0.4, t_fix=0.8)
+    assert route(B.make_params(**{**ok, "k": 0})) == -2
+    assert route(B.make_params(**{**ok, "c": 5})) == -2             # c < k
+    assert route(B.make_params(**{**ok, "c": 65})) == -2            # c > E
+    assert route(B.make_params(**{**ok, "eps_high": 0.0})) == -2
+    assert route(B.make_params(**{**ok, "t_fix": 1.5})) == -2
+    assert route(B.make_params(**{**ok, "t_fix": 0.0})) == -2
+    assert route(B.make_params(**ok), T=-1) == -2
+    assert route(B.make_params(k=6, c=8, eps_high=.4, t_fix=.8), E=65) == -5
+    assert route(B.make_params(k=2, c=17, eps_high=.4, t_fix=.8), E=64) == -5   # c > 16
+    assert route(B.make_params(**ok, trim_mode=B.TRIM_RANDOM)) == -5
+    assert route(B.make_params(**ok), H=2044) == -3                 # bf16 rows need H % 8 == 0
+    assert route(B.make_params(**ok), hidden=ctypes.c_void_p(0x1008)) == -3
+    assert route(B.make_params(**ok), hidden=None) == -1
+    assert route(B.make_params(**ok), wsz=1024) == -4
+    assert route(B.make_params(**ok), wsp=ctypes.c_void_p(0x10010)) == -3
+    bad = B.make_params(**ok)
+    bad.struct_bytes = 12
+    assert route(bad) == -6
+    assert route(B.make_params(**ok, dtype=7)) == -2
+
+
+def test_binding_raises_on_error(B):
+    with pytest.raises(B.LaserError):
+        B._check(-4)

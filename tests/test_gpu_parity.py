@@ -1,0 +1,173 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer outputs bit-exact; logits and weights within 2e-3
+(bf16 inputs) / 1e-5 (fp32 inputs) max abs error."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from synth import workloads as wl  # noqa: E402
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_cases.json")
+
+
+def _util():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _hand_cases():
+    with open(GOLDEN) as f:
+        return json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", _hand_cases(), ids=lambda c: c["name"])
+def test_hand_cases_on_gpu(case):
+    u = _util()
+    logits = np.log(np.array(case["p"], dtype=np.float64)).astype(np.float32)
+    gpu = u.run_route_from_logits(logits, case["k"], case["c"], case["eps_high"], case["t_fix"],
+                                  np.array(case["loads_in"], np.int32))
+    assert gpu["expert_ids"].tolist() == case["expert_ids"]
+    assert gpu["loads"].tolist() == case["loads_out"]
+    np.testing.assert_allclose(gpu["weights"], np.array(case["weights"]), atol=1e-5)
+
+
+@pytest.mark.parametrize("preset", ["paper", "stress", "topk", "gsm8k"])
+def test_tiny_fp32_config(preset):
+    u = _util()
+    inp = wl.layer_inputs("tiny")
+    s = inp["shape"]
+    eps, tfix = wl.thresholds("tiny", 0, preset)
+    gpu, ref = u.check_route(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
+                             inp["loads_in"], label=f"tiny/{preset}")
+    assert gpu["loads"].sum() == s.T * s.k
+
+
+SHAPES_FROM_LOGITS = [
+    # T, E, k, c, eps, tfix, kind
+    (1, 8, 2, 4, 0.9, 0.3, "normal"),
+    (63, 8, 2, 4, 0.7, 0.6, "normal"),
+    (64, 8, 2, 8, 2.0, 1e-30, "normal"),
+    (65, 64, 6, 8, 0.4, 0.8, "normal"),
+    (130, 64, 6, 8, 2.0, 1e-30, "normal"),
+    (1000, 64, 6, 16, 2.0, 0.05, "normal"),
+    (777, 5, 1, 5, 0.9, 0.2, "normal"),
+    (500, 33, 4, 7, 0.8, 0.3, "normal"),
+    (500, 2, 1, 2, 0.99, 0.1, "normal"),
+    (500, 2, 2, 2, 0.99, 0.1, "normal"),
+    (300, 16, 16, 16, 2.0, 0.5, "normal"),
+    (900, 6, 2, 4, 0.999, 0.37, "ties"),
+    (900, 64, 6, 10, 0.999, 0.37, "ties"),
+    (4096, 8, 2, 3, 0.6419, 0.6, "normal"),
+    (3000, 48, 8, 12, 0.5, 0.4, "normal"),
+]
+
+
+@pytest.mark.parametrize("T,E,k,c,eps,tfix,kind", SHAPES_FROM_LOGITS)
+@pytest.mark.parametrize("renorm", [True, False])
+def test_route_from_logits(T, E, k, c, eps, tfix, kind, renorm):
+    u = _util()
+    rng = np.random.default_rng(T * 131 + E)
+    logits = wl.random_logits(T + E + k, T, E, kind=kind, tie_levels=3,
+                              scale=float(rng.uniform(0.3, 2.0)))
+    loads_in = rng.integers(0, 7, size=E).astype(np.int32)
+    u.check_from_logits(logits, k, c, eps, tfix, loads_in, renormalize=renorm,
+                        label=f"T{T} E{E} k{k} c{c} {kind}")
+
+
+def test_extreme_logits():
+    """Scores that underflow the clamp, huge spreads, and all-equal rows."""
+    u = _util()
+    T, E = 200, 64
+    logits = wl.random_logits(5, T, E, scale=40.0)
+    logits[::7] = 1.25
+    logits[3] = -300.0
+    logits[3, 10] = 300.0
+    u.check_from_logits(logits, 6, 8, 0.9, 0.01, np.zeros(E, np.int32), label="extreme")
+
+
+def test_empty_batch():
+    u = _util()
+    E = 8
+    loads_in = np.arange(E, dtype=np.int32)
+    gpu = u.run_route_from_logits(np.zeros((0, E), np.float32), 2, 4, 0.5, 0.5, loads_in)
+    assert np.array_equal(gpu["loads"], loads_in)
+    assert np.array_equal(gpu["expert_offsets"], np.zeros(E + 1, np.int32))
+    assert gpu["expert_ids"].shape == (0, 2)
+
+
+BF16_SHAPES = [
+    # T, H, E, k, c
+    (200, 2048, 64, 6, 8),
+    (130, 4096, 8, 2, 4),
+    (65, 1000, 5, 2, 3),      # H not a multiple of the 64-value chunk, E < 8
+    (64, 8, 33, 4, 6),        # H smaller than a chunk
+    (1, 2048, 64, 6, 8),
+    (333, 512, 17, 3, 9),
+]
+
+
+@pytest.mark.parametrize("T,H,E,k,c", BF16_SHAPES)
+def test_bf16_gate_and_route(T, H, E, k, c):
+    u = _util()
+    rng = np.random.default_rng(T + H + E)
+    hidden, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16, bias=np.linspace(-1.0, 1.0, E))
+    if H < 64:
+        w = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(w) * 8.0)   # keep the logits spread
+    u.check_route(hidden, w, wl.DTYPE_BF16, k, c, 0.6, 0.3, rng.integers(0, 5, E).astype(np.int32),
+                  label=f"bf16 T{T} H{H} E{E}")
+
+
+def test_fp32_gate_ragged():
+    u = _util()
+    rng = np.random.default_rng(17)
+    hidden, w = wl.make_gate(rng, 300, 132, 12, wl.DTYPE_F32)
+    w = (w * 20).astype(np.float32)
+    u.check_route(hidden, w, wl.DTYPE_F32, 3, 6, 0.5, 0.2, np.zeros(12, np.int32), label="fp32 ragged")
+
+
+def test_split_call_carries_loads():
+    u = _util()
+    E, k, c, T = 64, 6, 8, 700
+    logits = wl.random_logits(9, T, E, scale=0.8)
+    L0 = (np.arange(E) % 5).astype(np.int32)
+    whole = u.run_route_from_logits(logits, k, c, 0.6, 0.5, L0)
+    a = 233
+    first = u.run_route_from_logits(logits[:a], k, c, 0.6, 0.5, L0)
+    second = u.run_route_from_logits(logits[a:], k, c, 0.6, 0.5, first["loads"])
+    assert np.array_equal(np.vstack([first["expert_ids"], second["expert_ids"]]), whole["expert_ids"])
+    assert np.array_equal(second["loads"], whole["loads"])
+
+
+def test_run_to_run_determinism():
+    u = _util()
+    inp = wl.layer_inputs("deepseek", 1, T=2048)
+    s = inp["shape"]
+    outs = [u.run_route(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, 2.0, 1e-30, inp["loads_in"])
+            for _ in range(3)]
+    for o in outs[1:]:
+        for key in outs[0]:
+            assert np.array_equal(o[key], outs[0][key]), key
+
+
+@pytest.mark.parametrize("name,layer,preset,T", [
+    ("mixtral", 0, "paper", 4096),
+    ("mixtral", 15, "paper", 4096),
+    ("mixtral", 3, "stress", 2048),
+    ("deepseek", 0, "paper", 4096),
+    ("deepseek", 2, "stress", 4096),
+    ("decode", 0, "gsm8k", None),
+    ("prefill", 0, "paper", 4096),
+])
+def test_benchmark_shapes_reduced_tokens(name, layer, preset, T):
+    u = _util()
+    inp = wl.layer_inputs(name, layer, T=T)
+    s = inp["shape"]
+    eps, tfix = wl.thresholds(name, layer, preset)
+    gpu, ref = u.check_route(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
+                             inp["loads_in"], label=f"{name}/{preset}")
+    if preset == "stress":
+        assert ref["expanded"].all() and (ref["cstar"] == s.c).all()
