@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the LASER routing step on one MI355X.
+
+A "step" is one pass of the whole routing path (gate projection, per-token
+analysis, load-ordered selection, dispatch) over every MoE layer of the workload:
+`layers` calls of laser_route on T tokens each, every layer with its own hidden
+states and gate matrix resident in HBM (distinct buffers, so that no layer is
+served from a cache warmed by the previous step) and its load counters zeroed
+at the start of the step.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes(T, H, E, k, sz):
+    """Bytes the method must move per layer: read hidden and the gate matrix once,
+    write ids, weights and permutation, read and write the counters, write offsets."""
+    whole = T * H * sz + E * H * sz + T * k * 12 + (E + 1) * 4 + 2 * E * 4
+    gate = T * H * sz + E * H * sz          # the gate kernel's share: its two inputs
+    return whole, gate
+
+
+def cpu_baseline(name, preset, budget_tokens):
+    """The oracle as it stands, single thread, on a bounded sample of the workload."""
+    import oracle
+    from synth import workloads as wl
+    s = wl.SHAPES[name]
+    T = min(s.T, budget_tokens)
+    inp = wl.layer_inputs(name, 0, T=T)
+    eps, tfix = wl.thresholds(name, 0, preset)
+    t0 = time.perf_counter()
+    out = oracle.route_from_hidden(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
+                                   inp["loads_in"])
+    dt = time.perf_counter() - t0
+    return {
+        "value": T / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": f"layer 0 of the {name} workload, {T} tokens, gate + routing + dispatch, "
+                  f"{dt:.2f} s on one host core",
+    }, float(out["expanded"].mean()), float((out["cstar"] > s.k).mean())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="deepseek", choices=["deepseek", "mixtral", "prefill"])
+    ap.add_argument("--preset", default="paper", choices=["paper", "gsm8k", "stress", "topk"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=16384)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_03293_amd import binding as B
+    from synth import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    s = wl.SHAPES[args.workload]
+    layers = args.layers or s.layers
+    T, H, E, k, c = s.T, s.H, s.E, s.k, s.c
+    sz = 2 if s.dtype == wl.DTYPE_BF16 else 4
+
+    # ---- inputs, resident in HBM before anything is timed --------------------
+    hidden, wgate, params = [], [], []
+    for layer in range(layers):
+        inp = wl.layer_inputs(args.workload, layer)
+        hidden.append(torch.from_numpy(inp["hidden"].view(np.int16)).view(torch.bfloat16).cuda())
+        wgate.append(torch.from_numpy(inp["w_gate"].view(np.int16)).view(torch.bfloat16).cuda())
+        eps, tfix = wl.thresholds(args.workload, layer, args.preset)
+        params.append(B.make_params(k, c, eps, tfix, dtype=s.dtype))
+    loads = torch.zeros((layers, E), dtype=torch.int32, device="cuda")
+    buf = B.RouteBuffers(T, H, E, params[0])
+    stream = torch.cuda.current_stream()
+    loads_of = [loads[layer] for layer in range(layers)]
+
+    def step():
+        loads.zero_()
+        for layer in range(layers):
+            B.laser_route(hidden[layer], wgate[layer], T, H, E, params[layer], loads_of[layer],
+                          buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
+                          buf.workspace, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = T * layers * args.steps / wall
+
+    # ---- the gate kernel alone, HIP events on the launch stream ---------------
+    B.laser_profile_enable(layers * args.steps)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    gate_ms, gate_launches = B.laser_profile_read()
+    B.laser_profile_enable(0)
+    whole_bytes, gate_bytes = algorithmic_bytes(T, H, E, k, sz)
+    gate_avg_s = gate_ms * 1e-3 / max(gate_launches, 1)
+    achieved = gate_bytes / gate_avg_s / 1e9
+
+    lo = loads.cpu().numpy().astype(np.float64)
+    imbalance = float(np.mean(lo.max(1) / lo.mean(1)))
+
+    out = {
+        "metric": "routed tokens/sec + % HBM roofline (fused gate+route+dispatch); max/mean load",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}-shaped gate: T={T} H={H} E={E} k={k} c={c}, "
+                        f"{layers} layers per step, thresholds preset '{args.preset}'",
+            "tokens_per_layer": T, "layers": layers, "preset": args.preset,
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "gate_bf16_kernel", "avg_launch_us": gate_avg_s * 1e6,
+            "algorithmic_bytes_per_launch": gate_bytes,
+        },
+        "whole_path": {
+            "us_per_layer": ms_per_step * 1e3 / layers,
+            "algorithmic_bytes_per_layer": whole_bytes,
+            "hbm_frac": whole_bytes / (ms_per_step * 1e-3 / layers) / 1e9 / HBM_PEAK_GBS,
+        },
+        "max_over_mean_load": imbalance,
+    }
+    if not args.no_cpu_baseline:
+        base, expanded, flexible = cpu_baseline(args.workload, args.preset, args.cpu_tokens)
+        out["cpu_baseline"] = base
+        out["expanded_fraction_layer0"] = expanded
+        out["load_dependent_fraction_layer0"] = flexible
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_out,
-      total;
+      flex_list, flex_ord, gsnap, rec_cids, total;
 };
 
 static Layout layout(int T, int E, bool need_logits) {
@@ -32,7 +32,11 @@ static Layout layout(int T, int E, bool need_logits) {
   L.flexmask = off;   off += align_up(ntiles * 8);
   L.fixed_cnt = off;  off += align_up(ntiles * 64 * 4);
   L.base = off;       off += align_up(ntiles * 64 * 4);
-  L.chain_out = off;  off += align_up(slots * 8);
+  L.chain_out = off;  off += align_up(ntiles * 2 * 64 * 4);
+  L.rec_cids = off;   off += align_up(slots * 16);
+  L.flex_list = off;  off += align_up(ntiles * 4);
+  L.flex_ord = off;   off += align_up(ntiles * 4);
+  L.gsnap = off;      off += align_up(ntiles * 64 * 4);
   L.total = off + 256;
   return L;
 }
@@ -52,7 +56,11 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.flexmask = reinterpret_cast<unsigned long long*>(b + L.flexmask);
   w.tile_fixed_cnt = reinterpret_cast<int32_t*>(b + L.fixed_cnt);
   w.tile_base = reinterpret_cast<int32_t*>(b + L.base);
-  w.chain_out = reinterpret_cast<unsigned long long*>(b + L.chain_out);
+  w.chain_out = reinterpret_cast<uint32_t*>(b + L.chain_out);
+  w.rec_cids = reinterpret_cast<uint8_t*>(b + L.rec_cids);
+  w.flex_list = reinterpret_cast<int32_t*>(b + L.flex_list);
+  w.flex_ord = reinterpret_cast<int32_t*>(b + L.flex_ord);
+  w.gsnap = reinterpret_cast<int32_t*>(b + L.gsnap);
   return w;
 }
 

@@ -39,7 +39,13 @@ struct Workspace {
   unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
   int32_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens
   int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
-  unsigned long long* chain_out;   // [slot] chosen-expert bit mask of a flexible token
+  uint32_t* chain_out;         // [ntiles,2,64] per expert: bit r%32 of word r/32 = chosen for
+                               //           the tile's r-th flexible token
+  uint8_t* rec_cids;           // [slot,16] lanes the chain reads: candidates by rank, padded
+  int32_t* flex_list;          // [ntiles]  tiles that hold flexible tokens, ascending
+  int32_t* flex_ord;           // [ntiles]  number of such tiles before this tile
+  int32_t* gsnap;              // [ntiles,64] flexible assignments up to the end of the
+                               //           f-th flexible tile, per expert
 };
 
 size_t workspace_bytes(int T, int E, bool need_logits);

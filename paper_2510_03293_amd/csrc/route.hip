@@ -240,6 +240,21 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
     }
     reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
     reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
+    // the chain reads exactly CP candidate lanes per token: ranks beyond the working
+    // set point at a lane that holds no candidate (its key compares as largest)
+    int padlane = a.E;  // lanes E..63 never hold a candidate
+    if (a.E == 64) {
+      unsigned used = 0;
+#pragma unroll
+      for (int j = 0; j < kMaxC; ++j)
+        if (j < cstar && top_e[j] < 32) used |= 1u << top_e[j];
+      padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
+    }
+    unsigned cidw = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxC; ++j)
+      if ((j >> 2) == q) cidw |= (unsigned)(j < cstar ? top_e[j] : padlane) << (8 * (j & 3));
+    reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
     // per owned expert: rank in the working set and the number of earlier fixed
     // tokens of this tile assigned to it
     uint16_t* row = ws.rec_lane + (size_t)slot * a.EP + q * NE;
@@ -301,92 +316,217 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
 
 // ----------------------------------------------------------------- chain -----
 //
-// One workgroup.  Wave 0 owns the counters (lane e = expert e) and walks the
-// tiles in order; waves 1..3 copy the next batch of records into LDS while it
-// works, so that no load of the chain waits on memory.  For a flexible token the
-// candidates' keys are (load << 4) + record, record = (fixed-prefix << 4 | rank):
-// ascending load, ties by score rank.  An expert is chosen iff fewer than k
-// candidate keys are smaller than its own.
+// One workgroup of 16 wavefronts.
+//   prefix  (all waves)  exclusive prefix over tiles of the fixed tokens' per-expert
+//           counts -> tile_base; ordered list of the tiles that hold flexible tokens.
+//   chain   (wave 0, lane e = expert e)  walks the flexible tiles in order.  The
+//           counters a flexible token sees are loads_in + fixed prefix of its tile
+//           + fixed tokens before it inside the tile (carried by its record) +
+//           flexible choices so far.  Candidate key = (load << 4) + rank: ascending
+//           load, ties by score rank.  An expert is chosen iff fewer than k
+//           candidate keys are smaller than its own; the candidates' keys are
+//           fetched with one lane read each (CP reads per token, CP = c rounded up
+//           to 4, 8 or 16).  Waves 1..12 copy the next batch of records into LDS
+//           meanwhile, so the chain never waits on memory.
+//   fix-up  (all waves)  tiles without flexible tokens add the flexible choices
+//           made before them to their tile_base.
+//
+// Output of the chain: for every flexible tile and expert, one bit per flexible
+// token of the tile (bit r of word r/32: chosen for the tile's r-th flexible token).
 
-constexpr int kChainBatch = 3;  // tiles per LDS batch (two batches fit 64 KiB of LDS)
+constexpr int kChainWaves = 16;
+constexpr int kChainThreads = kChainWaves * 64;
+constexpr int kChainBatch = 6;  // flexible tiles per LDS batch
 
 struct ChainBatch {
-  unsigned long long flexmask[kChainBatch];
-  int fixed_cnt[kChainBatch][64];
-  uint16_t rec[kChainBatch][kTile * kMaxE];
+  int tile[kChainBatch];
+  int nflex[kChainBatch];
+  int base[kChainBatch][64];
+  uint4 cids[kChainBatch][kTile];              // 16 candidate lanes per record
+  uint16_t rec[kChainBatch][kTile * kMaxE];    // per record and expert: prefix<<4 | rank
 };
+constexpr int kChainLdsBytes = 2 * (int)sizeof(ChainBatch);
 
-__device__ void chain_prefetch(ChainBatch* dst, int batch, const RouteArgs& a,
-                               const Workspace& ws, int ptid, int pthreads) {
-  for (int tl = 0; tl < kChainBatch; ++tl) {
-    const int tile = batch * kChainBatch + tl;
-    if (tile >= a.ntiles) break;
-    const unsigned long long fm = ws.flexmask[tile];
-    if (ptid == 0) dst->flexmask[tl] = fm;
-    for (int e = ptid; e < 64; e += pthreads)
-      dst->fixed_cnt[tl][e] = ws.tile_fixed_cnt[(size_t)tile * 64 + e];
-    const int words = (__builtin_popcountll(fm) * a.EP) >> 1;  // EP is even
-    const unsigned* src = reinterpret_cast<const unsigned*>(ws.rec_lane + (size_t)tile * kTile * a.EP);
-    unsigned* d32 = reinterpret_cast<unsigned*>(dst->rec[tl]);
-    for (int wd = ptid; wd < words; wd += pthreads) d32[wd] = src[wd];
+__device__ void chain_prefetch(ChainBatch* dst, int batch, int nflex_tiles, const RouteArgs& a,
+                               const Workspace& ws, int hwave, int lane) {
+  // two helper waves per tile of the batch
+  const int tl = hwave >> 1;
+  const int part = hwave & 1;
+  if (tl >= kChainBatch) return;
+  const int f = batch * kChainBatch + tl;
+  if (f >= nflex_tiles) return;
+  const int tile = ws.flex_list[f];
+  const int n = __builtin_popcountll(ws.flexmask[tile]);
+  if (part == 0) {
+    if (lane == 0) {
+      dst->tile[tl] = tile;
+      dst->nflex[tl] = n;
+    }
+    dst->base[tl][lane] = ws.tile_base[(size_t)tile * 64 + lane];
+    if (lane < n) dst->cids[tl][lane] = reinterpret_cast<const uint4*>(ws.rec_cids)[(size_t)tile * kTile + lane];
   }
+  const int words = (n * a.EP) >> 1;  // EP is even
+  const unsigned* src = reinterpret_cast<const unsigned*>(ws.rec_lane + (size_t)tile * kTile * a.EP);
+  unsigned* d32 = reinterpret_cast<unsigned*>(dst->rec[tl]);
+  for (int wd = part * 64 + lane; wd < words; wd += 128) d32[wd] = src[wd];
 }
 
-__global__ __launch_bounds__(256) void chain_kernel(const RouteArgs a, const Workspace ws,
-                                                    int32_t* __restrict__ loads_inout,
-                                                    int32_t* __restrict__ expert_offsets) {
-  __shared__ ChainBatch buf[2];
-  const int wave = threadIdx.x >> 6;
-  const int lane = threadIdx.x & 63;
-  const int nbatch = (a.ntiles + kChainBatch - 1) / kChainBatch;
+// One flexible token: returns whether this lane's expert is chosen.
+template <int CP>
+__device__ __forceinline__ bool chain_step(unsigned key, bool cand, const uint4 ids, int k) {
+  unsigned w[4];
+  w[0] = __builtin_amdgcn_readfirstlane(ids.x);
+  if (CP > 4) w[1] = __builtin_amdgcn_readfirstlane(ids.y);
+  if (CP > 8) {
+    w[2] = __builtin_amdgcn_readfirstlane(ids.z);
+    w[3] = __builtin_amdgcn_readfirstlane(ids.w);
+  }
+  int smaller = 0;
+#pragma unroll
+  for (int j = 0; j < CP; ++j) {
+    const int e = (w[j >> 2] >> (8 * (j & 3))) & 0xFF;
+    const unsigned other = __builtin_amdgcn_readlane(key, e);
+    smaller += (other < key) ? 1 : 0;
+  }
+  return cand && smaller < k;
+}
+
+template <int CP>
+__device__ __forceinline__ void chain_walk(ChainBatch* buf, int nflex_tiles, const RouteArgs& a,
+                                           const Workspace& ws, int wave, int lane, int lin,
+                                           int& gflex) {
+  const int nbatch = (nflex_tiles + kChainBatch - 1) / kChainBatch;
   const int NE = a.EP >> 2;
   const int mypos = (lane & 3) * NE + (lane >> 2);  // where expert `lane` sits in a record row
-
-  int lin = 0, lsum = 0;
-  if (wave == 0 && lane < a.E) lin = loads_inout[lane];
-  lsum = lin;
-
-  if (nbatch > 0) chain_prefetch(&buf[0], 0, a, ws, threadIdx.x, 256);
+  const bool lane_ok = lane < a.EP;
+  const int EP = a.EP;
+  const int k = a.k;
+  if (wave != 0) chain_prefetch(&buf[0], 0, nflex_tiles, a, ws, wave - 1, lane);
   __syncthreads();
-
   for (int b = 0; b < nbatch; ++b) {
     if (wave != 0) {
-      if (b + 1 < nbatch) chain_prefetch(&buf[(b + 1) & 1], b + 1, a, ws, threadIdx.x - 64, 192);
+      if (b + 1 < nbatch) chain_prefetch(&buf[(b + 1) & 1], b + 1, nflex_tiles, a, ws, wave - 1, lane);
     } else {
       const ChainBatch* cur = &buf[b & 1];
       for (int tl = 0; tl < kChainBatch; ++tl) {
-        const int tile = b * kChainBatch + tl;
-        if (tile >= a.ntiles) break;
-        ws.tile_base[(size_t)tile * 64 + lane] = lsum - lin;
-        unsigned long long fm = cur->flexmask[tl];
-        const int nflex = __builtin_popcountll(fm);
-        for (int r = 0; r < nflex; ++r) {
-          const unsigned rec = cur->rec[tl][r * a.EP + mypos];
-          const bool cand = (rec != 0xFFFFu) && (lane < a.EP);
-          const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
-          unsigned long long cm = __builtin_amdgcn_ballot_w64(cand);
-          int smaller = 0;
-          while (cm) {
-            const int e = __builtin_ctzll(cm);
-            cm &= cm - 1ull;
-            const unsigned other = __builtin_amdgcn_readlane(key, e);
-            smaller += (other < key) ? 1 : 0;
+        const int f = b * kChainBatch + tl;
+        if (f >= nflex_tiles) break;
+        const int tile = __builtin_amdgcn_readfirstlane(cur->tile[tl]);
+        const int n = __builtin_amdgcn_readfirstlane(cur->nflex[tl]);
+        const int fb = cur->base[tl][lane];
+        ws.tile_base[(size_t)tile * 64 + lane] = fb + gflex;
+        int lsum = lin + fb + gflex;
+        const uint16_t* recp = cur->rec[tl] + (lane_ok ? mypos : 0);
+        const uint4* cidp = cur->cids[tl];
+        unsigned rec_next = recp[0];
+        uint4 ids_next = cidp[0];
+        for (int r0 = 0; r0 < n; r0 += 32) {
+          const int r1 = min(n, r0 + 32);
+          unsigned hist = 0;
+          for (int r = r0; r < r1; ++r) {
+            const unsigned rec = rec_next;
+            const uint4 ids = ids_next;
+            if (r + 1 < n) {  // next record's LDS reads fly during this step
+              rec_next = recp[(r + 1) * EP];
+              ids_next = cidp[r + 1];
+            }
+            const bool cand = lane_ok && rec != 0xFFFFu;
+            const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
+            const bool chosen = chain_step<CP>(key, cand, ids, k);
+            lsum += chosen ? 1 : 0;
+            hist |= (chosen ? 1u : 0u) << (r - r0);
           }
-          const bool chosen = cand && smaller < a.k;
-          const unsigned long long chosen_mask = __builtin_amdgcn_ballot_w64(chosen);
-          lsum += chosen ? 1 : 0;
-          if (lane == 0) ws.chain_out[(size_t)tile * kTile + r] = chosen_mask;
+          ws.chain_out[((size_t)tile * 2 + (r0 >> 5)) * 64 + lane] = hist;
         }
-        lsum += cur->fixed_cnt[tl][lane];
+        gflex = lsum - lin - fb;
+        ws.gsnap[(size_t)f * 64 + lane] = gflex;
       }
     }
     __syncthreads();
   }
+}
+
+__global__ __launch_bounds__(kChainThreads) void chain_kernel(const RouteArgs a, const Workspace ws,
+                                                              int32_t* __restrict__ loads_inout,
+                                                              int32_t* __restrict__ expert_offsets) {
+  extern __shared__ __align__(16) unsigned char chain_lds[];
+  ChainBatch* buf = reinterpret_cast<ChainBatch*>(chain_lds);
+  __shared__ int wave_tot[kChainWaves][64];
+  __shared__ int wave_flex[kChainWaves];
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int ntiles = a.ntiles;
+
+  // ---- prefix over tiles of the fixed tokens' counts -------------------------
+  const int per_wave = (ntiles + kChainWaves - 1) / kChainWaves;
+  const int ta = min(wave * per_wave, ntiles), tb = min(ta + per_wave, ntiles);
+  int tot = 0;
+  for (int tile = ta; tile < tb; ++tile) tot += ws.tile_fixed_cnt[(size_t)tile * 64 + lane];
+  wave_tot[wave][lane] = tot;
+  // ---- which tiles hold flexible tokens (groups of 64 tiles per ballot) ------
+  const int groups = (ntiles + 63) >> 6;
+  const int gper = (groups + kChainWaves - 1) / kChainWaves;
+  const int ga = min(wave * gper, groups), gb = min(ga + gper, groups);
+  int nfl = 0;
+  for (int g = ga; g < gb; ++g) {
+    const int tile = g * 64 + lane;
+    const bool f = tile < ntiles && ws.flexmask[tile] != 0ull;
+    nfl += __builtin_popcountll(__builtin_amdgcn_ballot_w64(f));
+  }
+  if (lane == 0) wave_flex[wave] = nfl;
+  __syncthreads();
+  int run = 0, total_fixed = 0, fbefore = 0, nflex_tiles = 0;
+  for (int w = 0; w < kChainWaves; ++w) {
+    const int v = wave_tot[w][lane];
+    const int fl = wave_flex[w];
+    run += w < wave ? v : 0;
+    fbefore += w < wave ? fl : 0;
+    total_fixed += v;
+    nflex_tiles += fl;
+  }
+  for (int tile = ta; tile < tb; ++tile) {
+    const size_t o = (size_t)tile * 64 + lane;
+    const int cnt = ws.tile_fixed_cnt[o];
+    ws.tile_base[o] = run;
+    run += cnt;
+  }
+  for (int g = ga; g < gb; ++g) {
+    const int tile = g * 64 + lane;
+    const bool f = tile < ntiles && ws.flexmask[tile] != 0ull;
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(f);
+    const int ord = fbefore + __builtin_popcountll(bal & lanes_below(lane));
+    if (tile < ntiles) ws.flex_ord[tile] = ord;
+    if (f) ws.flex_list[ord] = tile;
+    fbefore += __builtin_popcountll(bal);
+  }
+  __syncthreads();  // tile_base, flex_list, flex_ord visible to the whole workgroup
+
+  int lin = 0;
+  if (lane < a.E) lin = loads_inout[lane];
+  int gflex = 0;  // flexible assignments so far (meaningful in wave 0)
+
+  if (nflex_tiles > 0) {
+    if (a.c <= 4)
+      chain_walk<4>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    else if (a.c <= 8)
+      chain_walk<8>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    else
+      chain_walk<16>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    // tiles without flexible tokens: add the flexible choices made before them
+    const long long total = (long long)ntiles * 64;
+    for (long long idx = threadIdx.x; idx < total; idx += kChainThreads) {
+      const int tile = (int)(idx >> 6);
+      if (ws.flexmask[tile] == 0ull) {
+        const int ord = ws.flex_ord[tile];
+        if (ord > 0) ws.tile_base[idx] += ws.gsnap[(size_t)(ord - 1) * 64 + (idx & 63)];
+      }
+    }
+  }
 
   if (wave == 0) {
-    if (lane < a.E) loads_inout[lane] = lsum;
+    const int cnt = lane < a.E ? total_fixed + gflex : 0;
+    if (lane < a.E) loads_inout[lane] = lin + cnt;
     // exclusive prefix sums of the per-expert assignment counts
-    const int cnt = lane < a.E ? lsum - lin : 0;
     int incl = cnt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -400,7 +540,15 @@ __global__ __launch_bounds__(256) void chain_kernel(const RouteArgs a, const Wor
 
 hipError_t launch_chain(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                         int32_t* expert_offsets, hipStream_t s) {
-  hipLaunchKernelGGL(chain_kernel, dim3(1), dim3(256), 0, s, a, ws, loads_inout, expert_offsets);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(chain_kernel, dim3(1), dim3(kChainThreads), kChainLdsBytes, s, a, ws,
+                     loads_inout, expert_offsets);
   return hipGetLastError();
 }
 
@@ -431,7 +579,12 @@ __global__ __launch_bounds__(64) void finish_kernel(const RouteArgs a, const Wor
   if (cstar > 0) {
     const unsigned long long fm = ws.flexmask[tile];
     const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(lane));
-    const unsigned long long chosen = ws.chain_out[slot];
+    const int r = slot - tile * kTile;
+    const unsigned* cw = ws.chain_out + ((size_t)tile * 2 + (r >> 5)) * 64;
+    unsigned long long chosen = 0ull;
+    for (int j = 0; j < cstar; ++j)
+      chosen |= (unsigned long long)((cw[ws.rec_ids[(size_t)t * 16 + j]] >> (r & 31)) & 1u)
+                << ws.rec_ids[(size_t)t * 16 + j];
     const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
     const float* pv = ws.rec_p + (size_t)t * 16;
     float denom = 0.0f;
