@@ -122,6 +122,15 @@ const char* laser_strerror(int code);
 int laser_profile_enable(int32_t max_calls);
 int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches);
 
+/*
+ * What a pair of HIP events adds to the kernel it brackets, in milliseconds (host
+ * pointer): the library launches a kernel that spins for a fixed 10 microseconds of
+ * the GPU's constant-rate clock between event pairs on `hip_stream`, synchronises,
+ * and returns the median of (elapsed - 10 us).  Benchmarks subtract it from the
+ * per-launch average of laser_profile_read.  Creates and destroys its own events.
+ */
+int laser_profile_event_overhead(void* hip_stream, double* overhead_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ TRIM_TOP = 0
 TRIM_RANDOM = 1
 
 EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_from_logits",
-           "laser_strerror", "laser_profile_enable", "laser_profile_read")
+           "laser_strerror", "laser_profile_enable", "laser_profile_read",
+           "laser_profile_event_overhead")
 
 
 class LaserParams(ctypes.Structure):
@@ -62,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.laser_profile_enable.restype = ctypes.c_int
     lib.laser_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.laser_profile_read.restype = ctypes.c_int
+    lib.laser_profile_event_overhead.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.laser_profile_event_overhead.restype = ctypes.c_int
     return lib
 
 
@@ -123,6 +126,13 @@ def laser_profile_read() -> tuple[float, int]:
     n = ctypes.c_int64(0)
     _check(_lib.laser_profile_read(ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def laser_profile_event_overhead(stream=None) -> float:
+    """Milliseconds a HIP event pair adds to the kernel it brackets (measured now)."""
+    ms = ctypes.c_double(0.0)
+    _check(_lib.laser_profile_event_overhead(_stream_handle(stream), ctypes.byref(ms)))
+    return ms.value
 
 
 class RouteBuffers:

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "../../include/laser.h"
@@ -30,7 +31,7 @@ static Layout layout(int T, int E, bool need_logits) {
   L.rec_Z = off;      off += align_up((size_t)T * 4);
   L.rec_lane = off;   off += align_up(slots * EP * 2);
   L.flexmask = off;   off += align_up(ntiles * 8);
-  L.fixed_cnt = off;  off += align_up(ntiles * 64 * 4);
+  L.fixed_cnt = off;  off += align_up(ntiles * 64);
   L.base = off;       off += align_up(ntiles * 64 * 4);
   L.chain_out = off;  off += align_up(ntiles * 2 * 64 * 4);
   L.rec_cids = off;   off += align_up(slots * 16);
@@ -54,7 +55,7 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.rec_Z = reinterpret_cast<float*>(b + L.rec_Z);
   w.rec_lane = reinterpret_cast<uint16_t*>(b + L.rec_lane);
   w.flexmask = reinterpret_cast<unsigned long long*>(b + L.flexmask);
-  w.tile_fixed_cnt = reinterpret_cast<int32_t*>(b + L.fixed_cnt);
+  w.tile_fixed_cnt = reinterpret_cast<uint8_t*>(b + L.fixed_cnt);
   w.tile_base = reinterpret_cast<int32_t*>(b + L.base);
   w.chain_out = reinterpret_cast<uint32_t*>(b + L.chain_out);
   w.rec_cids = reinterpret_cast<uint8_t*>(b + L.rec_cids);
@@ -65,6 +66,13 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
 }
 
 // ------------------------------------------------------- stage timing pool ----
+// Spins for `ticks` of the constant 100 MHz clock; used to calibrate event overhead.
+__global__ void spin_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < ticks) {
+  }
+}
+
 struct Profile {
   std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after the gate kernel
   int used = 0;                // pairs recorded
@@ -97,10 +105,9 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   return a;
 }
 
-static int route_tail(const float* logits, const RouteArgs& a, const Workspace& ws,
-                      int32_t* loads_inout, int32_t* expert_ids, float* weights,
-                      int32_t* permutation, int32_t* expert_offsets, hipStream_t s) {
-  if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+static int route_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                      int32_t* expert_ids, float* weights, int32_t* permutation,
+                      int32_t* expert_offsets, hipStream_t s) {
   if (launch_chain(a, ws, loads_inout, expert_offsets, s) != hipSuccess) return LASER_E_LAUNCH;
   if (launch_finish(a, ws, expert_offsets, expert_ids, weights, permutation, s) != hipSuccess)
     return LASER_E_LAUNCH;
@@ -141,20 +148,24 @@ int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, in
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const RouteArgs a = make_args(T, E, params);
   const Workspace ws = carve_workspace(workspace, T, E, need_logits);
-  float* logits = logits_out ? logits_out : ws.logits;
-
   const bool timed = !g_profile.ev.empty() && (size_t)(2 * g_profile.used + 1) < g_profile.ev.size() && T > 0;
   if (timed && hipEventRecord(g_profile.ev[2 * g_profile.used], s) != hipSuccess) return LASER_E_LAUNCH;
-  hipError_t he = params->dtype == LASER_DTYPE_BF16
-                      ? launch_gate_bf16(hidden, w_gate, T, H, E, logits, s)
-                      : launch_gate_f32(static_cast<const float*>(hidden),
-                                        static_cast<const float*>(w_gate), T, H, E, logits, s);
-  if (he != hipSuccess) return LASER_E_LAUNCH;
+  if (params->dtype == LASER_DTYPE_BF16) {
+    // gate projection and per-token analysis in one kernel
+    if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits_out, s) != hipSuccess)
+      return LASER_E_LAUNCH;
+  } else {
+    float* logits = logits_out ? logits_out : ws.logits;
+    if (launch_gate_f32(static_cast<const float*>(hidden), static_cast<const float*>(w_gate), T, H, E,
+                        logits, s) != hipSuccess)
+      return LASER_E_LAUNCH;
+    if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+  }
   if (timed) {
     if (hipEventRecord(g_profile.ev[2 * g_profile.used + 1], s) != hipSuccess) return LASER_E_LAUNCH;
     ++g_profile.used;
   }
-  return route_tail(logits, a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
+  return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
 }
 
 int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
@@ -170,8 +181,9 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
   if (workspace_bytes_given < workspace_bytes(T, E, true)) return LASER_E_WORKSPACE;
   const RouteArgs a = make_args(T, E, params);
   const Workspace ws = carve_workspace(workspace, T, E, true);
-  return route_tail(logits, a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets,
-                    static_cast<hipStream_t>(hip_stream));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+  return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
 }
 
 const char* laser_strerror(int code) {
@@ -217,6 +229,33 @@ int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches) {
   *gate_ms_sum = sum;
   *gate_launches = g_profile.used;
   g_profile.used = 0;
+  return LASER_OK;
+}
+
+int laser_profile_event_overhead(void* hip_stream, double* overhead_ms) {
+  if (!overhead_ms) return LASER_E_NULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int reps = 21;
+  const long long ticks = 1000;  // 10 us at 100 MHz
+  std::vector<hipEvent_t> ev(2 * reps);
+  for (size_t i = 0; i < ev.size(); ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) return LASER_E_LAUNCH;
+  for (int i = 0; i < reps; ++i) {
+    if (hipEventRecord(ev[2 * i], s) != hipSuccess) return LASER_E_LAUNCH;
+    hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
+    if (hipEventRecord(ev[2 * i + 1], s) != hipSuccess) return LASER_E_LAUNCH;
+  }
+  std::vector<float> ms(reps);
+  int rc = LASER_OK;
+  for (int i = 0; i < reps; ++i) {
+    if (hipEventSynchronize(ev[2 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms[i], ev[2 * i], ev[2 * i + 1]) != hipSuccess)
+      rc = LASER_E_LAUNCH;
+  }
+  for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  if (rc != LASER_OK) return rc;
+  std::sort(ms.begin(), ms.end());
+  *overhead_ms = (double)ms[reps / 2] - 0.010;
   return LASER_OK;
 }
 

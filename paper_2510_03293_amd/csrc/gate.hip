@@ -1,19 +1,26 @@
 // Gate projection: logits[t,e] = sum_h hidden[t,h] * w_gate[e,h]  (the paper's
 // "gate function", applied before Algorithm 1; Introduction / Method,
-// "Integration with MoE Forward Pass").
+// "Integration with MoE Forward Pass"), followed in the same kernel by the
+// per-token analysis, so the logits never travel through HBM unless asked for.
 //
 // bf16 path (gfx950): one workgroup of 4 wavefronts per tile of 64 tokens.  The
 // contraction axis is cut into chunks of 64 values dealt round-robin to the 4
 // waves, so at any moment a workgroup reads 512 contiguous bytes of every token
-// row.  Operands go from memory straight into MFMA layout.  The 16x16x32 bf16 MFMA
-// is used because of how its operands sit in the wave: lane l owns row (expert, A
-// operand) or column (token, B operand) l%16 and the 8 contraction slots
-// 8*(l/16)..+7, and both operands use the same slot -> h mapping.  One 16-byte
-// load per lane then covers 16 rows x 64 contiguous bytes, which the memory
-// pipeline handles as 16 half cache lines per instruction (the 32x32 shapes spread
-// a load over 32 rows x 2 separate 16-byte pieces and run at a quarter of the
-// rate).  Accumulation is fp32.  The 4 partial tiles meet in LDS and are added in
-// the fixed order ((w0 + w1) + w2) + w3, which keeps the logits bit-reproducible.
+// row; each wave owns its chunks from load to MFMA and needs no barrier until the
+// end.
+//
+// Memory -> registers: 16-byte loads with 8 consecutive lanes on one row, i.e. 8
+// rows x 128 contiguous bytes per instruction.  The vector memory pipeline runs at
+// full rate only when each group of 4 consecutive lanes reads 64 contiguous bytes;
+// loading straight into MFMA layout (consecutive lanes on different rows) runs at a
+// quarter of it, which for this kernel costs more than the HBM stream itself.
+// Registers -> LDS -> registers: the wave parks the chunk in a private LDS strip
+// (rows padded to 144 bytes) and reads it back in the layout of the 16x16x32 bf16
+// MFMA (lane l: row/column l%16, contraction slots 8*(l/16)..+7); both operands use
+// the same slot -> h mapping.  Two chunks are in flight in registers while a third
+// is being multiplied.  Accumulation is fp32.  The 4 partial tiles meet in LDS and
+// are added in the fixed order ((w0 + w1) + w2) + w3 (bit-reproducible logits).
+#include "analyse.h"
 #include "laser_internal.h"
 
 namespace laser {
@@ -22,51 +29,73 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* global_u4_ptr;
+typedef __attribute__((address_space(3))) u32x4* lds_u4_ptr;
 
 constexpr int kGateWaves = 4;
-constexpr int kPartStride = 68;  // floats per token row of a partial tile (64 + 4 pad)
-constexpr int kGateLdsBytes = kGateWaves * kTile * kPartStride * 4;
+constexpr int kPartStride = 68;   // floats per token row of a partial tile (64 + 4 pad)
+constexpr int kRowBytes = 144;    // staged row: 128 bytes of a chunk + 16 bytes pad
+constexpr int kStripBytes = 2 * kTile * kRowBytes;  // per wave: hidden rows, then W rows
+constexpr int kPartBytes = kGateWaves * kTile * kPartStride * 4;
+constexpr int kGateLdsBytes =
+    kPartBytes > kGateWaves * kStripBytes ? kPartBytes : kGateWaves * kStripBytes;
 
-// 16-byte load from global memory (explicit address space: plain global_load, which
-// only counts on vmcnt, so MFMAs can start while later loads are still in flight).
 __device__ __forceinline__ u32x4 load_global_16(const uint16_t* p) {
   return *(global_u4_ptr)(p);
 }
 
-// Loads one 64-value chunk of the operands in MFMA layout: 2 k-steps x (EB expert
-// blocks of W + 4 token blocks of hidden), 16 bytes per lane and piece.  Rows are
-// clamped to valid ones by the caller, so every load is unconditional.  The
-// scheduling barriers keep the compiler from sinking a chunk's loads down to their
-// first use, which would undo the prefetch.
-#define GATE_LOAD_CHUNK(A, B, KOFF)                                              \
-  _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) {                             \
-    _Pragma("unroll") for (int tb_ = 0; tb_ < 4; ++tb_)                          \
-        B[tb_][s_] = load_global_16(hrow[tb_] + (KOFF) + s_ * 32);               \
-    _Pragma("unroll") for (int eb_ = 0; eb_ < EB; ++eb_)                         \
-        A[eb_][s_] = load_global_16(wrow[eb_] + (KOFF) + s_ * 32);               \
-  }                                                                              \
+// G: global -> registers, one chunk (8 loads of hidden rows, 2*EB of W rows).
+#define GATE_G(R, KOFF)                                                          \
+  _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
+      R.h[q_] = load_global_16(hsrc[q_] + (KOFF));                               \
+  _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
+      R.w[q_] = load_global_16(wsrc[q_] + (KOFF));                               \
   __builtin_amdgcn_sched_barrier(0);
 
-#define GATE_MFMA_CHUNK(A, B)                                                    \
-  _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_)                               \
+// S: registers -> the wave's LDS strip.
+#define GATE_S(R)                                                                \
+  _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
+      *(lds_u4_ptr)(st_wr + q_ * 8 * kRowBytes) = R.h[q_];                       \
+  _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
+      *(lds_u4_ptr)(st_wr + kTile * kRowBytes + q_ * 8 * kRowBytes) = R.w[q_];   \
+  __builtin_amdgcn_sched_barrier(0);
+
+// M: LDS strip -> MFMA operands -> accumulate, two k-steps of 32.
+#define GATE_M()                                                                 \
+  _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_) {                             \
+    u32x4 b_[4], a_[EB];                                                         \
+    _Pragma("unroll") for (int tb_ = 0; tb_ < 4; ++tb_)                          \
+        b_[tb_] = *(lds_u4_ptr)(st_rd + tb_ * 16 * kRowBytes + s_ * 64);         \
+    _Pragma("unroll") for (int eb_ = 0; eb_ < EB; ++eb_)                         \
+        a_[eb_] = *(lds_u4_ptr)(st_rd + kTile * kRowBytes + eb_ * 16 * kRowBytes + s_ * 64); \
     _Pragma("unroll") for (int eb_ = 0; eb_ < EB; ++eb_)                         \
       _Pragma("unroll") for (int tb_ = 0; tb_ < 4; ++tb_)                        \
         acc[eb_][tb_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                 \
-            __builtin_bit_cast(bf16x8, A[eb_][s_]), __builtin_bit_cast(bf16x8, B[tb_][s_]), \
+            __builtin_bit_cast(bf16x8, a_[eb_]), __builtin_bit_cast(bf16x8, b_[tb_]), \
             acc[eb_][tb_], 0, 0, 0);                                             \
+  }                                                                              \
   __builtin_amdgcn_sched_barrier(0);
 
-template <int EB>  // 16-expert blocks: 1 (E <= 16), 2 (E <= 32) or 4 (E <= 64)
-__global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restrict__ hidden,
-                                                        const uint16_t* __restrict__ w,
-                                                        int T, int H, int E,
-                                                        float* __restrict__ logits) {
-  extern __shared__ __align__(16) float part[];  // [4][64][kPartStride]
+template <int EB>
+struct GateRegs {
+  u32x4 h[8];
+  u32x4 w[2 * EB];
+};
+
+// EB: 16-expert blocks, 1 (E <= 16), 2 (E <= 32) or 4 (E <= 64).  NE: experts per
+// lane of the per-token analysis that follows in the same kernel (padded E / 4).
+template <int EB, int NE>
+__global__ __launch_bounds__(256) void gate_analyse_bf16_kernel(
+    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a,
+    const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
+    float* __restrict__ logits_out) {
+  extern __shared__ __align__(16) unsigned char gate_lds[];
+  __shared__ unsigned long long mask64[64];
+  __shared__ unsigned long long flex_lds;
+  const int T = a.T, E = a.E;
   const int tile = blockIdx.x;
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
-  const int n = lane & 15;       // row (expert) / column (token) inside a 16-block
-  const int kgrp = lane >> 4;    // which 8-value group of a 32-value k-step
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
   f32x4 acc[EB][4];
 #pragma unroll
@@ -76,69 +105,95 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[eb][tb][r] = 0.0f;
 
-  // Rows past the end (tokens >= T, experts >= E) are clamped to the last valid
-  // row: their products land in accumulator entries that are never written out.
-  const uint16_t* hrow[4];
+  // Load side: lane l of load q takes piece l%8 (16 bytes) of row 8q + l/8.  Rows past
+  // the end (tokens >= T, experts >= E) are clamped to the last valid row: their
+  // products land in accumulator entries that are never used.
+  const int lrow = lane >> 3, lpiece = lane & 7;
+  const uint16_t* hsrc[8];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
-    hrow[tb] = hidden + (size_t)min(tile * kTile + tb * 16 + n, T - 1) * H + kgrp * 8;
-  const uint16_t* wrow[EB];
+  for (int q = 0; q < 8; ++q)
+    hsrc[q] = hidden + (size_t)min(tile * kTile + q * 8 + lrow, T - 1) * H + lpiece * 8;
+  const uint16_t* wsrc[2 * EB];
 #pragma unroll
-  for (int eb = 0; eb < EB; ++eb) wrow[eb] = w + (size_t)min(eb * 16 + n, E - 1) * H + kgrp * 8;
+  for (int q = 0; q < 2 * EB; ++q) wsrc[q] = w + (size_t)min(q * 8 + lrow, E - 1) * H + lpiece * 8;
+  // LDS side: the strip of this wave; write position of (row l/8, piece l%8), read
+  // position of (row l%16, slot group l/16).
+  unsigned char* strip = gate_lds + wave_u * kStripBytes;
+  unsigned char* st_wr = strip + lrow * kRowBytes + lpiece * 16;
+  unsigned char* st_rd = strip + (lane & 15) * kRowBytes + (lane >> 4) * 16;
 
-  // Full chunks, two in flight per wave: the loads of chunk i+1 are issued before
-  // the MFMAs of chunk i, so a workgroup keeps 64 KiB of operand reads outstanding.
-  // The wave index is made wave-uniform so that the loop is plain scalar control
-  // flow and the compiler's wait counts inside the body stay exact.
   const int nfull = H >> 6;
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int nmine = (nfull - wave_u + kGateWaves - 1) / kGateWaves;  // chunks wave, wave+4, ...
+  // Every tile starts its walk over the contraction axis at a different chunk, so
+  // that the workgroups running at the same time do not all read the same column
+  // range of their rows (which would land on the same memory channels).
+  const int lim = nfull * 64;
   const int cstride = kGateWaves * 64;
-  u32x4 a0[EB][2], b0[4][2], a1[EB][2], b1[4][2];
-  int koff = wave_u * 64;  // element offset of the chunk held in (a0, b0)
-  int i = 0;
-  if (nmine > 0) { GATE_LOAD_CHUNK(a0, b0, koff) }
-  while (i + 2 < nmine) {  // straight-line body: waits are exact
-    GATE_LOAD_CHUNK(a1, b1, koff + cstride)
-    GATE_MFMA_CHUNK(a0, b0)
-    GATE_LOAD_CHUNK(a0, b0, koff + 2 * cstride)
-    GATE_MFMA_CHUNK(a1, b1)
-    koff += 2 * cstride;
-    i += 2;
-  }
-  if (i + 1 < nmine) {
-    GATE_LOAD_CHUNK(a1, b1, koff + cstride)
-    GATE_MFMA_CHUNK(a0, b0)
-    GATE_MFMA_CHUNK(a1, b1)
-  } else if (i < nmine) {
-    GATE_MFMA_CHUNK(a0, b0)
+  int koff = nfull > 0 ? ((tile * 5 + wave_u) % nfull) * 64 : 0;
+  auto step = [&](int k) { k += cstride; return k >= lim ? k - lim : k; };  // nfull >= 4 when used
+
+  // Software pipeline over this wave's chunks c0, c1, ...: while chunk i is
+  // multiplied out of LDS, chunks i+1 and i+2 are in flight in ra / rb.
+  GateRegs<EB> ra, rb;
+  if (nmine > 0) {
+    GATE_G(ra, koff)
+    GATE_S(ra)                       // chunk 0 staged
+    if (nmine > 1) { koff = step(koff); GATE_G(ra, koff) }   // chunk 1 in ra
+    int i = 0;
+    while (i + 3 < nmine) {          // straight-line body, two chunks per trip
+      koff = step(koff);
+      GATE_G(rb, koff)               // chunk i+2
+      GATE_M()                       // chunk i
+      GATE_S(ra)                     // chunk i+1 staged
+      koff = step(koff);
+      GATE_G(ra, koff)               // chunk i+3
+      GATE_M()                       // chunk i+1
+      GATE_S(rb)                     // chunk i+2 staged
+      i += 2;
+    }
+    // here: chunk i staged, chunk i+1 (if any) in ra; at most 3 chunks left
+    if (i + 2 < nmine) {
+      koff = step(koff);
+      GATE_G(rb, koff)               // chunk i+2, the last one
+      GATE_M()
+      GATE_S(ra)
+      GATE_M()
+      GATE_S(rb)
+      GATE_M()
+    } else if (i + 1 < nmine) {
+      GATE_M()
+      GATE_S(ra)
+      GATE_M()
+    } else {
+      GATE_M()
+    }
   }
   // Ragged tail of the contraction axis (H % 64 != 0), taken by one wave: pieces
   // past H are read from the start of the row instead and replaced by zeros.
   if ((H & 63) != 0 && wave_u == (nfull & 3)) {
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const bool kin = nfull * 64 + lpiece * 8 < H;  // H % 8 == 0: a piece is all in or all out
+    const int off = kin ? nfull * 64 : -lpiece * 8;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int kk = nfull * 64 + s * 32 + kgrp * 8;  // H % 8 == 0: a piece is all in or all out
-      const bool kin = kk < H;
-      const int off = kin ? nfull * 64 + s * 32 : -kgrp * 8;
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb) {
-        const u32x4 v = load_global_16(hrow[tb] + off);
-        b0[tb][s] = kin ? v : zero4;
-      }
-#pragma unroll
-      for (int eb = 0; eb < EB; ++eb) {
-        const u32x4 v = load_global_16(wrow[eb] + off);
-        a0[eb][s] = kin ? v : zero4;
-      }
+    for (int q = 0; q < 8; ++q) {
+      const u32x4 v = load_global_16(hsrc[q] + off);
+      ra.h[q] = kin ? v : zero4;
     }
-    GATE_MFMA_CHUNK(a0, b0)
+#pragma unroll
+    for (int q = 0; q < 2 * EB; ++q) {
+      const u32x4 v = load_global_16(wsrc[q] + off);
+      ra.w[q] = kin ? v : zero4;
+    }
+    GATE_S(ra)
+    GATE_M()
   }
+  __syncthreads();  // all strips are dead: the partial tiles reuse the space
 
   // Accumulator layout of the 16x16 MFMA: register r of lane l holds
   // row 4*(l/16) + r (expert) of column l%16 (token).
+  float* part = reinterpret_cast<float*>(gate_lds);  // [4][64][kPartStride]
   float* mine = part + (size_t)wave * kTile * kPartStride;
+  const int n = lane & 15, kgrp = lane >> 4;
 #pragma unroll
   for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
@@ -148,48 +203,38 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const uint16_t* __restri
     }
   __syncthreads();
 
-  const int total = kTile * E;
-  for (int idx = threadIdx.x; idx < total; idx += 256) {
-    const int tok = idx / E;
-    const int e = idx - tok * E;
-    const int o = tok * kPartStride + e;
-    float v = part[o] + part[kTile * kPartStride + o];
-    v = v + part[2 * kTile * kPartStride + o];
-    v = v + part[3 * kTile * kPartStride + o];
-    const int t = tile * kTile + tok;
-    if (t < T) logits[(size_t)t * E + e] = v;
-  }
+  // The four partial tiles are summed on the fly by the analysis.
+  analyse_tile<NE, kGateWaves>(part, kPartStride, mask64, &flex_lds, tile, a, ws, expert_ids,
+                               weights, logits_out);
 }
 
-hipError_t launch_gate_bf16(const void* hidden, const void* w, int T, int H, int E,
-                            float* logits, hipStream_t s) {
+template <int EB, int NE>
+static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
+                             const Workspace& ws, int32_t* expert_ids, float* weights,
+                             float* logits_out, hipStream_t s) {
   static bool attr_set = false;
+  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE>);
   if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bf16_kernel<1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bf16_kernel<2>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-    hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bf16_kernel<4>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-    if (e1 != hipSuccess) return e1;
-    if (e2 != hipSuccess) return e2;
-    if (e4 != hipSuccess) return e4;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int ntiles = (T + kTile - 1) / kTile;
-  if (ntiles == 0) return hipSuccess;
-  const uint16_t* h16 = static_cast<const uint16_t*>(hidden);
-  const uint16_t* w16 = static_cast<const uint16_t*>(w);
-  if (E <= 16)
-    hipLaunchKernelGGL(gate_bf16_kernel<1>, dim3(ntiles), dim3(256), kGateLdsBytes, s, h16, w16,
-                       T, H, E, logits);
-  else if (E <= 32)
-    hipLaunchKernelGGL(gate_bf16_kernel<2>, dim3(ntiles), dim3(256), kGateLdsBytes, s, h16, w16,
-                       T, H, E, logits);
-  else
-    hipLaunchKernelGGL(gate_bf16_kernel<4>, dim3(ntiles), dim3(256), kGateLdsBytes, s, h16, w16,
-                       T, H, E, logits);
+  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE>), dim3(a.ntiles), dim3(256), kGateLdsBytes, s,
+                     static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
+                     expert_ids, weights, logits_out);
   return hipGetLastError();
+}
+
+hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
+                                    const Workspace& ws, int32_t* expert_ids, float* weights,
+                                    float* logits_out, hipStream_t s) {
+  if (a.ntiles == 0) return hipSuccess;
+  switch (a.EP) {
+    case 8: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 16: return launch_one<1, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 32: return launch_one<2, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    default: return launch_one<4, 16>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  }
 }
 
 // fp32 path: one thread per (token, expert) dot product, float4 loads, fused

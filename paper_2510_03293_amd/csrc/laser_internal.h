@@ -37,7 +37,7 @@ struct Workspace {
   float* rec_Z;                // [T]     softmax normaliser
   uint16_t* rec_lane;          // [slot,EP] per expert: (fixed-prefix << 4 | rank) or 0xFFFF
   unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
-  int32_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens
+  uint8_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens (<= 64)
   int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
   uint32_t* chain_out;         // [ntiles,2,64] per expert: bit r%32 of word r/32 = chosen for
                                //           the tile's r-th flexible token
@@ -54,8 +54,10 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits);
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
 
 // Launchers (enqueue only; return the HIP error of the launch).
-hipError_t launch_gate_bf16(const void* hidden, const void* w, int T, int H, int E,
-                            float* logits, hipStream_t s);
+// gate projection fused with the per-token analysis (logits_out may be NULL)
+hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
+                                    const Workspace& ws, int32_t* expert_ids, float* weights,
+                                    float* logits_out, hipStream_t s);
 hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E,
                            float* logits, hipStream_t s);
 hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
