@@ -118,6 +118,9 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
 
   if (tid < 64) mask64[tid] = 0ull;
   if (tid == 0) *flex_lds = 0ull;
+  // the tail kernel of this call polls these words; they are cleared here, one
+  // kernel earlier on the same stream
+  if (tile == 0 && tid < 4) ws.status[tid] = 0;
 
   float z[NE], zw[NE];
 #pragma unroll

@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_out,
-      flex_list, flex_ord, gsnap, rec_cids, total;
+      flex_list, flex_ord, gsnap, rec_cids, status, total;
 };
 
 static Layout layout(int T, int E, bool need_logits) {
@@ -38,6 +38,7 @@ static Layout layout(int T, int E, bool need_logits) {
   L.flex_list = off;  off += align_up(ntiles * 4);
   L.flex_ord = off;   off += align_up(ntiles * 4);
   L.gsnap = off;      off += align_up(ntiles * 64 * 4);
+  L.status = off;     off += align_up(16);
   L.total = off + 256;
   return L;
 }
@@ -62,6 +63,7 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.flex_list = reinterpret_cast<int32_t*>(b + L.flex_list);
   w.flex_ord = reinterpret_cast<int32_t*>(b + L.flex_ord);
   w.gsnap = reinterpret_cast<int32_t*>(b + L.gsnap);
+  w.status = reinterpret_cast<int32_t*>(b + L.status);
   return w;
 }
 
@@ -108,8 +110,7 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
 static int route_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                       int32_t* expert_ids, float* weights, int32_t* permutation,
                       int32_t* expert_offsets, hipStream_t s) {
-  if (launch_chain(a, ws, loads_inout, expert_offsets, s) != hipSuccess) return LASER_E_LAUNCH;
-  if (launch_finish(a, ws, expert_offsets, expert_ids, weights, permutation, s) != hipSuccess)
+  if (launch_tail(a, ws, loads_inout, expert_offsets, expert_ids, weights, permutation, s) != hipSuccess)
     return LASER_E_LAUNCH;
   return LASER_OK;
 }

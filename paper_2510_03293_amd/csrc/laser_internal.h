@@ -46,7 +46,12 @@ struct Workspace {
   int32_t* flex_ord;           // [ntiles]  number of such tiles before this tile
   int32_t* gsnap;              // [ntiles,64] flexible assignments up to the end of the
                                //           f-th flexible tile, per expert
+  int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
 };
+
+constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished
+constexpr int kStatusFlexTiles = 1;  // number of tiles that hold flexible tokens
+constexpr int kStatusError = 2;      // a bounded wait in the tail kernel ran out
 
 size_t workspace_bytes(int T, int E, bool need_logits);
 Workspace carve_workspace(void* base, int T, int E, bool need_logits);
@@ -62,10 +67,8 @@ hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, in
                            float* logits, hipStream_t s);
 hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s);
-hipError_t launch_chain(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
-                        int32_t* expert_offsets, hipStream_t s);
-hipError_t launch_finish(const RouteArgs& a, const Workspace& ws, const int32_t* expert_offsets,
-                         int32_t* expert_ids, float* weights, int32_t* permutation,
-                         hipStream_t s);
+hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                       int32_t* expert_offsets, int32_t* expert_ids, float* weights,
+                       int32_t* permutation, hipStream_t s);
 
 }  // namespace laser

@@ -1,6 +1,8 @@
 // Algorithm 1 of the paper (appendix "Pseudo Code"; Method: Expansion rule,
 // Final assignment) applied to the tokens of a layer in token order, plus the
-// dispatch tables.  Three kernels:
+// dispatch tables.  The analysis runs either fused behind the gate projection or as
+// the stand-alone kernel below; the tail kernel holds the chain and the finishing
+// pass:
 //
 //   analyse  (parallel over tokens)  everything about a token that does not
 //            depend on the load counters: scores, descending order statistics,
@@ -70,11 +72,16 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
   return hipGetLastError();
 }
 
-// ----------------------------------------------------------------- chain -----
+// ------------------------------------------------------------------ tail -----
 //
-// One workgroup of 16 wavefronts.
+// One kernel after the analysis: workgroup 0 is the chain, every other workgroup
+// finishes 4 tiles (one wavefront each).
+//
+// Chain workgroup (4 wavefronts):
 //   prefix  (all waves)  exclusive prefix over tiles of the fixed tokens' per-expert
 //           counts -> tile_base; ordered list of the tiles that hold flexible tokens.
+//           Then flag 1 is published: tile_base is final for every tile if no tile
+//           holds a flexible token.
 //   chain   (wave 0, lane e = expert e)  walks the flexible tiles in order.  The
 //           counters a flexible token sees are loads_in + fixed prefix of its tile
 //           + fixed tokens before it inside the tile (carried by its record) +
@@ -82,17 +89,31 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
 //           load, ties by score rank.  An expert is chosen iff fewer than k
 //           candidate keys are smaller than its own; the candidates' keys are
 //           fetched with one lane read each (CP reads per token, CP = c rounded up
-//           to 4, 8 or 16).  Waves 1..12 copy the next batch of records into LDS
+//           to 4, 8 or 16).  Waves 1..3 copy the next batch of records into LDS
 //           meanwhile, so the chain never waits on memory.
 //   fix-up  (all waves)  tiles without flexible tokens add the flexible choices
-//           made before them to their tile_base.
+//           made before them to their tile_base.  Loads, offsets, then flag 2.
+//   Output of the chain: for every flexible tile and expert, one bit per flexible
+//   token of the tile (bit r of word r/32: chosen for the tile's r-th flexible token).
 //
-// Output of the chain: for every flexible tile and expert, one bit per flexible
-// token of the tile (bit r of word r/32: chosen for the tile's r-th flexible token).
+// Finishing wavefront (lane = token of its tile): loads what does not depend on the
+// chain, waits for flag 1 (and for flag 2 if any tile holds flexible tokens), then
+// gives flexible tokens their experts (in score order) and weights from the chain's
+// bits and places every assignment slot t*k+j at
+//   expert_offsets[e] + (assignments to e in earlier tiles) + (earlier tokens of
+//   this tile assigned to e),
+// which is the stable counting sort of the flat expert_ids array.
+//
+// The waits are bounded polls of flags that the analysis kernel of the same call
+// cleared; workgroup 0 has the lowest index, is dispatched first and never waits,
+// so the polls end.  A poll that runs out sets ws.status[kStatusError] and the wave
+// leaves without writing.
 
-constexpr int kChainWaves = 16;
-constexpr int kChainThreads = kChainWaves * 64;
-constexpr int kChainBatch = 6;  // flexible tiles per LDS batch
+constexpr int kChainWaves = 4;
+constexpr int kTailThreads = kChainWaves * 64;
+constexpr int kChainBatch = 3;  // flexible tiles per LDS batch
+constexpr int kSpinLimit = 1 << 22;
+constexpr int kSelfPrefixTiles = 1024;  // up to here finishing workgroups sum the counts themselves
 
 struct ChainBatch {
   int tile[kChainBatch];
@@ -104,28 +125,44 @@ struct ChainBatch {
 constexpr int kChainLdsBytes = 2 * (int)sizeof(ChainBatch);
 constexpr int kChainStageTiles = kChainLdsBytes / 64;  // tiles of byte counts that fit the LDS
 
+// Data published by the chain workgroup is read with agent-scope atomic loads: they
+// see what the publisher wrote back before raising the flag, without the reader
+// having to invalidate its whole L2 (the chain may run on another XCD).
+__device__ __forceinline__ int load_published(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned load_published(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ bool poll_flag(const int* flag, int want) {
+  for (int it = 0; it < kSpinLimit; ++it) {
+    const int seen = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (seen >= want) return true;
+    __builtin_amdgcn_s_sleep(4);
+  }
+  return false;
+}
+
 __device__ void chain_prefetch(ChainBatch* dst, int batch, int nflex_tiles, const RouteArgs& a,
                                const Workspace& ws, int hwave, int lane) {
-  // two helper waves per tile of the batch
-  const int tl = hwave >> 1;
-  const int part = hwave & 1;
-  if (tl >= kChainBatch) return;
-  const int f = batch * kChainBatch + tl;
-  if (f >= nflex_tiles) return;
-  const int tile = ws.flex_list[f];
-  const int n = __builtin_popcountll(ws.flexmask[tile]);
-  if (part == 0) {
+  for (int tl = hwave; tl < kChainBatch; tl += kChainWaves - 1) {
+    const int f = batch * kChainBatch + tl;
+    if (f >= nflex_tiles) return;
+    const int tile = ws.flex_list[f];
+    const int n = __builtin_popcountll(ws.flexmask[tile]);
     if (lane == 0) {
       dst->tile[tl] = tile;
       dst->nflex[tl] = n;
     }
     dst->base[tl][lane] = ws.tile_base[(size_t)tile * 64 + lane];
     if (lane < n) dst->cids[tl][lane] = reinterpret_cast<const uint4*>(ws.rec_cids)[(size_t)tile * kTile + lane];
+    const int words = (n * a.EP) >> 1;  // EP is even
+    const unsigned* src = reinterpret_cast<const unsigned*>(ws.rec_lane + (size_t)tile * kTile * a.EP);
+    unsigned* d32 = reinterpret_cast<unsigned*>(dst->rec[tl]);
+    for (int wd = lane; wd < words; wd += 64) d32[wd] = src[wd];
   }
-  const int words = (n * a.EP) >> 1;  // EP is even
-  const unsigned* src = reinterpret_cast<const unsigned*>(ws.rec_lane + (size_t)tile * kTile * a.EP);
-  unsigned* d32 = reinterpret_cast<unsigned*>(dst->rec[tl]);
-  for (int wd = part * 64 + lane; wd < words; wd += 128) d32[wd] = src[wd];
 }
 
 // One flexible token: returns whether this lane's expert is chosen.
@@ -203,42 +240,80 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int nflex_tiles, con
   }
 }
 
-__global__ __launch_bounds__(kChainThreads) void chain_kernel(const RouteArgs a, const Workspace ws,
-                                                              int32_t* __restrict__ loads_inout,
-                                                              int32_t* __restrict__ expert_offsets) {
-  extern __shared__ __align__(16) uint8_t chain_lds[];
-  ChainBatch* buf = reinterpret_cast<ChainBatch*>(chain_lds);
+__device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
+                                int32_t* __restrict__ loads_inout,
+                                int32_t* __restrict__ expert_offsets) {
+  ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
   __shared__ int wave_flex[kChainWaves];
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
 
+  // Everything the workgroup reads first is requested before anything is consumed:
+  // the counters, the first super-batch of byte counts, the flexible-tile masks.
+  int lin = 0;
+  if (lane < a.E) lin = loads_inout[lane];
+  uint8_t* stage = lds;
+  uint4 sv[8];  // 8 loads in flight per thread
+  auto stage_load = [&](int sb0, int i0) {
+    const int nt = min(kChainStageTiles, ntiles - sb0);
+    const uint4* src = reinterpret_cast<const uint4*>(ws.tile_fixed_cnt + (size_t)sb0 * 64);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * kTailThreads;
+      sv[u] = i < nt * 4 ? src[i] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto stage_store = [&](int sb0, int i0) {
+    const int nt = min(kChainStageTiles, ntiles - sb0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * kTailThreads;
+      if (i < nt * 4) reinterpret_cast<uint4*>(stage)[i] = sv[u];
+    }
+  };
+  if (ntiles > 0) stage_load(0, threadIdx.x);
+
   // ---- which tiles hold flexible tokens (groups of 64 tiles per ballot) ------
   const int groups = (ntiles + 63) >> 6;
   const int gper = (groups + kChainWaves - 1) / kChainWaves;
   const int ga = min(wave * gper, groups), gb = min(ga + gper, groups);
   int nfl = 0;
+  bool first_flex = false;  // this lane's tile of the wave's first group (kept for the second pass)
   for (int g = ga; g < gb; ++g) {
     const int tile = g * 64 + lane;
     const bool f = tile < ntiles && ws.flexmask[tile] != 0ull;
+    if (g == ga) first_flex = f;
     nfl += __builtin_popcountll(__builtin_amdgcn_ballot_w64(f));
   }
   if (lane == 0) wave_flex[wave] = nfl;
+  __syncthreads();
+  int fbefore = 0, nflex_tiles = 0;
+  for (int w = 0; w < kChainWaves; ++w) {
+    const int fl = wave_flex[w];
+    fbefore += w < wave ? fl : 0;
+    nflex_tiles += fl;
+  }
+  // Without flexible tokens, small problems are finished without tile_base (the
+  // finishing workgroups sum the byte counts themselves): only the totals are needed.
+  const bool need_tile_base = nflex_tiles > 0 || ntiles > kSelfPrefixTiles;
 
   // ---- prefix over tiles of the fixed tokens' counts -------------------------
-  // The byte counts are staged through LDS in super-batches with one wide load per
-  // thread; wave w then scans a contiguous run of tiles for its lane's expert.
+  // The byte counts are staged through LDS in super-batches with wide loads; wave
+  // w then scans a contiguous run of tiles for its lane's expert.
   int carry = 0;  // fixed assignments in earlier super-batches (lane's expert)
-  uint8_t* stage = chain_lds;
   for (int sb0 = 0; sb0 < ntiles; sb0 += kChainStageTiles) {
     const int nt = min(kChainStageTiles, ntiles - sb0);
-    const uint4* src = reinterpret_cast<const uint4*>(ws.tile_fixed_cnt + (size_t)sb0 * 64);
-    for (int i = threadIdx.x; i < nt * 4; i += kChainThreads) reinterpret_cast<uint4*>(stage)[i] = src[i];
+    for (int i0 = threadIdx.x; i0 < nt * 4; i0 += kTailThreads * 8) {
+      if (sb0 != 0 || i0 != (int)threadIdx.x) stage_load(sb0, i0);  // the very first batch is in flight
+      stage_store(sb0, i0);
+    }
     __syncthreads();
     const int per_wave = (nt + kChainWaves - 1) / kChainWaves;
     const int ta = min(wave * per_wave, nt), tb = min(ta + per_wave, nt);
     int tot = 0;
+#pragma unroll 16
     for (int tile = ta; tile < tb; ++tile) tot += stage[tile * 64 + lane];
     wave_tot[wave][lane] = tot;
     __syncthreads();
@@ -248,58 +323,32 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(const RouteArgs a,
       run += w < wave ? v : 0;
       carry += v;
     }
-    for (int tile = ta; tile < tb; ++tile) {
-      ws.tile_base[(size_t)(sb0 + tile) * 64 + lane] = run;
-      run += stage[tile * 64 + lane];
+    if (need_tile_base) {
+#pragma unroll 16
+      for (int tile = ta; tile < tb; ++tile) {
+        ws.tile_base[(size_t)(sb0 + tile) * 64 + lane] = run;
+        run += stage[tile * 64 + lane];
+      }
     }
     __syncthreads();  // stage and wave_tot are reused by the next super-batch
   }
   const int total_fixed = carry;
-  if (ntiles == 0) __syncthreads();  // wave_flex visible even when the loop above did not run
 
-  int fbefore = 0, nflex_tiles = 0;
-  for (int w = 0; w < kChainWaves; ++w) {
-    const int fl = wave_flex[w];
-    fbefore += w < wave ? fl : 0;
-    nflex_tiles += fl;
-  }
-  for (int g = ga; g < gb; ++g) {
+  for (int g = ga; g < gb && nflex_tiles > 0; ++g) {
     const int tile = g * 64 + lane;
-    const bool f = tile < ntiles && ws.flexmask[tile] != 0ull;
+    const bool f = g == ga ? first_flex : (tile < ntiles && ws.flexmask[tile] != 0ull);
     const unsigned long long bal = __builtin_amdgcn_ballot_w64(f);
     const int ord = fbefore + __builtin_popcountll(bal & lanes_below(lane));
     if (tile < ntiles) ws.flex_ord[tile] = ord;
     if (f) ws.flex_list[ord] = tile;
     fbefore += __builtin_popcountll(bal);
   }
-  __syncthreads();  // tile_base, flex_list, flex_ord visible to the whole workgroup
 
-  int lin = 0;
-  if (lane < a.E) lin = loads_inout[lane];
   int gflex = 0;  // flexible assignments so far (meaningful in wave 0)
 
-  if (nflex_tiles > 0) {
-    if (a.c <= 4)
-      chain_walk<4>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
-    else if (a.c <= 8)
-      chain_walk<8>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
-    else
-      chain_walk<16>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
-    // tiles without flexible tokens: add the flexible choices made before them
-    const long long total = (long long)ntiles * 64;
-    for (long long idx = threadIdx.x; idx < total; idx += kChainThreads) {
-      const int tile = (int)(idx >> 6);
-      if (ws.flexmask[tile] == 0ull) {
-        const int ord = ws.flex_ord[tile];
-        if (ord > 0) ws.tile_base[idx] += ws.gsnap[(size_t)(ord - 1) * 64 + (idx & 63)];
-      }
-    }
-  }
-
-  if (wave == 0) {
+  auto write_totals = [&]() {  // wave 0: final loads and the exclusive prefix over experts
     const int cnt = lane < a.E ? total_fixed + gflex : 0;
     if (lane < a.E) loads_inout[lane] = lin + cnt;
-    // exclusive prefix sums of the per-expert assignment counts
     int incl = cnt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -308,58 +357,100 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(const RouteArgs a,
     }
     if (lane < a.E) expert_offsets[lane] = incl - cnt;
     if (lane == a.E - 1) expert_offsets[a.E] = incl;
+  };
+
+  if (nflex_tiles == 0 && wave == 0) write_totals();  // already final
+  __syncthreads();  // tile_base, flex_list, flex_ord (and the totals) written by every wave
+  if (threadIdx.x == 0) {
+    ws.status[kStatusFlexTiles] = nflex_tiles;
+    __hip_atomic_store(&ws.status[kStatusPhase], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
   }
+  if (nflex_tiles == 0) return;
+
+  if (a.c <= 4)
+    chain_walk<4>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+  else if (a.c <= 8)
+    chain_walk<8>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+  else
+    chain_walk<16>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+  // tiles without flexible tokens: add the flexible choices made before them
+  const long long total = (long long)ntiles * 64;
+  for (long long idx = threadIdx.x; idx < total; idx += kTailThreads) {
+    const int tile = (int)(idx >> 6);
+    if (ws.flexmask[tile] == 0ull) {
+      const int ord = ws.flex_ord[tile];
+      if (ord > 0) ws.tile_base[idx] += ws.gsnap[(size_t)(ord - 1) * 64 + (idx & 63)];
+    }
+  }
+  if (wave == 0) write_totals();
+  __syncthreads();
+  if (threadIdx.x == 0)
+    __hip_atomic_store(&ws.status[kStatusPhase], 2, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_chain(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
-                        int32_t* expert_offsets, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(chain_kernel, dim3(1), dim3(kChainThreads), kChainLdsBytes, s, a, ws,
-                     loads_inout, expert_offsets);
-  return hipGetLastError();
+struct FinishLds {
+  unsigned long long mask64[64];
+  uint8_t ids[kTile][kMaxC];
+};
+
+// One wavefront, one tile; `fl` is this wave's private LDS.
+// If `self` is set the caller has already computed, for every expert, the number of
+// assignments in earlier tiles (own_base, LDS, 64 words) and the exclusive prefix over
+// experts of the totals (own_offsets, LDS, 64 words); nothing is awaited then.
+// What a finishing wave can read before anything else of the tail kernel has run.
+struct FinishPrologue {
+  int cstar;               // working-set size of a flexible token, else 0
+  unsigned long long fm;   // the tile's flexible-token mask
+};
+
+__device__ __forceinline__ FinishPrologue finish_prologue(FinishLds* fl, int tile, const RouteArgs& a,
+                                                          const Workspace& ws,
+                                                          const int32_t* __restrict__ expert_ids) {
+  const int lane = threadIdx.x & 63;
+  const int t = tile * kTile + lane;
+  const bool live = t < a.T;
+  FinishPrologue p;
+  fl->mask64[lane] = 0ull;
+  p.cstar = live ? ws.rec_cstar[t] : 0;
+  p.fm = ws.flexmask[tile];
+  // experts of the tokens that are final already (rows of flexible tokens hold stale data;
+  // they are overwritten in finish_tile)
+  if (live)
+    for (int j = 0; j < a.k; ++j) fl->ids[lane][j] = (uint8_t)expert_ids[(size_t)t * a.k + j];
+  return p;
 }
 
-// ---------------------------------------------------------------- finish -----
-//
-// One wavefront per tile, lane = token.  Flexible tokens get their experts (in
-// score order) and weights from the chain's chosen-expert mask; then every
-// assignment slot t*k+j is placed at
-//   expert_offsets[e] + (assignments to e in earlier tiles) + (earlier tokens of
-//   this tile assigned to e),
-// which is the stable counting sort of the flat expert_ids array.
-
-__global__ __launch_bounds__(64) void finish_kernel(const RouteArgs a, const Workspace ws,
-                                                    const int32_t* __restrict__ expert_offsets,
-                                                    int32_t* __restrict__ expert_ids,
-                                                    float* __restrict__ weights,
-                                                    int32_t* __restrict__ permutation) {
-  __shared__ unsigned long long mask64[64];
-  __shared__ uint8_t ids_lds[kTile][kMaxC];
-  const int tile = blockIdx.x;
-  const int lane = threadIdx.x;
+__device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, const RouteArgs& a,
+                            const Workspace& ws, const int32_t* __restrict__ expert_offsets,
+                            int32_t* __restrict__ expert_ids, float* __restrict__ weights,
+                            int32_t* __restrict__ permutation, bool self, const int* own_base,
+                            const int* own_offsets) {
+  const int lane = threadIdx.x & 63;
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
   const int k = a.k;
-  mask64[lane] = 0ull;
+  const int cstar = pro.cstar;
+  const unsigned long long fm = pro.fm;
 
-  const int cstar = live ? ws.rec_cstar[t] : 0;
+  if (!self) {
+    if (!poll_flag(&ws.status[kStatusPhase], 1)) {
+      ws.status[kStatusError] = 1;
+      return;
+    }
+    if (load_published(&ws.status[kStatusFlexTiles]) > 0 && !poll_flag(&ws.status[kStatusPhase], 2)) {
+      ws.status[kStatusError] = 1;
+      return;
+    }
+  }
+
   if (cstar > 0) {
-    const unsigned long long fm = ws.flexmask[tile];
-    const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(lane));
-    const int r = slot - tile * kTile;
+    const int r = __builtin_popcountll(fm & lanes_below(lane));
     const unsigned* cw = ws.chain_out + ((size_t)tile * 2 + (r >> 5)) * 64;
-    unsigned long long chosen = 0ull;
-    for (int j = 0; j < cstar; ++j)
-      chosen |= (unsigned long long)((cw[ws.rec_ids[(size_t)t * 16 + j]] >> (r & 31)) & 1u)
-                << ws.rec_ids[(size_t)t * 16 + j];
     const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
     const float* pv = ws.rec_p + (size_t)t * 16;
+    unsigned long long chosen = 0ull;
+    for (int j = 0; j < cstar; ++j)
+      chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (r & 31)) & 1u) << ids[j];
     float denom = 0.0f;
     if (a.renormalize) {
       bool first = true;
@@ -378,34 +469,166 @@ __global__ __launch_bounds__(64) void finish_kernel(const RouteArgs a, const Wor
       if ((chosen >> e) & 1ull) {
         expert_ids[(size_t)t * k + n] = e;
         weights[(size_t)t * k + n] = pv[j] / denom;
-        ids_lds[lane][n] = (uint8_t)e;
+        fl->ids[lane][n] = (uint8_t)e;
         ++n;
       }
     }
-  } else if (live) {
-    for (int j = 0; j < k; ++j) ids_lds[lane][j] = (uint8_t)expert_ids[(size_t)t * k + j];
   }
-  __syncthreads();
+  // LDS traffic of one wavefront is processed in order; the fences only stop the
+  // compiler from moving reads above the other lanes' writes
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
   if (live)
-    for (int j = 0; j < k; ++j) atomicOr(&mask64[ids_lds[lane][j]], 1ull << lane);
-  __syncthreads();
+    for (int j = 0; j < k; ++j) atomicOr(&fl->mask64[fl->ids[lane][j]], 1ull << lane);
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
   if (live) {
     const unsigned long long below = lanes_below(lane);
     for (int j = 0; j < k; ++j) {
-      const int e = ids_lds[lane][j];
-      const int pos = expert_offsets[e] + ws.tile_base[(size_t)tile * 64 + e] +
-                      __builtin_popcountll(mask64[e] & below);
+      const int e = fl->ids[lane][j];
+      const int before = self ? own_offsets[e] + own_base[e]
+                              : load_published(&expert_offsets[e]) +
+                                    load_published(&ws.tile_base[(size_t)tile * 64 + e]);
+      const int pos = before + __builtin_popcountll(fl->mask64[e] & below);
       permutation[pos] = t * k + j;
     }
   }
 }
 
-hipError_t launch_finish(const RouteArgs& a, const Workspace& ws, const int32_t* expert_offsets,
-                         int32_t* expert_ids, float* weights, int32_t* permutation,
-                         hipStream_t s) {
-  if (a.ntiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(finish_kernel, dim3(a.ntiles), dim3(64), 0, s, a, ws, expert_offsets,
-                     expert_ids, weights, permutation);
+// Per-expert assignment counts of the tiles before `t0` and of all tiles, summed by
+// the whole workgroup straight from the analysis kernel's byte counts.  Only valid
+// when no tile holds a flexible token (then the fixed counts are all there is).
+// Lane l of a load takes experts 4*(l%16)..+3 of tile 4*j + l/16; bytes are
+// accumulated pairwise in 16-bit fields (at most 64 per tile, ntiles <= 1024).
+__device__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int (*sh_before)[64],
+                            int (*sh_all)[64], int* sh_anyflex) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ntiles = a.ntiles;
+  const int sub = lane >> 4;  // which of the 4 tiles of a load
+  const unsigned* cnt32 = reinterpret_cast<const unsigned*>(ws.tile_fixed_cnt);
+  unsigned b02 = 0, b13 = 0, a02 = 0, a13 = 0;
+  // flexible-tile masks first (ntiles <= kSelfPrefixTiles: at most 4 per thread), so that
+  // their latency overlaps the count loads
+  unsigned long long fmv[kSelfPrefixTiles / kTailThreads];
+#pragma unroll
+  for (int u = 0; u < kSelfPrefixTiles / kTailThreads; ++u) {
+    const int i = threadIdx.x + u * kTailThreads;
+    fmv[u] = i < ntiles ? ws.flexmask[i] : 0ull;
+  }
+  const int nload = (ntiles + 3) >> 2;
+  constexpr int kBatch = 16;  // loads issued together: the loop is bound by latency, not by volume
+  for (int j0 = wave; j0 < nload; j0 += kChainWaves * kBatch) {
+    unsigned wd[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int tile = 4 * (j0 + u * kChainWaves) + sub;
+      wd[u] = tile < ntiles ? cnt32[(size_t)tile * 16 + (lane & 15)] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int tile = 4 * (j0 + u * kChainWaves) + sub;
+      const unsigned lo = wd[u] & 0x00FF00FFu, hi = (wd[u] >> 8) & 0x00FF00FFu;
+      a02 += lo;
+      a13 += hi;
+      b02 += tile < t0 ? lo : 0u;
+      b13 += tile < t0 ? hi : 0u;
+    }
+  }
+  // fold the 4 tile sub-groups of the wave (lanes l, l+16, l+32, l+48)
+#pragma unroll
+  for (int d = 16; d < 64; d <<= 1) {
+    a02 += __shfl_xor(a02, d, 64);
+    a13 += __shfl_xor(a13, d, 64);
+    b02 += __shfl_xor(b02, d, 64);
+    b13 += __shfl_xor(b13, d, 64);
+  }
+  if (lane < 16) {
+    const int e = 4 * lane;
+    sh_all[wave][e] = a02 & 0xFFFF;
+    sh_all[wave][e + 1] = a13 & 0xFFFF;
+    sh_all[wave][e + 2] = a02 >> 16;
+    sh_all[wave][e + 3] = a13 >> 16;
+    sh_before[wave][e] = b02 & 0xFFFF;
+    sh_before[wave][e + 1] = b13 & 0xFFFF;
+    sh_before[wave][e + 2] = b02 >> 16;
+    sh_before[wave][e + 3] = b13 >> 16;
+  }
+  bool flex = false;
+#pragma unroll
+  for (int u = 0; u < kSelfPrefixTiles / kTailThreads; ++u) flex |= fmv[u] != 0ull;
+  if (__builtin_amdgcn_ballot_w64(flex) != 0ull && lane == 0) *sh_anyflex = 1;
+}
+
+__global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, const Workspace ws,
+                                                            int32_t* __restrict__ loads_inout,
+                                                            int32_t* __restrict__ expert_offsets,
+                                                            int32_t* __restrict__ expert_ids,
+                                                            float* __restrict__ weights,
+                                                            int32_t* __restrict__ permutation) {
+  extern __shared__ __align__(16) uint8_t tail_lds[];
+  if (blockIdx.x == 0) {
+    chain_workgroup(tail_lds, a, ws, loads_inout, expert_offsets);
+    return;
+  }
+  __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
+  __shared__ int own_base[kChainWaves][64], own_offsets[64];
+  __shared__ int sh_anyflex;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t0 = (blockIdx.x - 1) * kChainWaves;
+  const int tile = t0 + wave;
+  // Small problems without flexible tokens need nothing from the chain workgroup:
+  // every finishing workgroup sums the byte counts itself.
+  FinishLds* fl = reinterpret_cast<FinishLds*>(tail_lds) + wave;
+  FinishPrologue pro = {0, 0ull};
+  if (tile < a.ntiles) pro = finish_prologue(fl, tile, a, ws, expert_ids);  // loads overlap the sums below
+  bool self = false;
+  if (a.ntiles <= kSelfPrefixTiles) {
+    if (threadIdx.x == 0) sh_anyflex = 0;
+    __syncthreads();
+    self_prefix(t0, a, ws, sh_before, sh_all, &sh_anyflex);
+    __syncthreads();
+    self = sh_anyflex == 0;
+    if (self) {
+      int before = 0, all = 0;
+      for (int w = 0; w < kChainWaves; ++w) {
+        before += sh_before[w][lane];
+        all += sh_all[w][lane];
+      }
+      // this wave's tile: add the workgroup's earlier tiles
+      for (int j = 0; j < wave; ++j)
+        if (t0 + j < a.ntiles) before += ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane];
+      own_base[wave][lane] = before;
+      if (wave == 0) {
+        int incl = lane < a.E ? all : 0;
+        const int cnt = incl;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const int up = __shfl_up(incl, d, 64);
+          if (lane >= d) incl += up;
+        }
+        own_offsets[lane] = incl - cnt;
+      }
+    }
+    __syncthreads();
+  }
+  if (tile >= a.ntiles) return;
+  finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, self,
+              own_base[wave], own_offsets);
+}
+
+hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                       int32_t* expert_offsets, int32_t* expert_ids, float* weights,
+                       int32_t* permutation, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tail_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int grid = 1 + (a.ntiles + kChainWaves - 1) / kChainWaves;
+  hipLaunchKernelGGL(tail_kernel, dim3(grid), dim3(kTailThreads), kChainLdsBytes, s, a, ws, loads_inout,
+                     expert_offsets, expert_ids, weights, permutation);
   return hipGetLastError();
 }
 
