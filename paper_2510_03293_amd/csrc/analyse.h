@@ -11,6 +11,8 @@
 //   S_k          left-to-right sum of the k largest p in order
 //   top-k branch S_k >= fl(eps_high * Z)
 //   pool member  z_i - z_max >= fl32(ln t_fix)
+// Logits must be finite and above -3.4028234e38 (the value that stands in for
+// experts that do not exist).
 #pragma once
 
 #include "laser_internal.h"
@@ -60,55 +62,102 @@ __device__ __forceinline__ unsigned long long lanes_below(int i) {
 // 256 threads per tile of 64 tokens: 4 lanes per token, lane q of a token owns
 // the experts e = 4*i + q (i < NE).  Strides >= 4 of the Z tree then stay inside
 // a lane and the last two levels are quad exchanges.
+//
+// Order statistics.  Each logit becomes a 64-bit key that sorts, as an IEEE double,
+// exactly like (logit descending, expert ascending): the logit widened to double
+// (exact; the low 29 mantissa bits are free) with 6 tie-break bits in the lowest
+// mantissa bits -- 63 - e for non-negative logits, e for negative ones, because a
+// larger mantissa makes a negative number smaller.  All keys of a token are
+// distinct, so sorting needs nothing but double max/min: a sorting network inside
+// the lane, then two bitonic merges across the quad keep the CT best.  Every lane
+// of the quad ends with the same sorted list; expert and logit are read back from
+// the key.
 
-constexpr int kNegInfBits = 0xff800000;
+constexpr float kLowestLogit = -3.4028234663852886e38f;  // stands in for missing experts
+constexpr double kPadKey = -1.0e300;                      // below every real key
 
-template <int NE>
-__device__ __forceinline__ void extract_round(float (&zw)[NE], int q, float& win_v, int& win_e) {
-  // local best: first maximum in index order
-  float bv = zw[0];
-  int bi = 0;
-#pragma unroll
-  for (int i = 1; i < NE; ++i) {
-    const bool better = zw[i] > bv;
-    bv = better ? zw[i] : bv;
-    bi = better ? i : bi;
-  }
-  int be = 4 * bi + q;
-  // best of the quad under (value desc, expert asc)
-  {
-    const float ov = dpp_float<kQuadXor1>(bv);
-    const int oe = dpp_int<kQuadXor1>(be);
-    const bool take = (ov > bv) || (ov == bv && oe < be);
-    bv = take ? ov : bv;
-    be = take ? oe : be;
-  }
-  {
-    const float ov = dpp_float<kQuadXor2>(bv);
-    const int oe = dpp_int<kQuadXor2>(be);
-    const bool take = (ov > bv) || (ov == bv && oe < be);
-    bv = take ? ov : bv;
-    be = take ? oe : be;
-  }
-  win_v = bv;
-  win_e = be;
-  // the owner strikes the winner out
-  const bool owner = (be & 3) == q;
-  const int wi = be >> 2;
-#pragma unroll
-  for (int i = 0; i < NE; ++i)
-    zw[i] = (owner && wi == i) ? __int_as_float(kNegInfBits) : zw[i];
+__device__ __forceinline__ double make_key(float z, int e) {
+  const float zc = z + 0.0f;  // -0 -> +0: equal logits must give equal high parts
+  const int m = __float_as_int(zc) >> 31;  // 0 or -1
+  const unsigned code = ((unsigned)(e ^ 63) ^ (unsigned)m) & 63u;
+  return __longlong_as_double(__double_as_longlong((double)zc) | (long long)code);
 }
+__device__ __forceinline__ int key_expert(double key) {
+  const long long b = __double_as_longlong(key);
+  const int m = (int)(b >> 32) >> 31;
+  return ~((int)b ^ m) & 63;
+}
+__device__ __forceinline__ float key_logit(double key) {
+  return (float)__longlong_as_double(__double_as_longlong(key) & ~63LL);
+}
+__device__ __forceinline__ void order_pair(double& hi, double& lo) {
+  const double a = __builtin_fmax(hi, lo), b = __builtin_fmin(hi, lo);
+  hi = a;
+  lo = b;
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_double(double v) {
+  const long long b = __double_as_longlong(v);
+  const unsigned lo = (unsigned)dpp_int<CTRL>((int)b);
+  const unsigned hi = (unsigned)dpp_int<CTRL>((int)(b >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Batcher's odd-even merge sort for N = 2^m inputs as a list of compare-exchanges.
+template <int N>
+struct SortNet {
+  int a[N * N], b[N * N], n;
+};
+template <int N>
+constexpr SortNet<N> make_sort_net() {
+  SortNet<N> r{};
+  r.n = 0;
+  for (int p = 1; p < N; p *= 2)
+    for (int k = p; k >= 1; k /= 2)
+      for (int j = k % p; j + k < N; j += 2 * k)
+        for (int i = 0; i < k && i + j + k < N; ++i)
+          if ((i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+            r.a[r.n] = i + j;
+            r.b[r.n] = i + j + k;
+            ++r.n;
+          }
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void sort_descending(double (&K)[N]) {
+  constexpr SortNet<N> net = make_sort_net<N>();
+#pragma unroll
+  for (int i = 0; i < net.n; ++i) order_pair(K[net.a[i]], K[net.b[i]]);
+}
+// L: sorted descending.  Afterwards: the CT largest of L and of the partner lane's L,
+// sorted descending (the same list in both lanes).
+template <int CT, int CTRL>
+__device__ __forceinline__ void merge_with_partner(double (&L)[CT]) {
+  double M[CT];
+#pragma unroll
+  for (int i = 0; i < CT; ++i) M[i] = __builtin_fmax(L[i], dpp_double<CTRL>(L[CT - 1 - i]));
+#pragma unroll
+  for (int stride = CT / 2; stride >= 1; stride /= 2)
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+      if ((i & stride) == 0) order_pair(M[i], M[i + stride]);
+#pragma unroll
+  for (int i = 0; i < CT; ++i) L[i] = M[i];
+}
+
+__device__ __forceinline__ float clamp_exp_arg(float d) { return d < -80.0f ? -80.0f : d; }
 
 // lz: NP partial logit tiles in LDS, [NP][kTile rows][zs floats]; a token's logit is
 // the sum of its NP partials in the order ((p0 + p1) + p2) + p3.  mask64 (64 words)
 // and flex_lds (1 word) are LDS scratch.  logits_out (global, may be NULL) receives
-// the summed logits.  Must be called by all 256 threads of the workgroup.
-template <int NE, int NP>
-__device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long long* mask64,
-                             unsigned long long* flex_lds, int tile, const RouteArgs a,
-                             const Workspace ws, int32_t* __restrict__ expert_ids,
-                             float* __restrict__ weights, float* __restrict__ logits_out) {
+// the summed logits.  CT (8 or 16) bounds the trimming size c.  Must be called by
+// all 256 threads of the workgroup.
+template <int NE, int NP, int CT>
+__device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned long long* mask64,
+                                unsigned long long* flex_lds, int tile, const RouteArgs a,
+                                const Workspace ws, int32_t* __restrict__ expert_ids,
+                                float* __restrict__ weights, float* __restrict__ logits_out) {
+  constexpr int NS = CT / 4;  // ranks 4*s + q are handled by lane q ("slots")
   const int tid = threadIdx.x;
   const int itok = tid >> 2;
   const int q = tid & 3;
@@ -122,7 +171,8 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
   // kernel earlier on the same stream
   if (tile == 0 && tid < 4) ws.status[tid] = 0;
 
-  float z[NE], zw[NE];
+  float z[NE];
+  double K[NE];
 #pragma unroll
   for (int i = 0; i < NE; ++i) {
     const int e = 4 * i + q;
@@ -131,34 +181,46 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
     for (int pt = 1; pt < NP; ++pt) v = v + lz[pt * kTile * zs + itok * zs + e];
     const bool real = live && e < a.E;
     if (logits_out != nullptr && real) logits_out[(size_t)t * a.E + e] = v;
-    z[i] = real ? v : __int_as_float(kNegInfBits);
-    zw[i] = z[i];
+    z[i] = real ? v : kLowestLogit;
+    K[i] = make_key(z[i], e);
   }
   __syncthreads();  // masks zeroed before anyone ORs into them
 
-  float top_v[kMaxC];
-  int top_e[kMaxC];
+  // ---- the CT best of the token, sorted, in every lane of its quad -----------
+  sort_descending<NE>(K);
+  double L[CT];
 #pragma unroll
-  for (int j = 0; j < kMaxC; ++j) {
-    top_v[j] = 0.0f;
-    top_e[j] = 0;
-  }
+  for (int i = 0; i < CT; ++i) L[i] = i < NE ? K[i < NE ? i : 0] : kPadKey;
+  merge_with_partner<CT, kQuadXor1>(L);
+  merge_with_partner<CT, kQuadXor2>(L);
+
+  const float zmax = key_logit(L[0]);
+  // this lane's slots: rank 4*s + q
+  int my_e[NS];
+  float my_d[NS], my_p[NS];
 #pragma unroll
-  for (int j = 0; j < kMaxC; ++j) {
-    if (j < k) extract_round<NE>(zw, q, top_v[j], top_e[j]);
+  for (int s = 0; s < NS; ++s) {
+    // (the empty asm keeps the compiler from turning the selects into an indexed
+    // access of L, which would move the whole list to scratch memory)
+    double s0 = L[4 * s], s1 = L[4 * s + 1], s2 = L[4 * s + 2], s3 = L[4 * s + 3];
+    asm volatile("" : "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3));
+    double sel = s0;
+    sel = q == 1 ? s1 : sel;
+    sel = q == 2 ? s2 : sel;
+    sel = q == 3 ? s3 : sel;
+    my_e[s] = key_expert(sel);
+    my_d[s] = key_logit(sel) - zmax;
+    my_p[s] = exp_fixed(clamp_exp_arg(my_d[s]));
   }
 
-  const float zmax = top_v[0];
+  // ---- softmax normaliser over all experts ------------------------------------
   float p[NE];
-  int npool = 0;
 #pragma unroll
   for (int i = 0; i < NE; ++i) {
     const int e = 4 * i + q;
-    const float d = z[i] - zmax;
-    npool += (d >= a.tau_ln) ? 1 : 0;  // -inf padding never qualifies
-    p[i] = (e < a.E) ? exp_fixed(d < -80.0f ? -80.0f : d) : 0.0f;
+    p[i] = (e < a.E) ? exp_fixed(clamp_exp_arg(z[i] - zmax)) : 0.0f;
   }
-  // Z: in-lane levels (expert stride 4*s), then quad levels (stride 2, stride 1)
+  // in-lane levels (expert stride 4*s), then quad levels (stride 2, stride 1)
 #pragma unroll
   for (int s = NE / 2; s >= 1; s >>= 1)
 #pragma unroll
@@ -171,48 +233,46 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
     zsum = zsum + other1;                             // valid in lane 0
     zsum = dpp_float<kQuadBcast0>(zsum);
   }
-  npool += dpp_int<kQuadXor1>(npool);
-  npool += dpp_int<kQuadXor2>(npool);
 
-  float ptop[kMaxC];
+  // ---- top-k mass, pool size ---------------------------------------------------
+  // p of rank j lives in lane j%4, slot j/4
+  float ptop[CT];
 #pragma unroll
-  for (int j = 0; j < kMaxC; ++j) {
-    ptop[j] = 0.0f;
-    if (j < k) {
-      const float d = top_v[j] - zmax;
-      ptop[j] = exp_fixed(d < -80.0f ? -80.0f : d);
-    }
+  for (int j = 0; j < CT; ++j) {
+    const float src = my_p[j >> 2];
+    ptop[j] = (j & 3) == 0   ? dpp_float<0x00>(src)
+              : (j & 3) == 1 ? dpp_float<0x55>(src)
+              : (j & 3) == 2 ? dpp_float<0xAA>(src)
+                             : dpp_float<0xFF>(src);
   }
   float sk = ptop[0];
 #pragma unroll
-  for (int j = 1; j < kMaxC; ++j)
+  for (int j = 1; j < CT; ++j)
     if (j < k) sk = sk + ptop[j];
-
   const bool mass_ok = sk >= a.eps_high * zsum;
-  const int m = npool > k ? npool : k;
-  const int cstar = c < m ? c : m;
+  // the pool is a prefix of the order, so its size beyond k is the number of ranks in
+  // [k, c) that pass the cut
+  int extra = 0;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const int j = 4 * s + q;
+    extra += (j >= k && j < c && my_d[s] >= a.tau_ln) ? 1 : 0;
+  }
+  extra += dpp_int<kQuadXor1>(extra);
+  extra += dpp_int<kQuadXor2>(extra);
+  const int cstar = k + extra;
   const bool flex = live && !mass_ok && cstar > k;
 
-  // the rest of the order statistics, only where some token of the wave needs them
-  if (__builtin_amdgcn_ballot_w64(flex) != 0ull) {
-#pragma unroll
-    for (int j = 1; j < kMaxC; ++j) {
-      if (j >= k && j < c) {
-        extract_round<NE>(zw, q, top_v[j], top_e[j]);
-        const float d = top_v[j] - zmax;
-        ptop[j] = exp_fixed(d < -80.0f ? -80.0f : d);
-      }
-    }
-  }
-
+  // ---- tokens whose experts are final: outputs, per-expert masks ----------------
   if (live && !flex) {
     const float denom = a.renormalize ? sk : zsum;
 #pragma unroll
-    for (int j = 0; j < kMaxC; ++j) {
-      if (j < k && (j & 3) == q) {
-        expert_ids[(size_t)t * k + j] = top_e[j];
-        weights[(size_t)t * k + j] = ptop[j] / denom;
-        atomicOr(&mask64[top_e[j]], 1ull << itok);
+    for (int s = 0; s < NS; ++s) {
+      const int j = 4 * s + q;
+      if (j < k) {
+        expert_ids[(size_t)t * k + j] = my_e[s];
+        weights[(size_t)t * k + j] = my_p[s] / denom;
+        atomicOr(&mask64[my_e[s]], 1ull << itok);
       }
     }
   }
@@ -228,50 +288,67 @@ __device__ void analyse_tile(const float* __restrict__ lz, int zs, unsigned long
   const unsigned long long fm = *flex_lds;
   if (tid == 0) ws.flexmask[tile] = fm;
 
-  if (flex) {
-    const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(itok));
-    // ranks 4q..4q+3 of the ordered list go out through lane q
-    unsigned idw = 0;
-    float pv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  // ---- records of the flexible tokens (rare or chain-bound: not tuned) ----------
+  if (__builtin_amdgcn_ballot_w64(flex) != 0ull) {
+    int top_e[CT];
 #pragma unroll
-    for (int j = 0; j < kMaxC; ++j) {
-      if ((j >> 2) == q) {
-        idw |= (unsigned)top_e[j] << (8 * (j & 3));
-        pv[j & 3] = ptop[j];
+    for (int j = 0; j < CT; ++j) top_e[j] = key_expert(L[j]);
+    if (flex) {
+      const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(itok));
+      // ranks 4q..4q+3 of the ordered list go out through lane q
+      unsigned idw = 0, cidw = 0;
+      float pv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      // the chain reads exactly CP candidate lanes per token: ranks beyond the working
+      // set point at a lane that holds no candidate (its key compares as largest)
+      int padlane = a.E;  // lanes E..63 never hold a candidate
+      if (a.E == 64) {
+        unsigned used = 0;
+#pragma unroll
+        for (int j = 0; j < CT; ++j)
+          if (j < cstar && top_e[j] < 32) used |= 1u << top_e[j];
+        padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        if ((j >> 2) == q) {
+          const int ej = j < CT ? top_e[j < CT ? j : 0] : 0;
+          idw |= (unsigned)ej << (8 * (j & 3));
+          cidw |= (unsigned)(j < cstar ? ej : padlane) << (8 * (j & 3));
+          pv[j & 3] = j < CT ? ptop[j < CT ? j : 0] : 0.0f;
+        }
+      }
+      reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
+      reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
+      reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
+      // per owned expert: rank in the working set and the number of earlier fixed
+      // tokens of this tile assigned to it
+      uint16_t* row = ws.rec_lane + (size_t)slot * a.EP + q * NE;
+      const unsigned long long below = lanes_below(itok);
+#pragma unroll
+      for (int i = 0; i < NE; ++i) {
+        const int e = 4 * i + q;
+        int rank = -1;
+#pragma unroll
+        for (int j = 0; j < CT; ++j)
+          if (j < cstar && top_e[j] == e) rank = j;
+        const int fw = __builtin_popcountll(mask64[e] & below);
+        row[i] = rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF;
       }
     }
-    reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
-    reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
-    // the chain reads exactly CP candidate lanes per token: ranks beyond the working
-    // set point at a lane that holds no candidate (its key compares as largest)
-    int padlane = a.E;  // lanes E..63 never hold a candidate
-    if (a.E == 64) {
-      unsigned used = 0;
-#pragma unroll
-      for (int j = 0; j < kMaxC; ++j)
-        if (j < cstar && top_e[j] < 32) used |= 1u << top_e[j];
-      padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
-    }
-    unsigned cidw = 0;
-#pragma unroll
-    for (int j = 0; j < kMaxC; ++j)
-      if ((j >> 2) == q) cidw |= (unsigned)(j < cstar ? top_e[j] : padlane) << (8 * (j & 3));
-    reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
-    // per owned expert: rank in the working set and the number of earlier fixed
-    // tokens of this tile assigned to it
-    uint16_t* row = ws.rec_lane + (size_t)slot * a.EP + q * NE;
-    const unsigned long long below = lanes_below(itok);
-#pragma unroll
-    for (int i = 0; i < NE; ++i) {
-      const int e = 4 * i + q;
-      int rank = -1;
-#pragma unroll
-      for (int j = 0; j < kMaxC; ++j)
-        if (j < cstar && top_e[j] == e) rank = j;
-      const int fw = __builtin_popcountll(mask64[e] & below);
-      row[i] = rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF;
-    }
   }
+}
+
+template <int NE, int NP>
+__device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int zs,
+                                             unsigned long long* mask64, unsigned long long* flex_lds,
+                                             int tile, const RouteArgs a, const Workspace ws,
+                                             int32_t* __restrict__ expert_ids,
+                                             float* __restrict__ weights,
+                                             float* __restrict__ logits_out) {
+  if (a.c <= 8)
+    analyse_tile_ct<NE, NP, 8>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
+  else
+    analyse_tile_ct<NE, NP, 16>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
 }
 
 }  // namespace laser
