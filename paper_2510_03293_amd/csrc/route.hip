@@ -91,8 +91,9 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
 //           fetched with one lane read each (CP reads per token, CP = c rounded up
 //           to 4, 8 or 16).  Waves 1..3 copy the next batch of records into LDS
 //           meanwhile, so the chain never waits on memory.
-//   fix-up  (all waves)  tiles without flexible tokens add the flexible choices
-//           made before them to their tile_base.  Loads, offsets, then flag 2.
+//   totals  loads and offsets, then flag 2.  (A tile without flexible tokens has only
+//           the fixed prefix in tile_base; its finishing wave adds the flexible
+//           choices made before it, gsnap[flex_ord - 1].)
 //   Output of the chain: for every flexible tile and expert, one bit per flexible
 //   token of the tile (bit r of word r/32: chosen for the tile's r-th flexible token).
 //
@@ -373,15 +374,8 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
     chain_walk<8>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
   else
     chain_walk<16>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
-  // tiles without flexible tokens: add the flexible choices made before them
-  const long long total = (long long)ntiles * 64;
-  for (long long idx = threadIdx.x; idx < total; idx += kTailThreads) {
-    const int tile = (int)(idx >> 6);
-    if (ws.flexmask[tile] == 0ull) {
-      const int ord = ws.flex_ord[tile];
-      if (ord > 0) ws.tile_base[idx] += ws.gsnap[(size_t)(ord - 1) * 64 + (idx & 63)];
-    }
-  }
+  // (tiles without flexible tokens still lack the flexible choices made before them:
+  // their finishing waves add gsnap[flex_ord - 1] themselves)
   if (wave == 0) write_totals();
   __syncthreads();
   if (threadIdx.x == 0)
@@ -432,16 +426,23 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
   const int cstar = pro.cstar;
   const unsigned long long fm = pro.fm;
 
+  bool any_flex = false;
   if (!self) {
     if (!poll_flag(&ws.status[kStatusPhase], 1)) {
       ws.status[kStatusError] = 1;
       return;
     }
-    if (load_published(&ws.status[kStatusFlexTiles]) > 0 && !poll_flag(&ws.status[kStatusPhase], 2)) {
+    any_flex = load_published(&ws.status[kStatusFlexTiles]) > 0;
+    if (any_flex && !poll_flag(&ws.status[kStatusPhase], 2)) {
       ws.status[kStatusError] = 1;
       return;
     }
   }
+
+  // a tile without flexible tokens got only the fixed tokens' prefix as tile_base; the
+  // flexible choices made before it are in gsnap at the end of the previous flexible tile
+  int flex_ord_before = 0;
+  if (!self && fm == 0ull && any_flex) flex_ord_before = load_published(&ws.flex_ord[tile]);
 
   if (cstar > 0) {
     const int r = __builtin_popcountll(fm & lanes_below(lane));
@@ -486,9 +487,15 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     const unsigned long long below = lanes_below(lane);
     for (int j = 0; j < k; ++j) {
       const int e = fl->ids[lane][j];
-      const int before = self ? own_offsets[e] + own_base[e]
-                              : load_published(&expert_offsets[e]) +
-                                    load_published(&ws.tile_base[(size_t)tile * 64 + e]);
+      int before;
+      if (self) {
+        before = own_offsets[e] + own_base[e];
+      } else {
+        before = load_published(&expert_offsets[e]) +
+                 load_published(&ws.tile_base[(size_t)tile * 64 + e]);
+        if (flex_ord_before > 0)  // tile without flexible tokens, after some that have them
+          before += load_published(&ws.gsnap[(size_t)(flex_ord_before - 1) * 64 + e]);
+      }
       const int pos = before + __builtin_popcountll(fl->mask64[e] & below);
       permutation[pos] = t * k + j;
     }
