@@ -24,6 +24,31 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 
+# HBM bytes per launch of the gate kernel from rocprofv3 counters (two --pmc runs,
+# FETCH_SIZE then WRITE_SIZE, KiB per dispatch, each scaled by what the same counter
+# read for a plain 256 MiB device copy in the same run; summary under profiles/).
+# Valid only for the kernel sources they were taken on: the record carries their hash
+# and `traffic` is reported as null once the sources differ.
+PMC_TRAFFIC = {
+    "sources_sha256_16": "0bbd614e7f769d30",
+    "workload": "deepseek",
+    "fetch_kib": 33977.45, "fetch_scale": 1.9997,
+    "write_kib": 872.08, "write_scale": 1.0,
+}
+GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
+
+
+def measured_traffic_bytes(workload):
+    import hashlib
+    h = hashlib.sha256()
+    for rel in GATE_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    if h.hexdigest()[:16] != PMC_TRAFFIC["sources_sha256_16"] or workload != PMC_TRAFFIC["workload"]:
+        return None
+    return (PMC_TRAFFIC["fetch_kib"] * PMC_TRAFFIC["fetch_scale"] +
+            PMC_TRAFFIC["write_kib"] * PMC_TRAFFIC["write_scale"]) * 1024.0
+
 
 def algorithmic_bytes(T, H, E, k, sz):
     """Bytes the method must move per layer: read hidden and the gate matrix once,
@@ -158,7 +183,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(args.workload),
             "kernel": "gate_analyse_bf16_kernel", "avg_launch_us": gate_avg_s * 1e6,
             "algorithmic_bytes_per_launch": gate_bytes,
             "event_pair_overhead_us": event_overhead_s * 1e6,
