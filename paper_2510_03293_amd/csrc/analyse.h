@@ -59,9 +59,9 @@ __device__ __forceinline__ unsigned long long lanes_below(int i) {
 
 // --------------------------------------------------------------- analyse -----
 //
-// 256 threads per tile of 64 tokens: 4 lanes per token, lane q of a token owns
-// the experts e = 4*i + q (i < NE).  Strides >= 4 of the Z tree then stay inside
-// a lane and the last two levels are quad exchanges.
+// 512 threads per tile of 64 tokens: 8 lanes per token, lane q of a token owns
+// the experts e = 8*i + q (i < NE).  Strides >= 8 of the Z tree then stay inside
+// a lane and the last three levels are exchanges inside the 8-lane group.
 //
 // Order statistics.  Each logit becomes a 64-bit key that sorts, as an IEEE double,
 // exactly like (logit descending, expert ascending): the logit widened to double
@@ -69,9 +69,9 @@ __device__ __forceinline__ unsigned long long lanes_below(int i) {
 // mantissa bits -- 63 - e for non-negative logits, e for negative ones, because a
 // larger mantissa makes a negative number smaller.  All keys of a token are
 // distinct, so sorting needs nothing but double max/min: a sorting network inside
-// the lane, then two bitonic merges across the quad keep the CT best.  Every lane
-// of the quad ends with the same sorted list; expert and logit are read back from
-// the key.
+// the lane, then three bitonic merges across the group (partners 7-l, l^1, l^2)
+// keep the CT best.  Every lane of the group ends with the same sorted list; expert
+// and logit are read back from the key.
 
 constexpr float kLowestLogit = -3.4028234663852886e38f;  // stands in for missing experts
 constexpr double kPadKey = -1.0e300;                      // below every real key
@@ -147,20 +147,42 @@ __device__ __forceinline__ void merge_with_partner(double (&L)[CT]) {
 
 __device__ __forceinline__ float clamp_exp_arg(float d) { return d < -80.0f ? -80.0f : d; }
 
+// DPP controls
+constexpr int kRowShl4 = 0x104, kRowShr4 = 0x114, kRowShr1 = 0x111, kRowShl7 = 0x107;
+constexpr int kRowHalfMirror = 0x141;
+
+// value of lane `src` (0..7) of this lane's 8-lane group
+__device__ __forceinline__ float group_read(float v, int src) {
+  const int lane = threadIdx.x & 63;
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(((lane & ~7) | src) << 2, __float_as_int(v)));
+}
+// lane 0 of the group -> all 8 lanes
+__device__ __forceinline__ float group_bcast0(float v, int q) {
+  const float lo = dpp_float<kQuadBcast0>(v);
+  const float hi = dpp_float<kRowShr4>(lo);
+  return q < 4 ? lo : hi;
+}
+__device__ __forceinline__ int group_sum(int x, int q) {
+  x += dpp_int<kQuadXor1>(x);
+  x += dpp_int<kQuadXor2>(x);
+  const int up = dpp_int<kRowShl4>(x), down = dpp_int<kRowShr4>(x);
+  return x + (q < 4 ? up : down);
+}
+
 // lz: NP partial logit tiles in LDS, [NP][kTile rows][zs floats]; a token's logit is
-// the sum of its NP partials in the order ((p0 + p1) + p2) + p3.  mask64 (64 words)
+// the sum of its NP partials in the order (((p0 + p1) + p2) + ...).  mask64 (64 words)
 // and flex_lds (1 word) are LDS scratch.  logits_out (global, may be NULL) receives
 // the summed logits.  CT (8 or 16) bounds the trimming size c.  Must be called by
-// all 256 threads of the workgroup.
+// all 512 threads of the workgroup.
 template <int NE, int NP, int CT>
 __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned long long* mask64,
                                 unsigned long long* flex_lds, int tile, const RouteArgs a,
                                 const Workspace ws, int32_t* __restrict__ expert_ids,
                                 float* __restrict__ weights, float* __restrict__ logits_out) {
-  constexpr int NS = CT / 4;  // ranks 4*s + q are handled by lane q ("slots")
+  constexpr int NS = CT / 8;  // ranks 8*s + q are handled by lane q ("slots")
   const int tid = threadIdx.x;
-  const int itok = tid >> 2;
-  const int q = tid & 3;
+  const int itok = tid >> 3;
+  const int q = tid & 7;
   const int t = tile * kTile + itok;
   const bool live = t < a.T;
   const int k = a.k, c = a.c;
@@ -175,7 +197,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   double K[NE];
 #pragma unroll
   for (int i = 0; i < NE; ++i) {
-    const int e = 4 * i + q;
+    const int e = 8 * i + q;
     float v = lz[itok * zs + e];
 #pragma unroll
     for (int pt = 1; pt < NP; ++pt) v = v + lz[pt * kTile * zs + itok * zs + e];
@@ -186,28 +208,30 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   }
   __syncthreads();  // masks zeroed before anyone ORs into them
 
-  // ---- the CT best of the token, sorted, in every lane of its quad -----------
+  // ---- the CT best of the token, sorted, in every lane of its group -----------
   sort_descending<NE>(K);
   double L[CT];
 #pragma unroll
   for (int i = 0; i < CT; ++i) L[i] = i < NE ? K[i < NE ? i : 0] : kPadKey;
-  merge_with_partner<CT, kQuadXor1>(L);
-  merge_with_partner<CT, kQuadXor2>(L);
+  merge_with_partner<CT, kRowHalfMirror>(L);  // {l, 7-l}
+  merge_with_partner<CT, kQuadXor1>(L);       // + {l^1}: 4 lanes' experts
+  merge_with_partner<CT, kQuadXor2>(L);       // + {l^2}: all 8
 
   const float zmax = key_logit(L[0]);
-  // this lane's slots: rank 4*s + q
+  // this lane's slots: rank 8*s + q
   int my_e[NS];
   float my_d[NS], my_p[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     // (the empty asm keeps the compiler from turning the selects into an indexed
     // access of L, which would move the whole list to scratch memory)
-    double s0 = L[4 * s], s1 = L[4 * s + 1], s2 = L[4 * s + 2], s3 = L[4 * s + 3];
-    asm volatile("" : "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3));
-    double sel = s0;
-    sel = q == 1 ? s1 : sel;
-    sel = q == 2 ? s2 : sel;
-    sel = q == 3 ? s3 : sel;
+    double sel = L[8 * s];
+#pragma unroll
+    for (int r = 1; r < 8; ++r) {
+      double alt = L[8 * s + r];
+      asm volatile("" : "+v"(alt));
+      sel = q == r ? alt : sel;
+    }
     my_e[s] = key_expert(sel);
     my_d[s] = key_logit(sel) - zmax;
     my_p[s] = exp_fixed(clamp_exp_arg(my_d[s]));
@@ -217,49 +241,42 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   float p[NE];
 #pragma unroll
   for (int i = 0; i < NE; ++i) {
-    const int e = 4 * i + q;
+    const int e = 8 * i + q;
     p[i] = (e < a.E) ? exp_fixed(clamp_exp_arg(z[i] - zmax)) : 0.0f;
   }
-  // in-lane levels (expert stride 4*s), then quad levels (stride 2, stride 1)
+  // in-lane levels (expert stride 8*s), then group levels (stride 4, 2, 1)
 #pragma unroll
   for (int s = NE / 2; s >= 1; s >>= 1)
 #pragma unroll
     for (int i = 0; i < s; ++i) p[i] = p[i] + p[i + s];
   float zsum = p[0];
-  {
-    const float other = dpp_float<kQuadXor2>(zsum);  // lanes 0,1 receive lanes 2,3
-    zsum = zsum + other;                              // valid in lanes 0,1
-    const float other1 = dpp_float<kQuadXor1>(zsum);  // lane 0 receives lane 1
-    zsum = zsum + other1;                             // valid in lane 0
-    zsum = dpp_float<kQuadBcast0>(zsum);
-  }
+  zsum = zsum + dpp_float<kRowShl4>(zsum);   // valid in lanes 0..3: b[i] += b[i+4]
+  zsum = zsum + dpp_float<kQuadXor2>(zsum);  // valid in lanes 0,1:  b[i] += b[i+2]
+  zsum = zsum + dpp_float<kQuadXor1>(zsum);  // valid in lane 0:     b[0] += b[1]
+  zsum = group_bcast0(zsum, q);
 
-  // ---- top-k mass, pool size ---------------------------------------------------
-  // p of rank j lives in lane j%4, slot j/4
-  float ptop[CT];
+  // ---- top-k mass: left-to-right sum in rank order ------------------------------
+  // rank j lives in lane j%8, slot j/8; the running sum hops from lane to lane
+  float run = my_p[0];
 #pragma unroll
-  for (int j = 0; j < CT; ++j) {
-    const float src = my_p[j >> 2];
-    ptop[j] = (j & 3) == 0   ? dpp_float<0x00>(src)
-              : (j & 3) == 1 ? dpp_float<0x55>(src)
-              : (j & 3) == 2 ? dpp_float<0xAA>(src)
-                             : dpp_float<0xFF>(src);
+  for (int j = 1; j < CT; ++j) {
+    if (j < k) {
+      const float moved = (j & 7) != 0 ? dpp_float<kRowShr1>(run) : dpp_float<kRowShl7>(run);
+      const float next = moved + my_p[j >> 3];
+      run = q == (j & 7) ? next : run;
+    }
   }
-  float sk = ptop[0];
-#pragma unroll
-  for (int j = 1; j < CT; ++j)
-    if (j < k) sk = sk + ptop[j];
+  const float sk = group_read(run, (k - 1) & 7);
   const bool mass_ok = sk >= a.eps_high * zsum;
   // the pool is a prefix of the order, so its size beyond k is the number of ranks in
   // [k, c) that pass the cut
   int extra = 0;
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    const int j = 4 * s + q;
+    const int j = 8 * s + q;
     extra += (j >= k && j < c && my_d[s] >= a.tau_ln) ? 1 : 0;
   }
-  extra += dpp_int<kQuadXor1>(extra);
-  extra += dpp_int<kQuadXor2>(extra);
+  extra = group_sum(extra, q);
   const int cstar = k + extra;
   const bool flex = live && !mass_ok && cstar > k;
 
@@ -268,7 +285,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
     const float denom = a.renormalize ? sk : zsum;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const int j = 4 * s + q;
+      const int j = 8 * s + q;
       if (j < k) {
         expert_ids[(size_t)t * k + j] = my_e[s];
         weights[(size_t)t * k + j] = my_p[s] / denom;
@@ -291,53 +308,60 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   // ---- records of the flexible tokens (rare or chain-bound: not tuned) ----------
   if (__builtin_amdgcn_ballot_w64(flex) != 0ull) {
     int top_e[CT];
+    float ptop[CT];
 #pragma unroll
-    for (int j = 0; j < CT; ++j) top_e[j] = key_expert(L[j]);
+    for (int j = 0; j < CT; ++j) {
+      top_e[j] = key_expert(L[j]);
+      ptop[j] = group_read(my_p[j >> 3], j & 7);
+    }
     if (flex) {
       const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(itok));
-      // ranks 4q..4q+3 of the ordered list go out through lane q
-      unsigned idw = 0, cidw = 0;
-      float pv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      // the chain reads exactly CP candidate lanes per token: ranks beyond the working
-      // set point at a lane that holds no candidate (its key compares as largest)
-      int padlane = a.E;  // lanes E..63 never hold a candidate
-      if (a.E == 64) {
-        unsigned used = 0;
+      if (q < 4) {
+        // ranks 4q..4q+3 of the ordered list go out through lane q
+        unsigned idw = 0, cidw = 0;
+        float pv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        // the chain reads exactly CP candidate lanes per token: ranks beyond the working
+        // set point at a lane that holds no candidate (its key compares as largest)
+        int padlane = a.E;  // lanes E..63 never hold a candidate
+        if (a.E == 64) {
+          unsigned used = 0;
 #pragma unroll
-        for (int j = 0; j < CT; ++j)
-          if (j < cstar && top_e[j] < 32) used |= 1u << top_e[j];
-        padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
-      }
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        if ((j >> 2) == q) {
-          const int ej = j < CT ? top_e[j < CT ? j : 0] : 0;
-          idw |= (unsigned)ej << (8 * (j & 3));
-          cidw |= (unsigned)(j < cstar ? ej : padlane) << (8 * (j & 3));
-          pv[j & 3] = j < CT ? ptop[j < CT ? j : 0] : 0.0f;
+          for (int j = 0; j < CT; ++j)
+            if (j < cstar && top_e[j] < 32) used |= 1u << top_e[j];
+          padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
         }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          if ((j >> 2) == q) {
+            const int ej = j < CT ? top_e[j < CT ? j : 0] : 0;
+            idw |= (unsigned)ej << (8 * (j & 3));
+            cidw |= (unsigned)(j < cstar ? ej : padlane) << (8 * (j & 3));
+            pv[j & 3] = j < CT ? ptop[j < CT ? j : 0] : 0.0f;
+          }
+        }
+        reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
+        reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
+        reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
       }
-      reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
-      reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
-      reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
       // per owned expert: rank in the working set and the number of earlier fixed
-      // tokens of this tile assigned to it
-      uint16_t* row = ws.rec_lane + (size_t)slot * a.EP + q * NE;
+      // tokens of this tile assigned to it; row in expert order
+      uint16_t* row = ws.rec_lane + (size_t)slot * a.EP;
       const unsigned long long below = lanes_below(itok);
 #pragma unroll
       for (int i = 0; i < NE; ++i) {
-        const int e = 4 * i + q;
+        const int e = 8 * i + q;
         int rank = -1;
 #pragma unroll
         for (int j = 0; j < CT; ++j)
           if (j < cstar && top_e[j] == e) rank = j;
         const int fw = __builtin_popcountll(mask64[e] & below);
-        row[i] = rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF;
+        row[e] = rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF;
       }
     }
   }
 }
 
+// NE = padded experts / 8 (1, 2, 4 or 8).
 template <int NE, int NP>
 __device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int zs,
                                              unsigned long long* mask64, unsigned long long* flex_lds,

@@ -3,11 +3,14 @@
 // "Integration with MoE Forward Pass"), followed in the same kernel by the
 // per-token analysis, so the logits never travel through HBM unless asked for.
 //
-// bf16 path (gfx950): one workgroup of 4 wavefronts per tile of 64 tokens.  The
-// contraction axis is cut into chunks of 64 values dealt round-robin to the 4
-// waves, so at any moment a workgroup reads 512 contiguous bytes of every token
-// row; each wave owns its chunks from load to MFMA and needs no barrier until the
-// end.
+// bf16 path (gfx950): one workgroup of 8 wavefronts per tile of 64 tokens.  The
+// contraction axis is cut into chunks of 64 values dealt round-robin to the 8
+// waves; each wave owns its chunks from load to MFMA and needs no barrier until the
+// end.  Eight waves (two per SIMD, at most 256 registers each) rather than four
+// with deeper per-wave prefetch, because a lone wavefront issues a vector
+// instruction only every ~8 cycles on this part: the analysis that follows runs
+// twice as fast with a second wave to fill the gaps, and the same number of bytes
+// stays in flight per CU (8 waves x one 16 KiB chunk).
 //
 // Memory -> registers: 16-byte loads with 8 consecutive lanes on one row, i.e. 8
 // rows x 128 contiguous bytes per instruction.  The vector memory pipeline runs at
@@ -17,9 +20,9 @@
 // Registers -> LDS -> registers: the wave parks the chunk in a private LDS strip
 // (rows padded to 144 bytes) and reads it back in the layout of the 16x16x32 bf16
 // MFMA (lane l: row/column l%16, contraction slots 8*(l/16)..+7); both operands use
-// the same slot -> h mapping.  Two chunks are in flight in registers while a third
-// is being multiplied.  Accumulation is fp32.  The 4 partial tiles meet in LDS and
-// are added in the fixed order ((w0 + w1) + w2) + w3 (bit-reproducible logits).
+// the same slot -> h mapping.  While chunk i is multiplied out of LDS, chunk i+1 is
+// in flight in registers.  Accumulation is fp32.  The 8 partial tiles meet in LDS
+// and are added in a fixed order (bit-reproducible logits).
 #include "analyse.h"
 #include "laser_internal.h"
 
@@ -31,32 +34,35 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* global_u4_ptr;
 typedef __attribute__((address_space(3))) u32x4* lds_u4_ptr;
 
-constexpr int kGateWaves = 4;
-constexpr int kPartStride = 68;   // floats per token row of a partial tile (64 + 4 pad)
+constexpr int kGateWaves = 8;
+constexpr int kGateThreads = kGateWaves * 64;
+constexpr int kPartStride = 72;   // floats per token row of a partial tile (64 + 8 pad)
 constexpr int kRowBytes = 144;    // staged row: 128 bytes of a chunk + 16 bytes pad
 constexpr int kStripBytes = 2 * kTile * kRowBytes;  // per wave: hidden rows, then W rows
 constexpr int kPartBytes = kGateWaves * kTile * kPartStride * 4;
 constexpr int kGateLdsBytes =
     kPartBytes > kGateWaves * kStripBytes ? kPartBytes : kGateWaves * kStripBytes;
 
-__device__ __forceinline__ u32x4 load_global_16(const uint16_t* p) {
+__device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
   return *(global_u4_ptr)(p);
 }
 
-// G: global -> registers, one chunk (8 loads of hidden rows, 2*EB of W rows).
-#define GATE_G(R, KOFF)                                                          \
+// G: global -> registers, one chunk (8 loads of hidden rows, 2*EB of W rows).  The
+// scheduling barriers keep the compiler from sinking the loads down to their first
+// use, which would undo the prefetch.
+#define GATE_G(KBYTES)                                                           \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
-      R.h[q_] = load_global_16(hsrc[q_] + (KOFF));                               \
+      rh[q_] = load_global_16(hbase + hoff[q_] + (KBYTES));                      \
   _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
-      R.w[q_] = load_global_16(wsrc[q_] + (KOFF));                               \
+      rw[q_] = load_global_16(wbase + woff[q_] + (KBYTES));                      \
   __builtin_amdgcn_sched_barrier(0);
 
 // S: registers -> the wave's LDS strip.
-#define GATE_S(R)                                                                \
+#define GATE_S()                                                                 \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
-      *(lds_u4_ptr)(st_wr + q_ * 8 * kRowBytes) = R.h[q_];                       \
+      *(lds_u4_ptr)(st_wr + q_ * 8 * kRowBytes) = rh[q_];                        \
   _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
-      *(lds_u4_ptr)(st_wr + kTile * kRowBytes + q_ * 8 * kRowBytes) = R.w[q_];   \
+      *(lds_u4_ptr)(st_wr + kTile * kRowBytes + q_ * 8 * kRowBytes) = rw[q_];    \
   __builtin_amdgcn_sched_barrier(0);
 
 // M: LDS strip -> MFMA operands -> accumulate, two k-steps of 32.
@@ -75,16 +81,10 @@ __device__ __forceinline__ u32x4 load_global_16(const uint16_t* p) {
   }                                                                              \
   __builtin_amdgcn_sched_barrier(0);
 
-template <int EB>
-struct GateRegs {
-  u32x4 h[8];
-  u32x4 w[2 * EB];
-};
-
 // EB: 16-expert blocks, 1 (E <= 16), 2 (E <= 32) or 4 (E <= 64).  NE: experts per
-// lane of the per-token analysis that follows in the same kernel (padded E / 4).
+// lane of the per-token analysis that follows in the same kernel (padded E / 8).
 template <int EB, int NE>
-__global__ __launch_bounds__(256) void gate_analyse_bf16_kernel(
+__global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a,
     const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
     float* __restrict__ logits_out) {
@@ -107,15 +107,18 @@ __global__ __launch_bounds__(256) void gate_analyse_bf16_kernel(
 
   // Load side: lane l of load q takes piece l%8 (16 bytes) of row 8q + l/8.  Rows past
   // the end (tokens >= T, experts >= E) are clamped to the last valid row: their
-  // products land in accumulator entries that are never used.
+  // products land in accumulator entries that are never used.  Addresses are a
+  // wave-uniform base plus a 32-bit byte offset per lane.
   const int lrow = lane >> 3, lpiece = lane & 7;
-  const uint16_t* hsrc[8];
+  const size_t row_bytes = (size_t)H * 2;
+  const unsigned char* hbase = reinterpret_cast<const unsigned char*>(hidden) + (size_t)tile * kTile * row_bytes;
+  const unsigned char* wbase = reinterpret_cast<const unsigned char*>(w);
+  const int last_row = T - 1 - tile * kTile;  // >= 0
+  unsigned hoff[8], woff[2 * EB];
 #pragma unroll
-  for (int q = 0; q < 8; ++q)
-    hsrc[q] = hidden + (size_t)min(tile * kTile + q * 8 + lrow, T - 1) * H + lpiece * 8;
-  const uint16_t* wsrc[2 * EB];
+  for (int q = 0; q < 8; ++q) hoff[q] = (unsigned)(min(q * 8 + lrow, last_row) * row_bytes) + lpiece * 16;
 #pragma unroll
-  for (int q = 0; q < 2 * EB; ++q) wsrc[q] = w + (size_t)min(q * 8 + lrow, E - 1) * H + lpiece * 8;
+  for (int q = 0; q < 2 * EB; ++q) woff[q] = (unsigned)(min(q * 8 + lrow, E - 1) * row_bytes) + lpiece * 16;
   // LDS side: the strip of this wave; write position of (row l/8, piece l%8), read
   // position of (row l%16, slot group l/16).
   unsigned char* strip = gate_lds + wave_u * kStripBytes;
@@ -123,75 +126,51 @@ __global__ __launch_bounds__(256) void gate_analyse_bf16_kernel(
   unsigned char* st_rd = strip + (lane & 15) * kRowBytes + (lane >> 4) * 16;
 
   const int nfull = H >> 6;
-  const int nmine = (nfull - wave_u + kGateWaves - 1) / kGateWaves;  // chunks wave, wave+4, ...
+  const int nmine = (nfull - wave_u + kGateWaves - 1) / kGateWaves;  // chunks wave, wave+8, ...
   // Every tile starts its walk over the contraction axis at a different chunk, so
   // that the workgroups running at the same time do not all read the same column
   // range of their rows (which would land on the same memory channels).
-  const int lim = nfull * 64;
-  const int cstride = kGateWaves * 64;
-  int koff = nfull > 0 ? ((tile * 5 + wave_u) % nfull) * 64 : 0;
-  auto step = [&](int k) { k += cstride; return k >= lim ? k - lim : k; };  // nfull >= 4 when used
+  const int lim = nfull * 128;          // bytes of the full chunks of a row
+  const int cstride = kGateWaves * 128;
+  int koff = nfull > 0 ? ((tile * 5 + wave_u) % nfull) * 128 : 0;
+  auto step = [&](int k) { k += cstride; return k >= lim ? k - lim : k; };  // nfull >= 8 when used
 
-  // Software pipeline over this wave's chunks c0, c1, ...: while chunk i is
-  // multiplied out of LDS, chunks i+1 and i+2 are in flight in ra / rb.
-  GateRegs<EB> ra, rb;
+  u32x4 rh[8], rw[2 * EB];
   if (nmine > 0) {
-    GATE_G(ra, koff)
-    GATE_S(ra)                       // chunk 0 staged
-    if (nmine > 1) { koff = step(koff); GATE_G(ra, koff) }   // chunk 1 in ra
-    int i = 0;
-    while (i + 3 < nmine) {          // straight-line body, two chunks per trip
+    GATE_G(koff)
+    for (int i = 0; i + 1 < nmine; ++i) {
+      GATE_S()            // chunk i staged (waits for its loads)
       koff = step(koff);
-      GATE_G(rb, koff)               // chunk i+2
-      GATE_M()                       // chunk i
-      GATE_S(ra)                     // chunk i+1 staged
-      koff = step(koff);
-      GATE_G(ra, koff)               // chunk i+3
-      GATE_M()                       // chunk i+1
-      GATE_S(rb)                     // chunk i+2 staged
-      i += 2;
+      GATE_G(koff)        // chunk i+1 in flight ...
+      GATE_M()            // ... while chunk i is multiplied
     }
-    // here: chunk i staged, chunk i+1 (if any) in ra; at most 3 chunks left
-    if (i + 2 < nmine) {
-      koff = step(koff);
-      GATE_G(rb, koff)               // chunk i+2, the last one
-      GATE_M()
-      GATE_S(ra)
-      GATE_M()
-      GATE_S(rb)
-      GATE_M()
-    } else if (i + 1 < nmine) {
-      GATE_M()
-      GATE_S(ra)
-      GATE_M()
-    } else {
-      GATE_M()
-    }
+    GATE_S()
+    GATE_M()
   }
   // Ragged tail of the contraction axis (H % 64 != 0), taken by one wave: pieces
   // past H are read from the start of the row instead and replaced by zeros.
-  if ((H & 63) != 0 && wave_u == (nfull & 3)) {
+  if ((H & 63) != 0 && wave_u == (nfull & (kGateWaves - 1))) {
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const bool kin = nfull * 64 + lpiece * 8 < H;  // H % 8 == 0: a piece is all in or all out
-    const int off = kin ? nfull * 64 : -lpiece * 8;
+    const int off = kin ? nfull * 128 : -lpiece * 16;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const u32x4 v = load_global_16(hsrc[q] + off);
-      ra.h[q] = kin ? v : zero4;
+      const u32x4 v = load_global_16(hbase + hoff[q] + off);
+      rh[q] = kin ? v : zero4;
     }
 #pragma unroll
     for (int q = 0; q < 2 * EB; ++q) {
-      const u32x4 v = load_global_16(wsrc[q] + off);
-      ra.w[q] = kin ? v : zero4;
+      const u32x4 v = load_global_16(wbase + woff[q] + off);
+      rw[q] = kin ? v : zero4;
     }
-    GATE_S(ra)
+    GATE_S()
     GATE_M()
   }
   __syncthreads();  // all strips are dead: the partial tiles reuse the space
 
   // Accumulator layout of the 16x16 MFMA: register r of lane l holds
   // row 4*(l/16) + r (expert) of column l%16 (token).
-  float* part = reinterpret_cast<float*>(gate_lds);  // [4][64][kPartStride]
+  float* part = reinterpret_cast<float*>(gate_lds);  // [8][64][kPartStride]
   float* mine = part + (size_t)wave * kTile * kPartStride;
   const int n = lane & 15, kgrp = lane >> 4;
 #pragma unroll
@@ -203,7 +182,7 @@ __global__ __launch_bounds__(256) void gate_analyse_bf16_kernel(
     }
   __syncthreads();
 
-  // The four partial tiles are summed on the fly by the analysis.
+  // The eight partial tiles are summed on the fly by the analysis.
   analyse_tile<NE, kGateWaves>(part, kPartStride, mask64, &flex_lds, tile, a, ws, expert_ids,
                                weights, logits_out);
 }
@@ -219,7 +198,7 @@ static hipError_t launch_one(const void* hidden, const void* w, int H, const Rou
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE>), dim3(a.ntiles), dim3(256), kGateLdsBytes, s,
+  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out);
   return hipGetLastError();
@@ -230,10 +209,10 @@ hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, co
                                     float* logits_out, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
   switch (a.EP) {
-    case 8: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    case 16: return launch_one<1, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    case 32: return launch_one<2, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    default: return launch_one<4, 16>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 8: return launch_one<1, 1>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 16: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 32: return launch_one<2, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    default: return launch_one<4, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
   }
 }
 

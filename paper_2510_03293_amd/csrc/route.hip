@@ -30,12 +30,12 @@
 
 namespace laser {
 
-template <int NE>
-__global__ __launch_bounds__(256) void analyse_kernel(const float* __restrict__ logits,
+template <int NE>  // padded experts / 8
+__global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ logits,
                                                       const RouteArgs a, const Workspace ws,
                                                       int32_t* __restrict__ expert_ids,
                                                       float* __restrict__ weights) {
-  constexpr int ZS = 4 * NE + 4;
+  constexpr int ZS = 8 * NE + 8;
   __shared__ float lz[kTile * ZS];
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void analyse_kernel(const float* __restrict__ 
   const int E = a.E;
   const int rows = min(kTile, a.T - tile * kTile);
   const float* src = logits + (size_t)tile * kTile * E;
-  for (int idx = threadIdx.x; idx < rows * E; idx += 256) {
+  for (int idx = threadIdx.x; idx < rows * E; idx += 512) {
     const int tok = idx / E;
     lz[tok * ZS + (idx - tok * E)] = src[idx];
   }
@@ -54,19 +54,19 @@ __global__ __launch_bounds__(256) void analyse_kernel(const float* __restrict__ 
 hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
-  const dim3 grid(a.ntiles), block(256);
+  const dim3 grid(a.ntiles), block(512);
   switch (a.EP) {
     case 8:
-      hipLaunchKernelGGL(analyse_kernel<2>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
+      hipLaunchKernelGGL(analyse_kernel<1>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
       break;
     case 16:
-      hipLaunchKernelGGL(analyse_kernel<4>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
+      hipLaunchKernelGGL(analyse_kernel<2>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
       break;
     case 32:
-      hipLaunchKernelGGL(analyse_kernel<8>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
+      hipLaunchKernelGGL(analyse_kernel<4>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
       break;
     default:
-      hipLaunchKernelGGL(analyse_kernel<16>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
+      hipLaunchKernelGGL(analyse_kernel<8>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
       break;
   }
   return hipGetLastError();
@@ -191,8 +191,7 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int nflex_tiles, con
                                            const Workspace& ws, int wave, int lane, int lin,
                                            int& gflex) {
   const int nbatch = (nflex_tiles + kChainBatch - 1) / kChainBatch;
-  const int NE = a.EP >> 2;
-  const int mypos = (lane & 3) * NE + (lane >> 2);  // where expert `lane` sits in a record row
+  const int mypos = lane;  // a record row is in expert order
   const bool lane_ok = lane < a.EP;
   const int EP = a.EP;
   const int k = a.k;
