@@ -59,9 +59,11 @@ __device__ __forceinline__ unsigned long long lanes_below(int i) {
 
 // --------------------------------------------------------------- analyse -----
 //
-// 512 threads per tile of 64 tokens: 8 lanes per token, lane q of a token owns
-// the experts e = 8*i + q (i < NE).  Strides >= 8 of the Z tree then stay inside
-// a lane and the last three levels are exchanges inside the 8-lane group.
+// 512 threads per tile of 64 tokens: 8 lanes per token.  Lane q of a token owns NE =
+// (padded E)/8 experts in runs of G = min(4, NE) consecutive ones (so that a run is
+// one LDS read): run g, element r is expert g*(padded E)/NG + G*q + r, NG = NE/G runs
+// (two only for 64 experts).  The Z tree then starts with one in-lane level (64
+// experts), goes through three exchanges inside the 8-lane group and ends in-lane.
 //
 // Order statistics.  Each logit becomes a 64-bit key that sorts, as an IEEE double,
 // exactly like (logit descending, expert ascending): the logit widened to double
@@ -193,18 +195,38 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   // kernel earlier on the same stream
   if (tile == 0 && tid < 4) ws.status[tid] = 0;
 
+  constexpr int G = NE < 4 ? NE : 4;      // consecutive experts per run
+  constexpr int NG = NE / G;              // runs per lane
+  constexpr int kRunStride = 8 * NE / NG;  // experts between the starts of two runs
+  typedef float run_t __attribute__((ext_vector_type(G)));
+  auto owned = [&](int i) { return (i / G) * kRunStride + G * q + (i % G); };
+
   float z[NE];
   double K[NE];
 #pragma unroll
-  for (int i = 0; i < NE; ++i) {
-    const int e = 8 * i + q;
-    float v = lz[itok * zs + e];
+  for (int g = 0; g < NG; ++g) {
+    const float* src = lz + itok * zs + g * kRunStride + G * q;
+    float v[G];
+    {
+      const run_t first = *reinterpret_cast<const run_t*>(src);
 #pragma unroll
-    for (int pt = 1; pt < NP; ++pt) v = v + lz[pt * kTile * zs + itok * zs + e];
-    const bool real = live && e < a.E;
-    if (logits_out != nullptr && real) logits_out[(size_t)t * a.E + e] = v;
-    z[i] = real ? v : kLowestLogit;
-    K[i] = make_key(z[i], e);
+      for (int r = 0; r < G; ++r) v[r] = G == 1 ? *src : first[r < G ? r : 0];
+    }
+#pragma unroll
+    for (int pt = 1; pt < NP; ++pt) {
+      const run_t more = *reinterpret_cast<const run_t*>(src + pt * kTile * zs);
+#pragma unroll
+      for (int r = 0; r < G; ++r) v[r] = v[r] + more[r < G ? r : 0];
+    }
+#pragma unroll
+    for (int r = 0; r < G; ++r) {
+      const int i = g * G + r;
+      const int e = owned(i);
+      const bool real = live && e < a.E;
+      if (logits_out != nullptr && real) logits_out[(size_t)t * a.E + e] = v[r];
+      z[i] = real ? v[r] : kLowestLogit;
+      K[i] = make_key(z[i], e);
+    }
   }
   __syncthreads();  // masks zeroed before anyone ORs into them
 
@@ -240,20 +262,24 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   // ---- softmax normaliser over all experts ------------------------------------
   float p[NE];
 #pragma unroll
-  for (int i = 0; i < NE; ++i) {
-    const int e = 8 * i + q;
-    p[i] = (e < a.E) ? exp_fixed(clamp_exp_arg(z[i] - zmax)) : 0.0f;
+  for (int i = 0; i < NE; ++i) p[i] = (owned(i) < a.E) ? exp_fixed(clamp_exp_arg(z[i] - zmax)) : 0.0f;
+  // the tree, top level first: stride (padded E)/2 pairs the two runs of a lane; the
+  // next three strides pair lane q with q+4, q+2, q+1; the rest is inside the run
+  if (NG == 2) {
+#pragma unroll
+    for (int r = 0; r < G; ++r) p[r] = p[r] + p[G + r];
   }
-  // in-lane levels (expert stride 8*s), then group levels (stride 4, 2, 1)
 #pragma unroll
-  for (int s = NE / 2; s >= 1; s >>= 1)
+  for (int r = 0; r < G; ++r) p[r] = p[r] + dpp_float<kRowShl4>(p[r]);   // valid in lanes 0..3
 #pragma unroll
-    for (int i = 0; i < s; ++i) p[i] = p[i] + p[i + s];
-  float zsum = p[0];
-  zsum = zsum + dpp_float<kRowShl4>(zsum);   // valid in lanes 0..3: b[i] += b[i+4]
-  zsum = zsum + dpp_float<kQuadXor2>(zsum);  // valid in lanes 0,1:  b[i] += b[i+2]
-  zsum = zsum + dpp_float<kQuadXor1>(zsum);  // valid in lane 0:     b[0] += b[1]
-  zsum = group_bcast0(zsum, q);
+  for (int r = 0; r < G; ++r) p[r] = p[r] + dpp_float<kQuadXor2>(p[r]);  // valid in lanes 0,1
+#pragma unroll
+  for (int r = 0; r < G; ++r) p[r] = p[r] + dpp_float<kQuadXor1>(p[r]);  // valid in lane 0
+#pragma unroll
+  for (int s = G / 2; s >= 1; s >>= 1)
+#pragma unroll
+    for (int r = 0; r < s; ++r) p[r] = p[r] + p[r + s];
+  const float zsum = group_bcast0(p[0], q);
 
   // ---- top-k mass: left-to-right sum in rank order ------------------------------
   // rank j lives in lane j%8, slot j/8; the running sum hops from lane to lane
@@ -282,6 +308,14 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
 
   // ---- tokens whose experts are final: outputs, per-expert masks ----------------
   if (live && !flex) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      if (8 * s + q < k) atomicOr(&mask64[my_e[s]], 1ull << itok);
+  }
+  if (flex && q == 0) atomicOr(flex_lds, 1ull << itok);
+  __syncthreads();
+  // (global stores only after the barrier: a barrier waits for the stores before it)
+  if (live && !flex) {
     const float denom = a.renormalize ? sk : zsum;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -289,16 +323,13 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       if (j < k) {
         expert_ids[(size_t)t * k + j] = my_e[s];
         weights[(size_t)t * k + j] = my_p[s] / denom;
-        atomicOr(&mask64[my_e[s]], 1ull << itok);
       }
     }
   }
-  if (flex && q == 0) atomicOr(flex_lds, 1ull << itok);
   if (live && q == 0) {
     ws.rec_cstar[t] = flex ? (uint8_t)cstar : (uint8_t)0;
     ws.rec_Z[t] = zsum;
   }
-  __syncthreads();
 
   if (tid < 64)
     ws.tile_fixed_cnt[(size_t)tile * 64 + tid] = (uint8_t)__builtin_popcountll(mask64[tid]);
@@ -349,7 +380,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       const unsigned long long below = lanes_below(itok);
 #pragma unroll
       for (int i = 0; i < NE; ++i) {
-        const int e = 8 * i + q;
+        const int e = owned(i);
         int rank = -1;
 #pragma unroll
         for (int j = 0; j < CT; ++j)

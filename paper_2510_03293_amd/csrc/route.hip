@@ -36,7 +36,7 @@ __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ 
                                                       int32_t* __restrict__ expert_ids,
                                                       float* __restrict__ weights) {
   constexpr int ZS = 8 * NE + 8;
-  __shared__ float lz[kTile * ZS];
+  __shared__ __align__(16) float lz[kTile * ZS];
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
   const int tile = blockIdx.x;
