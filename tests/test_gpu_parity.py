@@ -171,3 +171,76 @@ def test_benchmark_shapes_reduced_tokens(name, layer, preset, T):
                              inp["loads_in"], label=f"{name}/{preset}")
     if preset == "stress":
         assert ref["expanded"].all() and (ref["cstar"] == s.c).all()
+
+
+# ---------------------------------------------------------------- full sizes --
+
+@pytest.mark.parametrize("name,layer,preset", [
+    ("deepseek", 0, "paper"), ("deepseek", 13, "stress"), ("deepseek", 26, "gsm8k"),
+    ("mixtral", 0, "paper"), ("mixtral", 31, "paper"),
+])
+def test_full_size_layers(name, layer, preset):
+    """One whole layer of the benchmark configurations, every output checked."""
+    u = _util()
+    inp = wl.layer_inputs(name, layer)
+    s = inp["shape"]
+    eps, tfix = wl.thresholds(name, layer, preset)
+    gpu, ref = u.check_route(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
+                             inp["loads_in"], label=f"{name}[{layer}]/{preset} full")
+    assert gpu["loads"].sum() == s.T * s.k
+
+
+def test_full_size_prefill():
+    """131072 tokens, H=4096, E=64: logits checked on a sample of rows (the fp64 gate
+    of all rows would take minutes), routing and dispatch checked in full against the
+    oracle fed with the GPU's logits."""
+    u = _util()
+    inp = wl.layer_inputs("prefill", 0)
+    s = inp["shape"]
+    eps, tfix = wl.thresholds("prefill", 0, "paper")
+    rows = np.random.default_rng(1).choice(s.T, size=1536, replace=False)
+    rows = np.concatenate([rows, [0, 63, 64, s.T - 65, s.T - 1]])
+    gpu, ref = u.check_route(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
+                             inp["loads_in"], label="prefill full", logit_rows=rows)
+    assert 0.05 < ref["expanded"].mean() < 0.2
+    # properties that hold at any size
+    perm = gpu["permutation"]
+    assert np.array_equal(np.sort(perm), np.arange(s.T * s.k, dtype=np.int32))
+    flat = gpu["expert_ids"].ravel()[perm]
+    assert np.all(np.diff(flat) >= 0)
+
+
+def test_decode_steps_carry_loads():
+    """64 tokens per step, loads persist across steps (a sample of the 512 steps of
+    the decode configuration is enough to cross several preset boundaries)."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    import oracle
+    u = _util()
+    s = wl.SHAPES["decode"]
+    w = wl.decode_gate_weight()
+    wd = u.to_device(w)
+    eps, tfix = wl.thresholds("decode", 0, "gsm8k")
+    params = B.make_params(s.k, s.c, eps, tfix, dtype=s.dtype)
+    loads = torch.zeros(s.E, dtype=torch.int32, device="cuda")
+    buf = B.RouteBuffers(s.T, s.H, s.E, params, want_logits=True)
+    ref_loads = np.zeros(s.E, dtype=np.int32)
+    flexible = 0
+    for step in range(96):
+        inp = wl.layer_inputs("decode", step, w=w)
+        hd = u.to_device(inp["hidden"])
+        B.route(hd, wd, params, loads, buffers=buf)
+        torch.cuda.synchronize()
+        z = buf.logits.cpu().numpy()
+        ref = oracle.route(z, s.k, s.c, eps, tfix, ref_loads)
+        assert np.array_equal(buf.expert_ids.cpu().numpy(), ref["expert_ids"]), step
+        assert np.array_equal(buf.permutation.cpu().numpy(), ref["permutation"]), step
+        assert np.array_equal(buf.expert_offsets.cpu().numpy(), ref["expert_offsets"]), step
+        ref_loads = ref["loads"]
+        assert np.array_equal(loads.cpu().numpy(), ref_loads), step
+        flexible += int((ref["cstar"] > s.k).sum())
+        if step % 32 == 0:
+            zz = oracle.gate(inp["hidden"], w, s.dtype)
+            assert np.abs(z - zz).max() <= 2e-3
+    assert flexible > 100          # the load-aware branch was really exercised
+    assert ref_loads.sum() == 96 * s.T * s.k
