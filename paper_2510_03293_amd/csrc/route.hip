@@ -166,22 +166,48 @@ __device__ void chain_prefetch(ChainBatch* dst, int batch, int nflex_tiles, cons
   }
 }
 
+// cnt += number of the 4 lanes named by the bytes of `w` whose key is smaller than this
+// lane's key.  Written in assembly because the order of the instructions is the
+// point: on gfx950 a vector instruction that reads an SGPR written by the vector
+// instruction just before it (lane read -> compare -> add-with-carry) needs two wait
+// states each time; grouped as 4 lane reads, 4 compares, 4 adds every producer is at
+// least three instructions ahead of its consumer and nothing waits.
+__device__ __forceinline__ void count_smaller4(unsigned key, unsigned w, int& cnt) {
+  unsigned e0, e1, e2, e3;
+  unsigned long long c0, c1, c2, c3, cy;
+  asm volatile(
+      "s_nop 1\n\t"
+      "s_bfe_u32 %[e0], %[w], 0x80000\n\t"
+      "s_bfe_u32 %[e1], %[w], 0x80008\n\t"
+      "s_bfe_u32 %[e2], %[w], 0x80010\n\t"
+      "s_lshr_b32 %[e3], %[w], 24\n\t"
+      "v_readlane_b32 %[e0], %[key], %[e0]\n\t"
+      "v_readlane_b32 %[e1], %[key], %[e1]\n\t"
+      "v_readlane_b32 %[e2], %[key], %[e2]\n\t"
+      "v_readlane_b32 %[e3], %[key], %[e3]\n\t"
+      "v_cmp_lt_u32_e64 %[c0], %[e0], %[key]\n\t"
+      "v_cmp_lt_u32_e64 %[c1], %[e1], %[key]\n\t"
+      "v_cmp_lt_u32_e64 %[c2], %[e2], %[key]\n\t"
+      "v_cmp_lt_u32_e64 %[c3], %[e3], %[key]\n\t"
+      "v_addc_co_u32_e64 %[cnt], %[cy], %[cnt], 0, %[c0]\n\t"
+      "v_addc_co_u32_e64 %[cnt], %[cy], %[cnt], 0, %[c1]\n\t"
+      "v_addc_co_u32_e64 %[cnt], %[cy], %[cnt], 0, %[c2]\n\t"
+      "v_addc_co_u32_e64 %[cnt], %[cy], %[cnt], 0, %[c3]\n\t"
+      "s_nop 1\n\t"
+      : [cnt] "+v"(cnt), [e0] "=&s"(e0), [e1] "=&s"(e1), [e2] "=&s"(e2), [e3] "=&s"(e3),
+        [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [cy] "=&s"(cy)
+      : [key] "v"(key), [w] "s"(w));
+}
+
 // One flexible token: returns whether this lane's expert is chosen.
 template <int CP>
 __device__ __forceinline__ bool chain_step(unsigned key, bool cand, const uint4 ids, int k) {
-  unsigned w[4];
-  w[0] = __builtin_amdgcn_readfirstlane(ids.x);
-  if (CP > 4) w[1] = __builtin_amdgcn_readfirstlane(ids.y);
-  if (CP > 8) {
-    w[2] = __builtin_amdgcn_readfirstlane(ids.z);
-    w[3] = __builtin_amdgcn_readfirstlane(ids.w);
-  }
   int smaller = 0;
-#pragma unroll
-  for (int j = 0; j < CP; ++j) {
-    const int e = (w[j >> 2] >> (8 * (j & 3))) & 0xFF;
-    const unsigned other = __builtin_amdgcn_readlane(key, e);
-    smaller += (other < key) ? 1 : 0;
+  count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.x), smaller);
+  if (CP > 4) count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.y), smaller);
+  if (CP > 8) {
+    count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.z), smaller);
+    count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.w), smaller);
   }
   return cand && smaller < k;
 }
