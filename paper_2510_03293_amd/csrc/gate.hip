@@ -9,8 +9,8 @@
 // end.  Eight waves (two per SIMD, at most 256 registers each) rather than four
 // with deeper per-wave prefetch, because a lone wavefront issues a vector
 // instruction only every ~8 cycles on this part: the analysis that follows runs
-// twice as fast with a second wave to fill the gaps, and the same number of bytes
-// stays in flight per CU (8 waves x one 16 KiB chunk).
+// twice as fast with a second wave to fill the gaps.  Each wave keeps two 16 KiB
+// chunks in flight (256 KiB per CU).
 //
 // Memory -> registers: 16-byte loads with 8 consecutive lanes on one row, i.e. 8
 // rows x 128 contiguous bytes per instruction.  The vector memory pipeline runs at
@@ -20,8 +20,8 @@
 // Registers -> LDS -> registers: the wave parks the chunk in a private LDS strip
 // (rows padded to 144 bytes) and reads it back in the layout of the 16x16x32 bf16
 // MFMA (lane l: row/column l%16, contraction slots 8*(l/16)..+7); both operands use
-// the same slot -> h mapping.  While chunk i is multiplied out of LDS, chunk i+1 is
-// in flight in registers.  Accumulation is fp32.  The 8 partial tiles meet in LDS
+// the same slot -> h mapping.  While chunk i is multiplied out of LDS, chunks i+1 and
+// i+2 are in flight in registers.  Accumulation is fp32.  The 8 partial tiles meet in LDS
 // and are added in a fixed order (bit-reproducible logits).
 #include "analyse.h"
 #include "laser_internal.h"
@@ -47,22 +47,24 @@ __device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
   return *(global_u4_ptr)(p);
 }
 
-// G: global -> registers, one chunk (8 loads of hidden rows, 2*EB of W rows).  The
-// scheduling barriers keep the compiler from sinking the loads down to their first
-// use, which would undo the prefetch.
-#define GATE_G(KBYTES)                                                           \
+// GH / GW: global -> registers, the hidden rows (8 loads) or the W rows (2*EB loads)
+// of one chunk.  The scheduling barriers keep the compiler from sinking the loads
+// down to their first use, which would undo the prefetch.
+#define GATE_GH(RH, KBYTES)                                                      \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
-      rh[q_] = load_global_16(hbase + hoff[q_] + (KBYTES));                      \
+      RH[q_] = load_global_16(hbase + hoff[q_] + (KBYTES));                      \
+  __builtin_amdgcn_sched_barrier(0);
+#define GATE_GW(RW, KBYTES)                                                      \
   _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
-      rw[q_] = load_global_16(wbase + woff[q_] + (KBYTES));                      \
+      RW[q_] = load_global_16(wbase + woff[q_] + (KBYTES));                      \
   __builtin_amdgcn_sched_barrier(0);
 
 // S: registers -> the wave's LDS strip.
-#define GATE_S()                                                                 \
+#define GATE_S(RH, RW)                                                           \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
-      *(lds_u4_ptr)(st_wr + q_ * 8 * kRowBytes) = rh[q_];                        \
+      *(lds_u4_ptr)(st_wr + q_ * 8 * kRowBytes) = RH[q_];                        \
   _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
-      *(lds_u4_ptr)(st_wr + kTile * kRowBytes + q_ * 8 * kRowBytes) = rw[q_];    \
+      *(lds_u4_ptr)(st_wr + kTile * kRowBytes + q_ * 8 * kRowBytes) = RW[q_];    \
   __builtin_amdgcn_sched_barrier(0);
 
 // M: LDS strip -> MFMA operands -> accumulate, two k-steps of 32.
@@ -78,12 +80,14 @@ __device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
         acc[eb_][tb_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                 \
             __builtin_bit_cast(bf16x8, a_[eb_]), __builtin_bit_cast(bf16x8, b_[tb_]), \
             acc[eb_][tb_], 0, 0, 0);                                             \
-  }                                                                              \
-  __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_sched_barrier(0);                                           \
+  }
 
 // EB: 16-expert blocks, 1 (E <= 16), 2 (E <= 32) or 4 (E <= 64).  NE: experts per
 // lane of the per-token analysis that follows in the same kernel (padded E / 8).
-template <int EB, int NE>
+// NM: chunks per wave when H == 512 * NM (the main loop is then written out with
+// deeper prefetch), 0 for any other H.
+template <int EB, int NE, int NM>
 __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a,
     const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
@@ -136,20 +140,55 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
   auto step = [&](int k) { k += cstride; return k >= lim ? k - lim : k; };  // nfull >= 8 when used
 
   u32x4 rh[8], rw[2 * EB];
-  if (nmine > 0) {
-    GATE_G(koff)
+  if constexpr (NM > 0) {
+    // Exactly NM chunks per wave (H == 512 * NM), written out straight.  In flight
+    // while chunk i is multiplied: the hidden rows of chunks i+1 and i+2 (from HBM;
+    // register sets rh, rh2 in turn) and the W rows of chunk i+1 (from L2).  Loads
+    // complete in issue order, so W(i+1) is issued before hidden(i+2).
+    u32x4 rh2[8];
+    int kw = koff;
+    GATE_GH(rh, koff)
+    GATE_GW(rw, kw)
+    koff = step(koff);
+    GATE_GH(rh2, koff)
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      if (i % 2 == 0) {
+        GATE_S(rh, rw)
+      } else {
+        GATE_S(rh2, rw)
+      }
+      if (i + 1 < NM) {
+        kw = step(kw);
+        GATE_GW(rw, kw)
+      }
+      if (i + 2 < NM) {
+        koff = step(koff);
+        if (i % 2 == 0) {
+          GATE_GH(rh, koff)
+        } else {
+          GATE_GH(rh2, koff)
+        }
+      }
+      GATE_M()
+    }
+  } else if (nmine > 0) {
+    // any H: one chunk in flight per wave
+    GATE_GH(rh, koff)
+    GATE_GW(rw, koff)
     for (int i = 0; i + 1 < nmine; ++i) {
-      GATE_S()            // chunk i staged (waits for its loads)
+      GATE_S(rh, rw)      // chunk i staged (waits for its loads)
       koff = step(koff);
-      GATE_G(koff)        // chunk i+1 in flight ...
+      GATE_GH(rh, koff)   // chunk i+1 in flight ...
+      GATE_GW(rw, koff)
       GATE_M()            // ... while chunk i is multiplied
     }
-    GATE_S()
+    GATE_S(rh, rw)
     GATE_M()
   }
   // Ragged tail of the contraction axis (H % 64 != 0), taken by one wave: pieces
   // past H are read from the start of the row instead and replaced by zeros.
-  if ((H & 63) != 0 && wave_u == (nfull & (kGateWaves - 1))) {
+  if (NM == 0 && (H & 63) != 0 && wave_u == (nfull & (kGateWaves - 1))) {
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const bool kin = nfull * 64 + lpiece * 8 < H;  // H % 8 == 0: a piece is all in or all out
     const int off = kin ? nfull * 128 : -lpiece * 16;
@@ -163,7 +202,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
       const u32x4 v = load_global_16(wbase + woff[q] + off);
       rw[q] = kin ? v : zero4;
     }
-    GATE_S()
+    GATE_S(rh, rw)
     GATE_M()
   }
   __syncthreads();  // all strips are dead: the partial tiles reuse the space
@@ -187,21 +226,30 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
                                weights, logits_out);
 }
 
-template <int EB, int NE>
-static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
+template <int EB, int NE, int NM>
+static hipError_t launch_nm(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
                              float* logits_out, hipStream_t s) {
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE>);
+  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
+  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out);
   return hipGetLastError();
+}
+
+template <int EB, int NE>
+static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
+                             const Workspace& ws, int32_t* expert_ids, float* weights,
+                             float* logits_out, hipStream_t s) {
+  if (H == 2048) return launch_nm<EB, NE, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  if (H == 4096) return launch_nm<EB, NE, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  return launch_nm<EB, NE, 0>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
 }
 
 hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
