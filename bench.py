@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # Valid only for the kernel sources they were taken on: the record carries their hash
 # and `traffic` is reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "0bbd614e7f769d30",
+    "sources_sha256_16": "47c57db431fef888",
     "workload": "deepseek",
-    "fetch_kib": 33977.45, "fetch_scale": 1.9997,
+    "fetch_kib": 33907.69, "fetch_scale": 1.9997,
     "write_kib": 872.08, "write_scale": 1.0,
 }
 GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
