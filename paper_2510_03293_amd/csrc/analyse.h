@@ -23,7 +23,8 @@ namespace laser {
 
 template <int CTRL>
 __device__ __forceinline__ int dpp_int(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+  // bound_ctrl: lanes whose source does not exist read 0 (no prior value to keep)
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
 }
 template <int CTRL>
 __device__ __forceinline__ float dpp_float(float v) {
@@ -92,8 +93,20 @@ __device__ __forceinline__ int key_expert(double key) {
 __device__ __forceinline__ float key_logit(double key) {
   return (float)__longlong_as_double(__double_as_longlong(key) & ~63LL);
 }
+// Keys are never NaN, so the bare instructions do; the library max/min would first
+// pass every operand through a quieting operation of its own.
+__device__ __forceinline__ double key_max(double a, double b) {
+  double r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ double key_min(double a, double b) {
+  double r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 __device__ __forceinline__ void order_pair(double& hi, double& lo) {
-  const double a = __builtin_fmax(hi, lo), b = __builtin_fmin(hi, lo);
+  const double a = key_max(hi, lo), b = key_min(hi, lo);
   hi = a;
   lo = b;
 }
@@ -137,7 +150,7 @@ template <int CT, int CTRL>
 __device__ __forceinline__ void merge_with_partner(double (&L)[CT]) {
   double M[CT];
 #pragma unroll
-  for (int i = 0; i < CT; ++i) M[i] = __builtin_fmax(L[i], dpp_double<CTRL>(L[CT - 1 - i]));
+  for (int i = 0; i < CT; ++i) M[i] = key_max(L[i], dpp_double<CTRL>(L[CT - 1 - i]));
 #pragma unroll
   for (int stride = CT / 2; stride >= 1; stride /= 2)
 #pragma unroll

@@ -16,7 +16,7 @@ constexpr int kMaxC = 16;        // trimming size limit (candidate ranks fit 4 b
 struct RouteArgs {
   int T;            // tokens
   int E;            // experts
-  int EP;           // experts padded to 8/16/32/64 (4 lanes per token x EP/4 each)
+  int EP;           // experts padded to 8/16/32/64 (8 lanes per token x EP/8 each)
   int k;            // experts per token
   int c;            // trimming size
   int ntiles;       // ceil(T / kTile)
