@@ -199,6 +199,67 @@ def main():
                   "max_over_mean_load": float(np.mean(lo_s.max(1) / lo_s.mean(1))),
                   "note": "every token load-dependent (eps_high=2, t_fix=1e-30): chain-bound"}
 
+    # ---- context figures (none of them enters `value`) --------------------------
+    extras = {}
+    # the box's own ceiling: a plain kernel reads the same number of bytes per launch
+    # as the gate kernel reads activations, from one buffer far beyond the cache
+    flat = torch.cat([h.view(torch.uint8).reshape(-1) for h in hidden])
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
+    read_ms, read_n = B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
+    read_s = (read_ms * 1e-3 - event_overhead_s) / max(read_n, 1)
+    extras["plain_read"] = {"bytes_per_launch": T * H * sz, "us_per_launch": read_s * 1e6,
+                            "GBps": T * H * sz / read_s / 1e9, "launches": read_n}
+    del flat
+
+    # plain top-k on the same inputs (c = k: every token keeps its k best)
+    p_topk = B.make_params(k, k, 0.5, 0.5, dtype=s.dtype)
+    loads.zero_()
+    for layer in range(layers):
+        B.laser_route(hidden[layer], wgate[layer], T, H, E, p_topk, loads_of[layer],
+                      buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
+                      buf.workspace, stream)
+    lo_k = loads.cpu().numpy().astype(np.float64)
+    extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
+
+    # run-to-run determinism: one layer twice into separate buffers, every output bit
+    buf2 = B.RouteBuffers(T, H, E, params[0])
+    l1 = torch.zeros(E, dtype=torch.int32, device="cuda")
+    l2 = torch.zeros_like(l1)
+    for bb, ll in ((buf, l1), (buf2, l2)):
+        B.laser_route(hidden[0], wgate[0], T, H, E, p_stress, ll, bb.expert_ids, bb.weights,
+                      bb.permutation, bb.expert_offsets, None, bb.workspace, stream)
+    torch.cuda.synchronize()
+    extras["bit_identical_rerun"] = bool(
+        torch.equal(buf.expert_ids, buf2.expert_ids) and torch.equal(buf.permutation, buf2.permutation)
+        and torch.equal(buf.weights.view(torch.int32), buf2.weights.view(torch.int32))
+        and torch.equal(buf.expert_offsets, buf2.expert_offsets) and torch.equal(l1, l2))
+    del buf2
+
+    # decode-shaped calls (64 tokens per call, loads carried): launch-latency-bound
+    sd = wl.SHAPES["decode"]
+    wdec = wl.decode_gate_weight()
+    wdec_d = torch.from_numpy(wdec.view(np.int16)).view(torch.bfloat16).cuda()
+    hdec = [torch.from_numpy(wl.layer_inputs("decode", i, w=wdec)["hidden"].view(np.int16))
+            .view(torch.bfloat16).cuda() for i in range(16)]
+    eps_d, tfix_d = wl.thresholds("decode", 0, args.preset)
+    p_dec = B.make_params(sd.k, sd.c, eps_d, tfix_d, dtype=sd.dtype)
+    bufd = B.RouteBuffers(sd.T, sd.H, sd.E, p_dec)
+    ld = torch.zeros(sd.E, dtype=torch.int32, device="cuda")
+
+    def decode_steps(n):
+        for i in range(n):
+            B.laser_route(hdec[i % len(hdec)], wdec_d, sd.T, sd.H, sd.E, p_dec, ld, bufd.expert_ids,
+                          bufd.weights, bufd.permutation, bufd.expert_offsets, None,
+                          bufd.workspace, stream)
+    decode_steps(32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    decode_steps(512)
+    torch.cuda.synchronize()
+    extras["decode_us_per_call"] = (time.perf_counter() - t0) * 1e6 / 512
+    extras["decode_tokens_per_call"] = sd.T
+
     out = {
         "metric": "routed tokens/sec + % HBM roofline (fused gate+route+dispatch); max/mean load",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -215,6 +276,7 @@ def main():
             "kernel": "gate_analyse_bf16_kernel", "avg_launch_us": gate_avg_s * 1e6,
             "algorithmic_bytes_per_launch": gate_bytes,
             "event_pair_overhead_us": event_overhead_s * 1e6,
+            "other_kernels_us_per_layer": ms_per_step * 1e3 / layers - gate_avg_s * 1e6,
         },
         "whole_path": {
             "us_per_layer": ms_per_step * 1e3 / layers,
@@ -223,6 +285,7 @@ def main():
         },
         "max_over_mean_load": imbalance,
         "chain_stress": stress,
+        "context": extras,
     }
     if not args.no_cpu_baseline:
         base, expanded, flexible = cpu_baseline(args.workload, args.preset, args.cpu_seconds)

@@ -131,6 +131,19 @@ int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches);
  */
 int laser_profile_event_overhead(void* hip_stream, double* overhead_ms);
 
+/*
+ * The box's own ceiling for a streaming read, for benchmarks: a plain kernel (16-byte
+ * loads, nothing else) reads `bytes` of `device_buf` (device pointer, 16-byte
+ * aligned) in back-to-back launches of `bytes_per_launch` (a multiple of 16; a last
+ * partial piece is skipped) on `hip_stream`, bracketed by one HIP event pair; the call
+ * synchronises and returns the elapsed milliseconds and the number of launches (host
+ * pointers).  `device_sink` is a device word the kernel may write.  Pass a buffer
+ * well beyond the 256 MB last-level cache to measure HBM.
+ */
+int laser_profile_plain_read(const void* device_buf, size_t bytes, size_t bytes_per_launch,
+                             void* device_sink, void* hip_stream, double* ms_total,
+                             int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

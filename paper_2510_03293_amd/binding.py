@@ -21,7 +21,7 @@ TRIM_RANDOM = 1
 
 EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_from_logits",
            "laser_strerror", "laser_profile_enable", "laser_profile_read",
-           "laser_profile_event_overhead")
+           "laser_profile_event_overhead", "laser_profile_plain_read")
 
 
 class LaserParams(ctypes.Structure):
@@ -65,6 +65,9 @@ def _load() -> ctypes.CDLL:
     lib.laser_profile_read.restype = ctypes.c_int
     lib.laser_profile_event_overhead.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     lib.laser_profile_event_overhead.restype = ctypes.c_int
+    lib.laser_profile_plain_read.argtypes = [vp, sz, sz, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_int64)]
+    lib.laser_profile_plain_read.restype = ctypes.c_int
     return lib
 
 
@@ -133,6 +136,17 @@ def laser_profile_event_overhead(stream=None) -> float:
     ms = ctypes.c_double(0.0)
     _check(_lib.laser_profile_event_overhead(_stream_handle(stream), ctypes.byref(ms)))
     return ms.value
+
+
+def laser_profile_plain_read(buf, bytes_per_launch: int, sink, stream=None):
+    """(milliseconds, launches) of a plain streaming read of `buf` in pieces."""
+    ms = ctypes.c_double(0.0)
+    n = ctypes.c_int64(0)
+    nbytes = buf.numel() * buf.element_size()
+    _check(_lib.laser_profile_plain_read(
+        ctypes.c_void_p(buf.data_ptr()), ctypes.c_size_t(nbytes), ctypes.c_size_t(bytes_per_launch),
+        ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream), ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 class RouteBuffers:

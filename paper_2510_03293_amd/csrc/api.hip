@@ -75,6 +75,26 @@ __global__ void spin_kernel(long long ticks) {
   }
 }
 
+// Reads `n16` 16-byte words and keeps nothing: the plain streaming read that other
+// kernels' bandwidth is compared with.  The xor keeps the loads alive; the store
+// never happens for real data streams short of a 2^-32 coincidence per thread, and
+// `sink` is a valid device word in any case.
+__global__ __launch_bounds__(256) void plain_read_kernel(const uint4* __restrict__ p, size_t n16,
+                                                         unsigned* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  unsigned x = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+    x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = p[i];
+    x ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (x == 0x9E3779B9u) *sink = x;
+}
+
 struct Profile {
   std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after the gate kernel
   int used = 0;                // pairs recorded
@@ -257,6 +277,44 @@ int laser_profile_event_overhead(void* hip_stream, double* overhead_ms) {
   if (rc != LASER_OK) return rc;
   std::sort(ms.begin(), ms.end());
   *overhead_ms = (double)ms[reps / 2] - 0.010;
+  return LASER_OK;
+}
+
+int laser_profile_plain_read(const void* device_buf, size_t bytes, size_t bytes_per_launch,
+                             void* device_sink, void* hip_stream, double* ms_total,
+                             int64_t* launches) {
+  if (!device_buf || !device_sink || !ms_total || !launches) return LASER_E_NULL;
+  if (bytes == 0 || bytes_per_launch == 0 || (bytes_per_launch & 15) != 0 ||
+      (reinterpret_cast<uintptr_t>(device_buf) & 15) != 0)
+    return LASER_E_RANGE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return LASER_E_LAUNCH;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return LASER_E_LAUNCH;
+  }
+  int rc = LASER_OK;
+  int64_t n = 0;
+  if (hipEventRecord(e0, s) != hipSuccess) rc = LASER_E_LAUNCH;
+  for (size_t off = 0; rc == LASER_OK && off + bytes_per_launch <= bytes; off += bytes_per_launch) {
+    const size_t n16 = bytes_per_launch >> 4;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 2048);
+    hipLaunchKernelGGL(plain_read_kernel, dim3(blocks), dim3(256), 0, s,
+                       reinterpret_cast<const uint4*>(static_cast<const char*>(device_buf) + off), n16,
+                       static_cast<unsigned*>(device_sink));
+    if (hipGetLastError() != hipSuccess) rc = LASER_E_LAUNCH;
+    ++n;
+  }
+  float ms = 0.0f;
+  if (rc == LASER_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                         hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+    rc = LASER_E_LAUNCH;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != LASER_OK) return rc;
+  *ms_total = ms;
+  *launches = n;
   return LASER_OK;
 }
 
