@@ -362,8 +362,9 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(itok));
       if (q < 4) {
         // ranks 4q..4q+3 of the ordered list go out through lane q
-        unsigned idw = 0, cidw = 0;
+        unsigned idw = 0, cidw = 0, prefw = 0;
         float pv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        const unsigned long long earlier = lanes_below(itok);
         // the chain reads exactly CP candidate lanes per token: ranks beyond the working
         // set point at a lane that holds no candidate (its key compares as largest)
         int padlane = a.E;  // lanes E..63 never hold a candidate
@@ -381,11 +382,15 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
             idw |= (unsigned)ej << (8 * (j & 3));
             cidw |= (unsigned)(j < cstar ? ej : padlane) << (8 * (j & 3));
             pv[j & 3] = j < CT ? ptop[j < CT ? j : 0] : 0.0f;
+            // fixed tokens of the tile before this one that were assigned to candidate j
+            const int fwj = j < cstar ? __builtin_popcountll(mask64[ej] & earlier) : 0;
+            prefw |= (unsigned)fwj << (8 * (j & 3));
           }
         }
         reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
         reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
         reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
+        reinterpret_cast<unsigned*>(ws.rec_pref)[(size_t)slot * 4 + q] = prefw;
       }
       // per owned expert: rank in the working set and the number of earlier fixed
       // tokens of this tile assigned to it; row in expert order

@@ -14,8 +14,8 @@ namespace laser {
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_out,
-      flex_list, flex_ord, gsnap, rec_cids, status, total;
+  size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_bits,
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, status, total;
 };
 
 static Layout layout(int T, int E, bool need_logits) {
@@ -33,11 +33,15 @@ static Layout layout(int T, int E, bool need_logits) {
   L.flexmask = off;   off += align_up(ntiles * 8);
   L.fixed_cnt = off;  off += align_up(ntiles * 64);
   L.base = off;       off += align_up(ntiles * 64 * 4);
-  L.chain_out = off;  off += align_up(ntiles * 2 * 64 * 4);
+  const size_t words = (size_t)T / 32 + 2;
+  L.chain_bits = off; off += align_up(words * 64 * 4);
+  L.chain_cum = off;  off += align_up(words * 64 * 4);
   L.rec_cids = off;   off += align_up(slots * 16);
+  L.rec_pref = off;   off += align_up(slots * 16);
   L.flex_list = off;  off += align_up(ntiles * 4);
   L.flex_ord = off;   off += align_up(ntiles * 4);
-  L.gsnap = off;      off += align_up(ntiles * 64 * 4);
+  L.flex_tok_base = off; off += align_up((ntiles + 1) * 4);
+  L.flex_slot = off;  off += align_up((size_t)T * 4);
   L.status = off;     off += align_up(16);
   L.total = off + 256;
   return L;
@@ -58,11 +62,14 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.flexmask = reinterpret_cast<unsigned long long*>(b + L.flexmask);
   w.tile_fixed_cnt = reinterpret_cast<uint8_t*>(b + L.fixed_cnt);
   w.tile_base = reinterpret_cast<int32_t*>(b + L.base);
-  w.chain_out = reinterpret_cast<uint32_t*>(b + L.chain_out);
+  w.chain_bits = reinterpret_cast<uint32_t*>(b + L.chain_bits);
+  w.chain_cum = reinterpret_cast<int32_t*>(b + L.chain_cum);
   w.rec_cids = reinterpret_cast<uint8_t*>(b + L.rec_cids);
+  w.rec_pref = reinterpret_cast<uint8_t*>(b + L.rec_pref);
   w.flex_list = reinterpret_cast<int32_t*>(b + L.flex_list);
   w.flex_ord = reinterpret_cast<int32_t*>(b + L.flex_ord);
-  w.gsnap = reinterpret_cast<int32_t*>(b + L.gsnap);
+  w.flex_tok_base = reinterpret_cast<int32_t*>(b + L.flex_tok_base);
+  w.flex_slot = reinterpret_cast<int32_t*>(b + L.flex_slot);
   w.status = reinterpret_cast<int32_t*>(b + L.status);
   return w;
 }

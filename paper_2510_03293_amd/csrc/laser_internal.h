@@ -39,13 +39,16 @@ struct Workspace {
   unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
   uint8_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens (<= 64)
   int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
-  uint32_t* chain_out;         // [ntiles,2,64] per expert: bit r%32 of word r/32 = chosen for
-                               //           the tile's r-th flexible token
   uint8_t* rec_cids;           // [slot,16] lanes the chain reads: candidates by rank, padded
+  uint8_t* rec_pref;           // [slot,16] per candidate (by rank): earlier fixed tokens of the
+                               //           tile assigned to it (<= 63)
   int32_t* flex_list;          // [ntiles]  tiles that hold flexible tokens, ascending
   int32_t* flex_ord;           // [ntiles]  number of such tiles before this tile
-  int32_t* gsnap;              // [ntiles,64] flexible assignments up to the end of the
-                               //           f-th flexible tile, per expert
+  int32_t* flex_tok_base;      // [ntiles+1] flexible tokens in earlier tiles; [ntiles] = all
+  int32_t* flex_slot;          // [T]       slot of the f-th flexible token (token order)
+  uint32_t* chain_bits;        // [T/32+1,64] per expert: bit f%32 of word f/32 = chosen for
+                               //           the f-th flexible token
+  int32_t* chain_cum;          // [T/32+2,64] per expert: choices by flexible tokens < 32*w
   int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
 };
 

@@ -146,10 +146,10 @@ __device__ __forceinline__ bool poll_flag(const int* flag, int want) {
   return false;
 }
 
-__device__ void chain_prefetch(ChainBatch* dst, int batch, int nflex_tiles, const RouteArgs& a,
+__device__ void chain_prefetch(ChainBatch* dst, int batch, int ft0, int nflex_tiles, const RouteArgs& a,
                                const Workspace& ws, int hwave, int lane) {
   for (int tl = hwave; tl < kChainBatch; tl += kChainWaves - 1) {
-    const int f = batch * kChainBatch + tl;
+    const int f = ft0 + batch * kChainBatch + tl;
     if (f >= nflex_tiles) return;
     const int tile = ws.flex_list[f];
     const int n = __builtin_popcountll(ws.flexmask[tile]);
@@ -212,38 +212,45 @@ __device__ __forceinline__ bool chain_step(unsigned key, bool cand, const uint4 
   return cand && smaller < k;
 }
 
+// Sequential walk (wave 0, lane = expert) over the flexible tiles from flexible tile
+// `ft0`, record `r_start` of that tile, which is flexible token `f0` of the call;
+// `hist0` holds the bits of output word f0/32 that are decided already.  The output
+// (chain_bits, chain_cum) is indexed by the flexible token's number within the call.
 template <int CP>
-__device__ __forceinline__ void chain_walk(ChainBatch* buf, int nflex_tiles, const RouteArgs& a,
-                                           const Workspace& ws, int wave, int lane, int lin,
-                                           int& gflex) {
-  const int nbatch = (nflex_tiles + kChainBatch - 1) / kChainBatch;
+__device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start, int f0,
+                                           unsigned hist0, int nflex_tiles, const RouteArgs& a, const Workspace& ws,
+                                           int wave, int lane, int lin, int& gflex) {
+  const int nbatch = (nflex_tiles - ft0 + kChainBatch - 1) / kChainBatch;
   const int mypos = lane;  // a record row is in expert order
   const bool lane_ok = lane < a.EP;
   const int EP = a.EP;
   const int k = a.k;
-  if (wave != 0) chain_prefetch(&buf[0], 0, nflex_tiles, a, ws, wave - 1, lane);
+  int f = f0;
+  unsigned hist = hist0;  // bits of the current output word decided before this walk
+  if (wave != 0) chain_prefetch(&buf[0], 0, ft0, nflex_tiles, a, ws, wave - 1, lane);
   __syncthreads();
   for (int b = 0; b < nbatch; ++b) {
     if (wave != 0) {
-      if (b + 1 < nbatch) chain_prefetch(&buf[(b + 1) & 1], b + 1, nflex_tiles, a, ws, wave - 1, lane);
+      if (b + 1 < nbatch) chain_prefetch(&buf[(b + 1) & 1], b + 1, ft0, nflex_tiles, a, ws, wave - 1, lane);
     } else {
       const ChainBatch* cur = &buf[b & 1];
       for (int tl = 0; tl < kChainBatch; ++tl) {
-        const int f = b * kChainBatch + tl;
-        if (f >= nflex_tiles) break;
-        const int tile = __builtin_amdgcn_readfirstlane(cur->tile[tl]);
+        const int ft = ft0 + b * kChainBatch + tl;
+        if (ft >= nflex_tiles) break;
         const int n = __builtin_amdgcn_readfirstlane(cur->nflex[tl]);
         const int fb = cur->base[tl][lane];
-        ws.tile_base[(size_t)tile * 64 + lane] = fb + gflex;
         int lsum = lin + fb + gflex;
+        int r = (ft == ft0) ? r_start : 0;
+        if (r >= n) continue;
         const uint16_t* recp = cur->rec[tl] + (lane_ok ? mypos : 0);
         const uint4* cidp = cur->cids[tl];
-        unsigned rec_next = recp[0];
-        uint4 ids_next = cidp[0];
-        for (int r0 = 0; r0 < n; r0 += 32) {
-          const int r1 = min(n, r0 + 32);
-          unsigned hist = 0;
-          for (int r = r0; r < r1; ++r) {
+        unsigned rec_next = recp[r * EP];
+        uint4 ids_next = cidp[r];
+        while (r < n) {
+          // up to the end of the tile or of the 32-token output word, whichever is first
+          const int sh0 = f & 31;
+          const int seg = min(n - r, 32 - sh0);
+          for (int sh = sh0; sh < sh0 + seg; ++sh, ++r) {
             const unsigned rec = rec_next;
             const uint4 ids = ids_next;
             if (r + 1 < n) {  // next record's LDS reads fly during this step
@@ -254,16 +261,21 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int nflex_tiles, con
             const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
             const bool chosen = chain_step<CP>(key, cand, ids, k);
             lsum += chosen ? 1 : 0;
-            hist |= (chosen ? 1u : 0u) << (r - r0);
+            hist |= (chosen ? 1u : 0u) << sh;
           }
-          ws.chain_out[((size_t)tile * 2 + (r0 >> 5)) * 64 + lane] = hist;
+          f += seg;
+          if ((f & 31) == 0) {
+            ws.chain_bits[(size_t)((f >> 5) - 1) * 64 + lane] = hist;
+            ws.chain_cum[(size_t)(f >> 5) * 64 + lane] = lsum - lin - fb;
+            hist = 0;
+          }
         }
         gflex = lsum - lin - fb;
-        ws.gsnap[(size_t)f * 64 + lane] = gflex;
       }
     }
     __syncthreads();
   }
+  if (wave == 0 && (f & 31) != 0) ws.chain_bits[(size_t)(f >> 5) * 64 + lane] = hist;
 }
 
 __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
@@ -271,7 +283,7 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
                                 int32_t* __restrict__ expert_offsets) {
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
-  __shared__ int wave_flex[kChainWaves];
+  __shared__ int wave_flex[kChainWaves], wave_tok[kChainWaves];
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
@@ -305,21 +317,29 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   const int groups = (ntiles + 63) >> 6;
   const int gper = (groups + kChainWaves - 1) / kChainWaves;
   const int ga = min(wave * gper, groups), gb = min(ga + gper, groups);
-  int nfl = 0;
-  bool first_flex = false;  // this lane's tile of the wave's first group (kept for the second pass)
+  int nfl = 0, ntok = 0;
+  unsigned long long first_fm = 0ull;  // mask of this lane's tile in the wave's first group
   for (int g = ga; g < gb; ++g) {
     const int tile = g * 64 + lane;
-    const bool f = tile < ntiles && ws.flexmask[tile] != 0ull;
-    if (g == ga) first_flex = f;
-    nfl += __builtin_popcountll(__builtin_amdgcn_ballot_w64(f));
+    const unsigned long long fm = tile < ntiles ? ws.flexmask[tile] : 0ull;
+    if (g == ga) first_fm = fm;
+    nfl += __builtin_popcountll(__builtin_amdgcn_ballot_w64(fm != 0ull));
+    ntok += __builtin_popcountll(fm);
   }
-  if (lane == 0) wave_flex[wave] = nfl;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) ntok += __shfl_xor(ntok, d, 64);
+  if (lane == 0) {
+    wave_flex[wave] = nfl;
+    wave_tok[wave] = ntok;
+  }
   __syncthreads();
-  int fbefore = 0, nflex_tiles = 0;
+  int fbefore = 0, nflex_tiles = 0, tokbefore = 0, nflex_tok = 0;  // nflex_tok: flexible tokens of the call
   for (int w = 0; w < kChainWaves; ++w) {
-    const int fl = wave_flex[w];
+    const int fl = wave_flex[w], tk = wave_tok[w];
     fbefore += w < wave ? fl : 0;
+    tokbefore += w < wave ? tk : 0;
     nflex_tiles += fl;
+    nflex_tok += tk;
   }
   // Without flexible tokens, small problems are finished without tile_base (the
   // finishing workgroups sum the byte counts themselves): only the totals are needed.
@@ -360,14 +380,28 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   }
   const int total_fixed = carry;
 
+  // order of the flexible tiles, and for every tile the number of flexible tokens before it
   for (int g = ga; g < gb && nflex_tiles > 0; ++g) {
     const int tile = g * 64 + lane;
-    const bool f = g == ga ? first_flex : (tile < ntiles && ws.flexmask[tile] != 0ull);
+    const unsigned long long fm = g == ga ? first_fm : (tile < ntiles ? ws.flexmask[tile] : 0ull);
+    const bool f = fm != 0ull;
     const unsigned long long bal = __builtin_amdgcn_ballot_w64(f);
     const int ord = fbefore + __builtin_popcountll(bal & lanes_below(lane));
-    if (tile < ntiles) ws.flex_ord[tile] = ord;
+    const int np = __builtin_popcountll(fm);
+    int incl = np;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (tile < ntiles) {
+      ws.flex_ord[tile] = ord;
+      ws.flex_tok_base[tile] = tokbefore + incl - np;
+      if (tile == ntiles - 1) ws.flex_tok_base[ntiles] = tokbefore + incl;
+    }
     if (f) ws.flex_list[ord] = tile;
     fbefore += __builtin_popcountll(bal);
+    tokbefore += __shfl(incl, 63, 64);
   }
 
   int gflex = 0;  // flexible assignments so far (meaningful in wave 0)
@@ -393,14 +427,13 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   }
   if (nflex_tiles == 0) return;
 
+  if (wave == 0) ws.chain_cum[lane] = 0;  // nothing chosen before flexible token 0
   if (a.c <= 4)
-    chain_walk<4>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    chain_walk<4>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
   else if (a.c <= 8)
-    chain_walk<8>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    chain_walk<8>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
   else
-    chain_walk<16>(buf, nflex_tiles, a, ws, wave, lane, lin, gflex);
-  // (tiles without flexible tokens still lack the flexible choices made before them:
-  // their finishing waves add gsnap[flex_ord - 1] themselves)
+    chain_walk<16>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
   if (wave == 0) write_totals();
   __syncthreads();
   if (threadIdx.x == 0)
@@ -409,13 +442,10 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
 
 struct FinishLds {
   unsigned long long mask64[64];
+  int before[64];  // per expert: slots of all earlier experts + of this expert in earlier tiles
   uint8_t ids[kTile][kMaxC];
 };
 
-// One wavefront, one tile; `fl` is this wave's private LDS.
-// If `self` is set the caller has already computed, for every expert, the number of
-// assignments in earlier tiles (own_base, LDS, 64 words) and the exclusive prefix over
-// experts of the totals (own_offsets, LDS, 64 words); nothing is awaited then.
 // What a finishing wave can read before anything else of the tail kernel has run.
 struct FinishPrologue {
   int cstar;               // working-set size of a flexible token, else 0
@@ -439,6 +469,10 @@ __device__ __forceinline__ FinishPrologue finish_prologue(FinishLds* fl, int til
   return p;
 }
 
+// One wavefront, one tile; `fl` is this wave's private LDS.
+// If `self` is set the caller has already computed, for every expert, the number of
+// assignments in earlier tiles (own_base, LDS, 64 words) and the exclusive prefix over
+// experts of the totals (own_offsets, LDS, 64 words); nothing is awaited then.
 __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, const RouteArgs& a,
                             const Workspace& ws, const int32_t* __restrict__ expert_offsets,
                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
@@ -464,19 +498,34 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     }
   }
 
-  // a tile without flexible tokens got only the fixed tokens' prefix as tile_base; the
-  // flexible choices made before it are in gsnap at the end of the previous flexible tile
-  int flex_ord_before = 0;
-  if (!self && fm == 0ull && any_flex) flex_ord_before = load_published(&ws.flex_ord[tile]);
+  // lane = expert: where this tile's first slot of the expert goes.  With flexible
+  // tokens about, the choices made for the f0 flexible tokens of earlier tiles are
+  // the running count at the last 32-token boundary plus the bits since.
+  const int f0 = any_flex ? load_published(&ws.flex_tok_base[tile]) : 0;
+  {
+    int bef;
+    if (self) {
+      bef = own_offsets[lane] + own_base[lane];
+    } else {
+      bef = (lane < a.E ? load_published(&expert_offsets[lane]) : 0) +
+            load_published(&ws.tile_base[(size_t)tile * 64 + lane]);
+      if (any_flex) {
+        const size_t w = (size_t)(f0 >> 5) * 64 + lane;
+        const unsigned bits = load_published(&ws.chain_bits[w]) & ((1u << (f0 & 31)) - 1u);
+        bef += load_published(&ws.chain_cum[w]) + __builtin_popcount(bits);
+      }
+    }
+    fl->before[lane] = bef;
+  }
 
   if (cstar > 0) {
-    const int r = __builtin_popcountll(fm & lanes_below(lane));
-    const unsigned* cw = ws.chain_out + ((size_t)tile * 2 + (r >> 5)) * 64;
+    const int f = f0 + __builtin_popcountll(fm & lanes_below(lane));
+    const unsigned* cw = ws.chain_bits + (size_t)(f >> 5) * 64;
     const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
     const float* pv = ws.rec_p + (size_t)t * 16;
     unsigned long long chosen = 0ull;
     for (int j = 0; j < cstar; ++j)
-      chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (r & 31)) & 1u) << ids[j];
+      chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
     float denom = 0.0f;
     if (a.renormalize) {
       bool first = true;
@@ -512,16 +561,7 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     const unsigned long long below = lanes_below(lane);
     for (int j = 0; j < k; ++j) {
       const int e = fl->ids[lane][j];
-      int before;
-      if (self) {
-        before = own_offsets[e] + own_base[e];
-      } else {
-        before = load_published(&expert_offsets[e]) +
-                 load_published(&ws.tile_base[(size_t)tile * 64 + e]);
-        if (flex_ord_before > 0)  // tile without flexible tokens, after some that have them
-          before += load_published(&ws.gsnap[(size_t)(flex_ord_before - 1) * 64 + e]);
-      }
-      const int pos = before + __builtin_popcountll(fl->mask64[e] & below);
+      const int pos = fl->before[e] + __builtin_popcountll(fl->mask64[e] & below);
       permutation[pos] = t * k + j;
     }
   }
