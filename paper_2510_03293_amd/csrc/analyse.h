@@ -383,7 +383,8 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
             cidw |= (unsigned)(j < cstar ? ej : padlane) << (8 * (j & 3));
             pv[j & 3] = j < CT ? ptop[j < CT ? j : 0] : 0.0f;
             // fixed tokens of the tile before this one that were assigned to candidate j
-            const int fwj = j < cstar ? __builtin_popcountll(mask64[ej] & earlier) : 0;
+            // (0xFF marks the ranks beyond the working set)
+            const int fwj = j < cstar ? __builtin_popcountll(mask64[ej] & earlier) : 0xFF;
             prefw |= (unsigned)fwj << (8 * (j & 3));
           }
         }

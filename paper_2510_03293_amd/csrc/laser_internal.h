@@ -41,7 +41,7 @@ struct Workspace {
   int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
   uint8_t* rec_cids;           // [slot,16] lanes the chain reads: candidates by rank, padded
   uint8_t* rec_pref;           // [slot,16] per candidate (by rank): earlier fixed tokens of the
-                               //           tile assigned to it (<= 63)
+                               //           tile assigned to it (<= 63); 0xFF beyond the working set
   int32_t* flex_list;          // [ntiles]  tiles that hold flexible tokens, ascending
   int32_t* flex_ord;           // [ntiles]  number of such tiles before this tile
   int32_t* flex_tok_base;      // [ntiles+1] flexible tokens in earlier tiles; [ntiles] = all

@@ -278,6 +278,255 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start
   if (wave == 0 && (f & 31) != 0) ws.chain_bits[(size_t)(f >> 5) * 64 + lane] = hist;
 }
 
+// ------------------------------------------------ window evaluation of the chain ----
+//
+// The sequential walk above costs one dependent step per flexible token.  Where
+// consecutive flexible tokens rarely compete for the same experts at nearly equal
+// loads, most of them can be decided side by side.  Wave 0 holds a window of 64
+// consecutive flexible tokens, one per lane, each with a tentative choice.  A sweep
+// re-decides every token of the window against
+//     counters before the window  +  tentative choices of the window tokens before it,
+// all lanes at once.  If q is the first token whose choice changed in a sweep, the new
+// choices of tokens 0..q are final: each was computed from choices that did not change,
+// hence from final ones (induction from the window head, whose inputs are all final).
+// They leave the window, the next tokens enter with an empty tentative choice.  The
+// result is the sequential one exactly, whatever the order of evaluation.  A sweep
+// costs about as much as four sequential steps; if a run of sweeps retires fewer
+// tokens than that, the workgroup goes back to the sequential walk for the rest.
+//
+// Lane = token side: candidates by rank (ids), their counters without any flexible
+// choice (b: loads_in + fixed prefix of the tile + fixed tokens before it inside the
+// tile), tentative choice as a bit mask over ranks.  Lane = expert side, in LDS: the
+// window lanes that tentatively chose the expert (64-bit mask) and the final
+// flexible choices so far (G).  Lane l holds the token f of the window with
+// f % 64 == l, so nothing moves when the window advances.
+//
+// Waves 1 and 2 prepare the per-token data two segments ahead in an LDS ring; the
+// workgroup meets at a barrier once per segment of 128 tokens.
+
+constexpr int kSpecSeg = 128;                 // tokens per segment (64 per producer wave)
+constexpr int kSpecRing = 3 * kSpecSeg;       // tokens in the LDS ring
+constexpr unsigned kSpecInvalid = 1u << 27;   // counter of a rank beyond the working set
+constexpr int kSpecMinTokens = 192;           // fewer flexible tokens: sequential walk
+constexpr int kSpecCheckSweeps = 8;           // progress is judged over this many sweeps ...
+constexpr int kSpecMinProgress = 28;          // ... and must retire at least this many tokens
+
+template <int CP>
+struct SpecTok {
+  uint4 ids;       // candidate experts by rank, one byte each
+  unsigned b[CP];  // their counters without flexible choices
+};
+struct __align__(16) SpecExp {
+  unsigned long long mask;  // window lanes that tentatively chose the expert
+  int G;                    // final flexible choices of the expert so far
+  int pad;
+};
+static_assert(kSpecRing * (int)sizeof(SpecTok<16>) <= kChainLdsBytes, "ring must fit the chain LDS");
+
+template <int N>
+__device__ __forceinline__ void sort_ascending_u32(unsigned (&K)[N]) {
+  constexpr SortNet<N> net = make_sort_net<N>();
+#pragma unroll
+  for (int i = 0; i < net.n; ++i) {
+    const unsigned lo = min(K[net.a[i]], K[net.b[i]]), hi = max(K[net.a[i]], K[net.b[i]]);
+    K[net.a[i]] = lo;
+    K[net.b[i]] = hi;
+  }
+}
+
+__device__ __forceinline__ unsigned long long rotl64(unsigned long long x, int s) {  // s in [0, 63]
+  return s ? (x << s) | (x >> (64 - s)) : x;
+}
+__device__ __forceinline__ unsigned long long rotr64(unsigned long long x, int s) {
+  return s ? (x >> s) | (x << (64 - s)) : x;
+}
+
+// Producer: tokens seg*128 + half*64 + lane of the call -> ring.
+template <int CP>
+__device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, const Workspace& ws,
+                          const int* lin_tab, int lane) {
+  const int f = seg * kSpecSeg + half * 64 + lane;
+  if (f >= nflex_tok) return;
+  const int slot = ws.flex_slot[f];
+  const int tile = slot >> 6;
+  const uint4 ids = reinterpret_cast<const uint4*>(ws.rec_cids)[slot];
+  const uint4 pref = reinterpret_cast<const uint4*>(ws.rec_pref)[slot];
+  const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
+  const unsigned pfw[4] = {pref.x, pref.y, pref.z, pref.w};
+  SpecTok<CP>* dst = &ring[f % kSpecRing];
+  dst->ids = ids;
+  int base[CP];
+#pragma unroll
+  for (int j = 0; j < CP; ++j) {
+    const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+    base[j] = ws.tile_base[(size_t)tile * 64 + e] + lin_tab[e];
+  }
+#pragma unroll
+  for (int j = 0; j < CP; ++j) {
+    const unsigned pf = (pfw[j >> 2] >> (8 * (j & 3))) & 255u;
+    dst->b[j] = pf == 0xFFu ? kSpecInvalid : (unsigned)base[j] + pf;
+  }
+}
+
+// Runs the window evaluation from flexible token 0.  All four waves call it.  Returns
+// (to every wave) the number of flexible tokens decided; wave 0 leaves the flexible
+// choices so far in `gflex` (lane = expert) and the bits of the unfinished output
+// word in `hist`.
+template <int CP>
+__device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
+                         int wave, int lane, int lin, int& gflex, unsigned& hist) {
+  SpecTok<CP>* ring = reinterpret_cast<SpecTok<CP>*>(lds);
+  __shared__ SpecExp M[64];
+  __shared__ int lin_tab[64];
+  __shared__ int sh_done[2], sh_bail[2];  // by segment parity: written before, read after a barrier
+  const int k = a.k;
+  if (wave == 0) {
+    M[lane].mask = 0ull;
+    M[lane].G = 0;
+    lin_tab[lane] = lin;
+  }
+  __syncthreads();
+  const bool producer = wave == 1 || wave == 2;
+  if (producer) {
+    spec_fill<CP>(ring, 0, wave - 1, nflex_tok, ws, lin_tab, lane);
+    spec_fill<CP>(ring, 1, wave - 1, nflex_tok, ws, lin_tab, lane);
+  }
+  __syncthreads();
+
+  // consumer state (wave 0)
+  uint4 ids = make_uint4(0, 0, 0, 0);
+  unsigned b[CP];
+#pragma unroll
+  for (int j = 0; j < CP; ++j) b[j] = kSpecInvalid;
+  unsigned sel = 0;
+  int cur_f = -1;                  // token whose data this lane holds
+  int done = 0;                    // tokens decided (uniform)
+  int G = 0;                       // lane = expert: final flexible choices
+  unsigned long long pend = 0ull;  // lane = expert: decided bits not yet written, from token 32*w
+  int pn = 0, w = 0, gflushed = 0;
+  int sweeps = 0, done_mark = 0;
+  bool bail = false;
+  int decided = 0;
+
+  const int nep = (nflex_tok + kSpecSeg - 1) / kSpecSeg;
+  for (int ep = 0; ep < nep; ++ep) {
+    if (producer) {
+      spec_fill<CP>(ring, ep + 2, wave - 1, nflex_tok, ws, lin_tab, lane);
+    } else if (wave == 0) {
+      const int avail = min(nflex_tok, (ep + 2) * kSpecSeg);
+      const int target = min(nflex_tok, (ep + 1) * kSpecSeg);
+      while (done < target && !bail) {
+        const int head = done & 63;
+        // this lane's token of the window [done, done + 64)
+        const int f_lane = done + ((lane - head) & 63);
+        if (f_lane < avail && cur_f != f_lane) {
+          const SpecTok<CP>* src = &ring[f_lane % kSpecRing];
+          ids = src->ids;
+#pragma unroll
+          for (int j = 0; j < CP; ++j) b[j] = src->b[j];
+          cur_f = f_lane;
+          sel = 0;
+        }
+        const bool valid = cur_f == f_lane;
+        if (!valid) sel = 0;
+        const unsigned long long lb = lanes_below(lane), hb = lanes_below(head);
+        const unsigned long long earlier = lane >= head ? (lb & ~hb) : (~hb | lb);
+        const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
+        unsigned key[CP];
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+          const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+          const uint4 m = *reinterpret_cast<const uint4*>(&M[e]);
+          const unsigned long long mk = ((unsigned long long)m.y << 32) | m.x;
+          const unsigned cnt = (unsigned)__builtin_popcountll(mk & earlier);
+          key[j] = ((b[j] + m.z + cnt) << 4) | (unsigned)j;
+        }
+        sort_ascending_u32<CP>(key);
+        unsigned newsel = 0;
+#pragma unroll
+        for (int i = 0; i < CP; ++i)
+          if (i < k) newsel |= 1u << (key[i] & 15u);
+        newsel = valid ? newsel : 0u;
+        const bool changed = newsel != sel;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(changed);
+        if (bal != 0ull && changed) {
+          const unsigned diff = sel ^ newsel;
+          const unsigned long long bit = 1ull << lane;
+#pragma unroll
+          for (int j = 0; j < CP; ++j) {
+            if ((diff >> j) & 1u) {
+              const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+              if ((newsel >> j) & 1u)
+                atomicOr(&M[e].mask, bit);
+              else
+                atomicAnd(&M[e].mask, ~bit);
+            }
+          }
+        }
+        sel = newsel;
+        // tokens up to the first changed one are final
+        const unsigned long long rot = rotr64(bal, head);
+        const int q = rot ? __builtin_ctzll(rot) : 64;
+        const int nvalid = min(64, avail - done);
+        const int fin = min(q + 1, nvalid);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        {  // lane = expert
+          const unsigned long long span = fin == 64 ? ~0ull : ((1ull << fin) - 1ull);
+          const unsigned long long finmask = rotl64(span, head);
+          const unsigned long long mk = M[lane].mask;
+          const unsigned long long fbits = mk & finmask;
+          G += __builtin_popcountll(fbits);
+          M[lane].mask = mk & ~finmask;
+          M[lane].G = G;
+          const unsigned long long ob = rotr64(fbits, head);  // bit i: token done + i
+          // append to the pending output (pn < 32 bits held), at most 32 bits at a time
+#pragma unroll
+          for (int part = 0; part < 2; ++part) {
+            const int nb = part == 0 ? min(fin, 32) : fin - 32;
+            if (nb > 0) {
+              const unsigned long long piece = (part == 0 ? ob : ob >> 32) & 0xFFFFFFFFull;
+              pend |= piece << pn;
+              pn += nb;
+              if (pn >= 32) {
+                const unsigned word = (unsigned)pend;
+                gflushed += __builtin_popcount(word);
+                ws.chain_bits[(size_t)w * 64 + lane] = word;
+                ws.chain_cum[(size_t)(w + 1) * 64 + lane] = gflushed;
+                pend >>= 32;
+                pn -= 32;
+                ++w;
+              }
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        done += fin;
+        if (++sweeps == kSpecCheckSweeps) {
+          if (done - done_mark < kSpecMinProgress && nflex_tok - done > 2 * kSpecSeg) bail = true;
+          sweeps = 0;
+          done_mark = done;
+        }
+      }
+      if (lane == 0) {
+        sh_done[ep & 1] = done;
+        sh_bail[ep & 1] = bail ? 1 : 0;
+      }
+    }
+    __syncthreads();
+    decided = sh_done[ep & 1];
+    if (sh_bail[ep & 1]) break;
+  }
+  if (wave == 0) {
+    gflex = G;
+    hist = (unsigned)pend;  // the decided % 32 bits of the unfinished word
+    if (decided == nflex_tok && pn > 0) ws.chain_bits[(size_t)w * 64 + lane] = (unsigned)pend;
+  }
+  __syncthreads();  // the ring is dead: the sequential walk may reuse the LDS
+  return decided;
+}
+
 __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
                                 int32_t* __restrict__ loads_inout,
                                 int32_t* __restrict__ expert_offsets) {
@@ -380,6 +629,7 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   }
   const int total_fixed = carry;
 
+  const bool use_spec = nflex_tok >= kSpecMinTokens;
   // order of the flexible tiles, and for every tile the number of flexible tokens before it
   for (int g = ga; g < gb && nflex_tiles > 0; ++g) {
     const int tile = g * 64 + lane;
@@ -400,6 +650,16 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
       if (tile == ntiles - 1) ws.flex_tok_base[ntiles] = tokbefore + incl;
     }
     if (f) ws.flex_list[ord] = tile;
+    if (use_spec) {
+      // slot (tile * 64 + rank among the tile's flexible tokens) of every flexible token
+      const int mybase = tokbefore + incl - np;
+      for (unsigned long long rem = bal; rem != 0ull; rem &= rem - 1ull) {
+        const int src = __builtin_ctzll(rem);
+        const int fbase = __builtin_amdgcn_readlane(mybase, src);
+        const int n_src = __builtin_amdgcn_readlane(np, src);
+        if (lane < n_src) ws.flex_slot[fbase + lane] = ((g * 64 + src) << 6) + lane;
+      }
+    }
     fbefore += __builtin_popcountll(bal);
     tokbefore += __shfl(incl, 63, 64);
   }
@@ -428,12 +688,31 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   if (nflex_tiles == 0) return;
 
   if (wave == 0) ws.chain_cum[lane] = 0;  // nothing chosen before flexible token 0
-  if (a.c <= 4)
-    chain_walk<4>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
-  else if (a.c <= 8)
-    chain_walk<8>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
-  else
-    chain_walk<16>(buf, 0, 0, 0, 0u, nflex_tiles, a, ws, wave, lane, lin, gflex);
+  int decided = 0;
+  unsigned hist0 = 0;
+  if (use_spec) {
+    if (a.c <= 4)
+      decided = spec_walk<4>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    else if (a.c <= 8)
+      decided = spec_walk<8>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    else
+      decided = spec_walk<16>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+  }
+  if (decided < nflex_tok) {
+    // the rest (or everything) one token after the other
+    int ft0 = 0, r0 = 0;
+    if (decided > 0) {
+      const int slot = ws.flex_slot[decided];
+      ft0 = ws.flex_ord[slot >> 6];
+      r0 = slot & 63;
+    }
+    if (a.c <= 4)
+      chain_walk<4>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    else if (a.c <= 8)
+      chain_walk<8>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    else
+      chain_walk<16>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
+  }
   if (wave == 0) write_totals();
   __syncthreads();
   if (threadIdx.x == 0)
