@@ -220,12 +220,17 @@ template <int CP>
 __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start, int f0,
                                            unsigned hist0, int nflex_tiles, const RouteArgs& a, const Workspace& ws,
                                            int wave, int lane, int lin, int& gflex) {
+  // wave-uniform values that arrive through LDS or memory: tell the compiler so, or the
+  // loops below are compiled as divergent ones
+  ft0 = __builtin_amdgcn_readfirstlane(ft0);
+  r_start = __builtin_amdgcn_readfirstlane(r_start);
+  nflex_tiles = __builtin_amdgcn_readfirstlane(nflex_tiles);
   const int nbatch = (nflex_tiles - ft0 + kChainBatch - 1) / kChainBatch;
   const int mypos = lane;  // a record row is in expert order
   const bool lane_ok = lane < a.EP;
   const int EP = a.EP;
   const int k = a.k;
-  int f = f0;
+  int f = __builtin_amdgcn_readfirstlane(f0);
   unsigned hist = hist0;  // bits of the current output word decided before this walk
   if (wave != 0) chain_prefetch(&buf[0], 0, ft0, nflex_tiles, a, ws, wave - 1, lane);
   __syncthreads();
@@ -375,6 +380,7 @@ __device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, c
 template <int CP>
 __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
                          int wave, int lane, int lin, int& gflex, unsigned& hist) {
+  nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
   SpecTok<CP>* ring = reinterpret_cast<SpecTok<CP>*>(lds);
   __shared__ SpecExp M[64];
   __shared__ int lin_tab[64];
@@ -515,8 +521,8 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
       }
     }
     __syncthreads();
-    decided = sh_done[ep & 1];
-    if (sh_bail[ep & 1]) break;
+    decided = __builtin_amdgcn_readfirstlane(sh_done[ep & 1]);
+    if (__builtin_amdgcn_readfirstlane(sh_bail[ep & 1])) break;
   }
   if (wave == 0) {
     gflex = G;
@@ -533,7 +539,9 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
   __shared__ int wave_flex[kChainWaves], wave_tok[kChainWaves];
-  const int wave = threadIdx.x >> 6;
+  // (as a scalar: branches on the wave number are then uniform for the compiler, and
+  // values carried around them stay in scalar registers)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
 
@@ -629,6 +637,8 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   }
   const int total_fixed = carry;
 
+  nflex_tiles = __builtin_amdgcn_readfirstlane(nflex_tiles);
+  nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
   const bool use_spec = nflex_tok >= kSpecMinTokens;
   // order of the flexible tiles, and for every tile the number of flexible tokens before it
   for (int g = ga; g < gb && nflex_tiles > 0; ++g) {

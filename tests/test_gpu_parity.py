@@ -78,6 +78,53 @@ def test_route_from_logits(T, E, k, c, eps, tfix, kind, renorm):
                         label=f"T{T} E{E} k{k} c{c} {kind}")
 
 
+# The chain decides flexible tokens 64 at a time where that pays (a window advancing
+# over them, data staged in segments of 128 through a ring of 384) and one by one
+# otherwise, switching over at an arbitrary token.  Every token here is flexible
+# (eps_high = 2, tiny t_fix), so T is the number of flexible tokens.
+WINDOW_SIZES = [191, 192, 193, 255, 256, 257, 383, 384, 385, 511, 513, 1025, 2000]
+
+
+@pytest.mark.parametrize("T", WINDOW_SIZES)
+@pytest.mark.parametrize("E,k,c", [(64, 6, 8), (8, 2, 4), (40, 3, 16)])
+def test_window_chain_sizes(T, E, k, c):
+    u = _util()
+    rng = np.random.default_rng(T * 7 + E)
+    logits = wl.random_logits(T + 3 * E + c, T, E, kind="normal", scale=0.3)
+    loads_in = rng.integers(0, 1000, size=E).astype(np.int32)
+    u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"window T{T} E{E} k{k} c{c}")
+
+
+@pytest.mark.parametrize("E,k,c,T1,T2", [(64, 6, 8, 3001, 3000), (8, 2, 4, 1237, 5000),
+                                         (64, 6, 12, 700, 2500), (16, 4, 8, 5000, 0)])
+def test_window_chain_gives_way_to_sequential(E, k, c, T1, T2):
+    """First T1 tokens with unrelated candidate sets (decided side by side), then T2
+    identical tokens that all compete for the same experts at equal loads (one by
+    one): the hand-over happens wherever progress drops, mid word and mid tile."""
+    u = _util()
+    rng = np.random.default_rng(E * 1000 + T1)
+    a = wl.random_logits(E + T1, T1, E, kind="normal", scale=1.0)
+    row = wl.random_logits(E + T2 + 1, 1, E, kind="normal", scale=1.0)
+    logits = np.concatenate([a, np.repeat(row, T2, axis=0)], axis=0)
+    loads_in = rng.integers(0, 50, size=E).astype(np.int32)
+    u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"handover E{E} c{c} {T1}+{T2}")
+
+
+def test_window_chain_long_run():
+    """Many segments: the ring wraps dozens of times; flexible tokens are sparse inside
+    their tiles (about one in ten), as in the prefill-shaped workload."""
+    u = _util()
+    T, E, k, c = 40000, 64, 6, 8
+    rng = np.random.default_rng(4242)
+    peaked = wl.random_logits(1, T, E, kind="normal", scale=3.0)
+    flat = wl.random_logits(2, T, E, kind="normal", scale=0.05)
+    pick = rng.random(T) < 0.1
+    logits = np.where(pick[:, None], flat, peaked).astype(np.float32)
+    loads_in = np.zeros(E, np.int32)
+    gpu, ref = u.check_from_logits(logits, k, c, 0.4, 0.8, loads_in, label="window long run")
+    assert int((ref["cstar"] > k).sum()) > 2000
+
+
 def test_extreme_logits():
     """Scores that underflow the clamp, huge spreads, and all-equal rows."""
     u = _util()
