@@ -55,6 +55,7 @@ struct Workspace {
 constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished
 constexpr int kStatusFlexTiles = 1;  // number of tiles that hold flexible tokens
 constexpr int kStatusError = 2;      // a bounded wait in the tail kernel ran out
+constexpr int kStatusSweeps = 3;     // sweeps of the chain's window evaluation (diagnostic)
 
 size_t workspace_bytes(int T, int E, bool need_logits);
 Workspace carve_workspace(void* base, int T, int E, bool need_logits);

@@ -79,23 +79,25 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
 //
 // Chain workgroup (4 wavefronts):
 //   prefix  (all waves)  exclusive prefix over tiles of the fixed tokens' per-expert
-//           counts -> tile_base; ordered list of the tiles that hold flexible tokens.
-//           Then flag 1 is published: tile_base is final for every tile if no tile
-//           holds a flexible token.
-//   chain   (wave 0, lane e = expert e)  walks the flexible tiles in order.  The
-//           counters a flexible token sees are loads_in + fixed prefix of its tile
-//           + fixed tokens before it inside the tile (carried by its record) +
-//           flexible choices so far.  Candidate key = (load << 4) + rank: ascending
-//           load, ties by score rank.  An expert is chosen iff fewer than k
-//           candidate keys are smaller than its own; the candidates' keys are
-//           fetched with one lane read each (CP reads per token, CP = c rounded up
-//           to 4, 8 or 16).  Waves 1..3 copy the next batch of records into LDS
-//           meanwhile, so the chain never waits on memory.
-//   totals  loads and offsets, then flag 2.  (A tile without flexible tokens has only
-//           the fixed prefix in tile_base; its finishing wave adds the flexible
-//           choices made before it, gsnap[flex_ord - 1].)
-//   Output of the chain: for every flexible tile and expert, one bit per flexible
-//   token of the tile (bit r of word r/32: chosen for the tile's r-th flexible token).
+//           counts -> tile_base; ordered list of the tiles that hold flexible tokens;
+//           for every tile the number of flexible tokens before it.  Then flag 1 is
+//           published: everything is final if no tile holds a flexible token.
+//   chain   decides the flexible tokens in token order.  The counters a flexible token
+//           sees are loads_in + fixed prefix of its tile + fixed tokens before it
+//           inside the tile (carried by its record) + flexible choices so far.
+//           Candidate key = (load << 4) + rank: ascending load, ties by score rank; the
+//           k smallest keys win.  Two evaluations, same result:
+//           - window (wave 0, lane = token): 64 consecutive flexible tokens per sweep,
+//             see "window evaluation" below; used first when there are enough tokens;
+//           - sequential (wave 0, lane = expert): an expert is chosen iff fewer than k
+//             candidate keys are smaller than its own; the candidates' keys are fetched
+//             with one lane read each (CP reads per token, CP = c rounded up to 4, 8 or
+//             16).  Takes over where the window evaluation stops paying.
+//           The other waves stage the records in LDS ahead of wave 0.
+//   totals  loads and offsets, then flag 2.
+//   Output of the chain, per expert: one bit per flexible token of the call in token
+//   order (chain_bits, 32 per word) and the running count of chosen bits at every
+//   32-token boundary (chain_cum).
 //
 // Finishing wavefront (lane = token of its tile): loads what does not depend on the
 // chain, waits for flag 1 (and for flag 2 if any tile holds flexible tokens), then
@@ -103,7 +105,9 @@ hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspa
 // bits and places every assignment slot t*k+j at
 //   expert_offsets[e] + (assignments to e in earlier tiles) + (earlier tokens of
 //   this tile assigned to e),
-// which is the stable counting sort of the flat expert_ids array.
+// which is the stable counting sort of the flat expert_ids array.  The middle term is
+// the fixed tokens' prefix (tile_base) plus the flexible choices of earlier tiles
+// (chain_cum at the last boundary + the bits since).
 //
 // The waits are bounded polls of flags that the analysis kernel of the same call
 // cleared; workgroup 0 has the lowest index, is dispatched first and never waits,
@@ -296,7 +300,7 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start
 // hence from final ones (induction from the window head, whose inputs are all final).
 // They leave the window, the next tokens enter with an empty tentative choice.  The
 // result is the sequential one exactly, whatever the order of evaluation.  A sweep
-// costs about as much as four sequential steps; if a run of sweeps retires fewer
+// costs about as much as five sequential steps; if a run of sweeps retires fewer
 // tokens than that, the workgroup goes back to the sequential walk for the rest.
 //
 // Lane = token side: candidates by rank (ids), their counters without any flexible
@@ -306,15 +310,17 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start
 // flexible choices so far (G).  Lane l holds the token f of the window with
 // f % 64 == l, so nothing moves when the window advances.
 //
-// Waves 1 and 2 prepare the per-token data two segments ahead in an LDS ring; the
-// workgroup meets at a barrier once per segment of 128 tokens.
+// Waves 1 to 3 prepare the per-token data two segments ahead in an LDS ring; the
+// workgroup meets at a barrier once per segment of 192 tokens.
 
-constexpr int kSpecSeg = 128;                 // tokens per segment (64 per producer wave)
+constexpr int kSpecSeg = 192;                 // tokens per segment (64 per producer wave)
 constexpr int kSpecRing = 3 * kSpecSeg;       // tokens in the LDS ring
 constexpr unsigned kSpecInvalid = 1u << 27;   // counter of a rank beyond the working set
-constexpr int kSpecMinTokens = 192;           // fewer flexible tokens: sequential walk
+constexpr int kSpecMinTokens = 256;           // fewer flexible tokens: sequential walk
 constexpr int kSpecCheckSweeps = 8;           // progress is judged over this many sweeps ...
-constexpr int kSpecMinProgress = 28;          // ... and must retire at least this many tokens
+// ... in which at least this many tokens must retire (measured: a sweep costs about
+// 0.56 / 0.96 us for 4 / 8 candidates, a sequential step 0.12 / 0.17 us)
+constexpr int spec_min_progress(int cp) { return cp <= 4 ? 40 : cp <= 8 ? 48 : 56; }
 
 template <int CP>
 struct SpecTok {
@@ -346,7 +352,7 @@ __device__ __forceinline__ unsigned long long rotr64(unsigned long long x, int s
   return s ? (x >> s) | (x << (64 - s)) : x;
 }
 
-// Producer: tokens seg*128 + half*64 + lane of the call -> ring.
+// Producer: tokens seg*192 + half*64 + lane of the call -> ring (half = 0, 1, 2).
 template <int CP>
 __device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, const Workspace& ws,
                           const int* lin_tab, int lane) {
@@ -376,8 +382,8 @@ __device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, c
 // Runs the window evaluation from flexible token 0.  All four waves call it.  Returns
 // (to every wave) the number of flexible tokens decided; wave 0 leaves the flexible
 // choices so far in `gflex` (lane = expert) and the bits of the unfinished output
-// word in `hist`.
-template <int CP>
+// word in `hist`.  KK = k when known at compile time, else 0.
+template <int CP, int KK>
 __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
                          int wave, int lane, int lin, int& gflex, unsigned& hist) {
   nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
@@ -385,14 +391,14 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
   __shared__ SpecExp M[64];
   __shared__ int lin_tab[64];
   __shared__ int sh_done[2], sh_bail[2];  // by segment parity: written before, read after a barrier
-  const int k = a.k;
+  const int k = KK > 0 ? KK : a.k;
   if (wave == 0) {
     M[lane].mask = 0ull;
     M[lane].G = 0;
     lin_tab[lane] = lin;
   }
   __syncthreads();
-  const bool producer = wave == 1 || wave == 2;
+  const bool producer = wave != 0;
   if (producer) {
     spec_fill<CP>(ring, 0, wave - 1, nflex_tok, ws, lin_tab, lane);
     spec_fill<CP>(ring, 1, wave - 1, nflex_tok, ws, lin_tab, lane);
@@ -400,25 +406,30 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
   __syncthreads();
 
   // consumer state (wave 0)
-  uint4 ids = make_uint4(0, 0, 0, 0);
-  unsigned b[CP];
+  int ex[CP];       // candidate experts by rank
+  unsigned b[CP];   // their counters without flexible choices
 #pragma unroll
-  for (int j = 0; j < CP; ++j) b[j] = kSpecInvalid;
+  for (int j = 0; j < CP; ++j) {
+    ex[j] = 0;
+    b[j] = kSpecInvalid;
+  }
   unsigned sel = 0;
   int cur_f = -1;                  // token whose data this lane holds
+  int ridx = lane - 64;            // its place in the ring (advances by 64 per token)
   int done = 0;                    // tokens decided (uniform)
   int G = 0;                       // lane = expert: final flexible choices
   unsigned long long pend = 0ull;  // lane = expert: decided bits not yet written, from token 32*w
   int pn = 0, w = 0, gflushed = 0;
-  int sweeps = 0, done_mark = 0;
+  int sweeps = 0, done_mark = 0, total_sweeps = 0;
   bool bail = false;
   int decided = 0;
+  const unsigned long long lane_bit = 1ull << lane, lb = lanes_below(lane);
 
   const int nep = (nflex_tok + kSpecSeg - 1) / kSpecSeg;
   for (int ep = 0; ep < nep; ++ep) {
     if (producer) {
       spec_fill<CP>(ring, ep + 2, wave - 1, nflex_tok, ws, lin_tab, lane);
-    } else if (wave == 0) {
+    } else {
       const int avail = min(nflex_tok, (ep + 2) * kSpecSeg);
       const int target = min(nflex_tok, (ep + 1) * kSpecSeg);
       while (done < target && !bail) {
@@ -426,91 +437,88 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
         // this lane's token of the window [done, done + 64)
         const int f_lane = done + ((lane - head) & 63);
         if (f_lane < avail && cur_f != f_lane) {
-          const SpecTok<CP>* src = &ring[f_lane % kSpecRing];
-          ids = src->ids;
+          ridx += 64;
+          ridx = ridx >= kSpecRing ? ridx - kSpecRing : ridx;
+          const SpecTok<CP>* src = &ring[ridx];
+          const uint4 ids = src->ids;
+          const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
 #pragma unroll
-          for (int j = 0; j < CP; ++j) b[j] = src->b[j];
+          for (int j = 0; j < CP; ++j) {
+            ex[j] = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+            b[j] = src->b[j];
+          }
           cur_f = f_lane;
           sel = 0;
         }
         const bool valid = cur_f == f_lane;
         if (!valid) sel = 0;
-        const unsigned long long lb = lanes_below(lane), hb = lanes_below(head);
+        const unsigned long long hb = lanes_below(head);
         const unsigned long long earlier = lane >= head ? (lb & ~hb) : (~hb | lb);
-        const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
         unsigned key[CP];
 #pragma unroll
         for (int j = 0; j < CP; ++j) {
-          const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
-          const uint4 m = *reinterpret_cast<const uint4*>(&M[e]);
-          const unsigned long long mk = ((unsigned long long)m.y << 32) | m.x;
-          const unsigned cnt = (unsigned)__builtin_popcountll(mk & earlier);
-          key[j] = ((b[j] + m.z + cnt) << 4) | (unsigned)j;
+          const SpecExp* m = &M[ex[j]];
+          const unsigned cnt = (unsigned)__builtin_popcountll(m->mask & earlier);
+          key[j] = ((b[j] + (unsigned)m->G + cnt) << 4) | (unsigned)j;
         }
         sort_ascending_u32<CP>(key);
         unsigned newsel = 0;
+        if (KK > 0) {
 #pragma unroll
-        for (int i = 0; i < CP; ++i)
-          if (i < k) newsel |= 1u << (key[i] & 15u);
+          for (int i = 0; i < KK; ++i) newsel |= 1u << (key[i < CP ? i : 0] & 15u);
+        } else {
+#pragma unroll
+          for (int i = 0; i < CP; ++i)
+            if (i < k) newsel |= 1u << (key[i] & 15u);
+        }
         newsel = valid ? newsel : 0u;
-        const bool changed = newsel != sel;
-        const unsigned long long bal = __builtin_amdgcn_ballot_w64(changed);
-        if (bal != 0ull && changed) {
-          const unsigned diff = sel ^ newsel;
-          const unsigned long long bit = 1ull << lane;
+        const unsigned diff = sel ^ newsel;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(diff != 0u);
+        if (bal != 0ull) {
+          // flip this lane's bit in the masks of the experts whose choice changed
 #pragma unroll
-          for (int j = 0; j < CP; ++j) {
-            if ((diff >> j) & 1u) {
-              const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
-              if ((newsel >> j) & 1u)
-                atomicOr(&M[e].mask, bit);
-              else
-                atomicAnd(&M[e].mask, ~bit);
-            }
-          }
+          for (int j = 0; j < CP; ++j)
+            if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
         }
         sel = newsel;
-        // tokens up to the first changed one are final
+        // tokens up to the first changed one are final (at most 32 per sweep: a token
+        // needs a sweep to get a tentative choice, so more is rare)
         const unsigned long long rot = rotr64(bal, head);
         const int q = rot ? __builtin_ctzll(rot) : 64;
-        const int nvalid = min(64, avail - done);
-        const int fin = min(q + 1, nvalid);
+        const int fin = min(min(q + 1, avail - done), 32);
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __builtin_amdgcn_wave_barrier();
         {  // lane = expert
-          const unsigned long long span = fin == 64 ? ~0ull : ((1ull << fin) - 1ull);
-          const unsigned long long finmask = rotl64(span, head);
+          const unsigned long long finmask = rotl64((1ull << fin) - 1ull, head);
           const unsigned long long mk = M[lane].mask;
           const unsigned long long fbits = mk & finmask;
           G += __builtin_popcountll(fbits);
           M[lane].mask = mk & ~finmask;
           M[lane].G = G;
-          const unsigned long long ob = rotr64(fbits, head);  // bit i: token done + i
-          // append to the pending output (pn < 32 bits held), at most 32 bits at a time
-#pragma unroll
-          for (int part = 0; part < 2; ++part) {
-            const int nb = part == 0 ? min(fin, 32) : fin - 32;
-            if (nb > 0) {
-              const unsigned long long piece = (part == 0 ? ob : ob >> 32) & 0xFFFFFFFFull;
-              pend |= piece << pn;
-              pn += nb;
-              if (pn >= 32) {
-                const unsigned word = (unsigned)pend;
-                gflushed += __builtin_popcount(word);
-                ws.chain_bits[(size_t)w * 64 + lane] = word;
-                ws.chain_cum[(size_t)(w + 1) * 64 + lane] = gflushed;
-                pend >>= 32;
-                pn -= 32;
-                ++w;
-              }
-            }
+          const unsigned ob = (unsigned)rotr64(fbits, head);  // bit i: token done + i
+          pend |= (unsigned long long)ob << pn;               // pn < 32 bits were held
+          pn += fin;
+          if (pn >= 32) {
+            const unsigned word = (unsigned)pend;
+            gflushed += __builtin_popcount(word);
+            ws.chain_bits[(size_t)w * 64 + lane] = word;
+            ws.chain_cum[(size_t)(w + 1) * 64 + lane] = gflushed;
+            pend >>= 32;
+            pn -= 32;
+            ++w;
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __builtin_amdgcn_wave_barrier();
         done += fin;
+        ++total_sweeps;
         if (++sweeps == kSpecCheckSweeps) {
-          if (done - done_mark < kSpecMinProgress && nflex_tok - done > 2 * kSpecSeg) bail = true;
+          // give up only if both the last run of sweeps and the average so far are
+          // below break-even: the switch is one-way
+          if (done - done_mark < spec_min_progress(CP) &&
+              done * kSpecCheckSweeps < spec_min_progress(CP) * total_sweeps &&
+              nflex_tok - done > 2 * kSpecSeg)
+            bail = true;
           sweeps = 0;
           done_mark = done;
         }
@@ -528,6 +536,7 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
     gflex = G;
     hist = (unsigned)pend;  // the decided % 32 bits of the unfinished word
     if (decided == nflex_tok && pn > 0) ws.chain_bits[(size_t)w * 64 + lane] = (unsigned)pend;
+    if (lane == 0) ws.status[kStatusSweeps] = total_sweeps;
   }
   __syncthreads();  // the ring is dead: the sequential walk may reuse the LDS
   return decided;
@@ -701,12 +710,15 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
   int decided = 0;
   unsigned hist0 = 0;
   if (use_spec) {
-    if (a.c <= 4)
-      decided = spec_walk<4>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
-    else if (a.c <= 8)
-      decided = spec_walk<8>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
-    else
-      decided = spec_walk<16>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    if (a.c <= 4) {
+      decided = a.k == 2 ? spec_walk<4, 2>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0)
+                         : spec_walk<4, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    } else if (a.c <= 8) {
+      decided = a.k == 6 ? spec_walk<8, 6>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0)
+                         : spec_walk<8, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    } else {
+      decided = spec_walk<16, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+    }
   }
   if (decided < nflex_tok) {
     // the rest (or everything) one token after the other

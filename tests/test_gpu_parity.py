@@ -79,10 +79,10 @@ def test_route_from_logits(T, E, k, c, eps, tfix, kind, renorm):
 
 
 # The chain decides flexible tokens 64 at a time where that pays (a window advancing
-# over them, data staged in segments of 128 through a ring of 384) and one by one
+# over them, data staged in segments of 192 through a ring of 576) and one by one
 # otherwise, switching over at an arbitrary token.  Every token here is flexible
 # (eps_high = 2, tiny t_fix), so T is the number of flexible tokens.
-WINDOW_SIZES = [191, 192, 193, 255, 256, 257, 383, 384, 385, 511, 513, 1025, 2000]
+WINDOW_SIZES = [191, 192, 193, 255, 256, 257, 383, 384, 385, 511, 513, 575, 576, 577, 1025, 2000]
 
 
 @pytest.mark.parametrize("T", WINDOW_SIZES)
