@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # Valid only for the kernel sources they were taken on: the record carries their hash
 # and `traffic` is reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "47c57db431fef888",
+    "sources_sha256_16": "969bf94d1e3e4897",
     "workload": "deepseek",
-    "fetch_kib": 33907.69, "fetch_scale": 1.9997,
+    "fetch_kib": 33910.46, "fetch_scale": 1.9997,
     "write_kib": 872.08, "write_scale": 1.0,
 }
 GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-chain-stress", action="store_true",
                     help="skip the extra full-duty chain measurement (keeps kernel traces to the timed workload)")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the context figures (plain read, top-k, rerun, decode calls)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -201,64 +203,65 @@ def main():
 
     # ---- context figures (none of them enters `value`) --------------------------
     extras = {}
-    # the box's own ceiling: a plain kernel reads the same number of bytes per launch
-    # as the gate kernel reads activations, from one buffer far beyond the cache
-    flat = torch.cat([h.view(torch.uint8).reshape(-1) for h in hidden])
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
-    read_ms, read_n = B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
-    read_s = (read_ms * 1e-3 - event_overhead_s) / max(read_n, 1)
-    extras["plain_read"] = {"bytes_per_launch": T * H * sz, "us_per_launch": read_s * 1e6,
-                            "GBps": T * H * sz / read_s / 1e9, "launches": read_n}
-    del flat
+    if not args.no_context:
+        # the box's own ceiling: a plain kernel reads the same number of bytes per launch
+        # as the gate kernel reads activations, from one buffer far beyond the cache
+        flat = torch.cat([h.view(torch.uint8).reshape(-1) for h in hidden])
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
+        read_ms, read_n = B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
+        read_s = (read_ms * 1e-3 - event_overhead_s) / max(read_n, 1)
+        extras["plain_read"] = {"bytes_per_launch": T * H * sz, "us_per_launch": read_s * 1e6,
+                                "GBps": T * H * sz / read_s / 1e9, "launches": read_n}
+        del flat
 
-    # plain top-k on the same inputs (c = k: every token keeps its k best)
-    p_topk = B.make_params(k, k, 0.5, 0.5, dtype=s.dtype)
-    loads.zero_()
-    for layer in range(layers):
-        B.laser_route(hidden[layer], wgate[layer], T, H, E, p_topk, loads_of[layer],
-                      buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                      buf.workspace, stream)
-    lo_k = loads.cpu().numpy().astype(np.float64)
-    extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
+        # plain top-k on the same inputs (c = k: every token keeps its k best)
+        p_topk = B.make_params(k, k, 0.5, 0.5, dtype=s.dtype)
+        loads.zero_()
+        for layer in range(layers):
+            B.laser_route(hidden[layer], wgate[layer], T, H, E, p_topk, loads_of[layer],
+                          buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
+                          buf.workspace, stream)
+        lo_k = loads.cpu().numpy().astype(np.float64)
+        extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
 
-    # run-to-run determinism: one layer twice into separate buffers, every output bit
-    buf2 = B.RouteBuffers(T, H, E, params[0])
-    l1 = torch.zeros(E, dtype=torch.int32, device="cuda")
-    l2 = torch.zeros_like(l1)
-    for bb, ll in ((buf, l1), (buf2, l2)):
-        B.laser_route(hidden[0], wgate[0], T, H, E, p_stress, ll, bb.expert_ids, bb.weights,
-                      bb.permutation, bb.expert_offsets, None, bb.workspace, stream)
-    torch.cuda.synchronize()
-    extras["bit_identical_rerun"] = bool(
-        torch.equal(buf.expert_ids, buf2.expert_ids) and torch.equal(buf.permutation, buf2.permutation)
-        and torch.equal(buf.weights.view(torch.int32), buf2.weights.view(torch.int32))
-        and torch.equal(buf.expert_offsets, buf2.expert_offsets) and torch.equal(l1, l2))
-    del buf2
+        # run-to-run determinism: one layer twice into separate buffers, every output bit
+        buf2 = B.RouteBuffers(T, H, E, params[0])
+        l1 = torch.zeros(E, dtype=torch.int32, device="cuda")
+        l2 = torch.zeros_like(l1)
+        for bb, ll in ((buf, l1), (buf2, l2)):
+            B.laser_route(hidden[0], wgate[0], T, H, E, p_stress, ll, bb.expert_ids, bb.weights,
+                          bb.permutation, bb.expert_offsets, None, bb.workspace, stream)
+        torch.cuda.synchronize()
+        extras["bit_identical_rerun"] = bool(
+            torch.equal(buf.expert_ids, buf2.expert_ids) and torch.equal(buf.permutation, buf2.permutation)
+            and torch.equal(buf.weights.view(torch.int32), buf2.weights.view(torch.int32))
+            and torch.equal(buf.expert_offsets, buf2.expert_offsets) and torch.equal(l1, l2))
+        del buf2
 
-    # decode-shaped calls (64 tokens per call, loads carried): launch-latency-bound
-    sd = wl.SHAPES["decode"]
-    wdec = wl.decode_gate_weight()
-    wdec_d = torch.from_numpy(wdec.view(np.int16)).view(torch.bfloat16).cuda()
-    hdec = [torch.from_numpy(wl.layer_inputs("decode", i, w=wdec)["hidden"].view(np.int16))
-            .view(torch.bfloat16).cuda() for i in range(16)]
-    eps_d, tfix_d = wl.thresholds("decode", 0, args.preset)
-    p_dec = B.make_params(sd.k, sd.c, eps_d, tfix_d, dtype=sd.dtype)
-    bufd = B.RouteBuffers(sd.T, sd.H, sd.E, p_dec)
-    ld = torch.zeros(sd.E, dtype=torch.int32, device="cuda")
+        # decode-shaped calls (64 tokens per call, loads carried): launch-latency-bound
+        sd = wl.SHAPES["decode"]
+        wdec = wl.decode_gate_weight()
+        wdec_d = torch.from_numpy(wdec.view(np.int16)).view(torch.bfloat16).cuda()
+        hdec = [torch.from_numpy(wl.layer_inputs("decode", i, w=wdec)["hidden"].view(np.int16))
+                .view(torch.bfloat16).cuda() for i in range(16)]
+        eps_d, tfix_d = wl.thresholds("decode", 0, args.preset)
+        p_dec = B.make_params(sd.k, sd.c, eps_d, tfix_d, dtype=sd.dtype)
+        bufd = B.RouteBuffers(sd.T, sd.H, sd.E, p_dec)
+        ld = torch.zeros(sd.E, dtype=torch.int32, device="cuda")
 
-    def decode_steps(n):
-        for i in range(n):
-            B.laser_route(hdec[i % len(hdec)], wdec_d, sd.T, sd.H, sd.E, p_dec, ld, bufd.expert_ids,
-                          bufd.weights, bufd.permutation, bufd.expert_offsets, None,
-                          bufd.workspace, stream)
-    decode_steps(32)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    decode_steps(512)
-    torch.cuda.synchronize()
-    extras["decode_us_per_call"] = (time.perf_counter() - t0) * 1e6 / 512
-    extras["decode_tokens_per_call"] = sd.T
+        def decode_steps(n):
+            for i in range(n):
+                B.laser_route(hdec[i % len(hdec)], wdec_d, sd.T, sd.H, sd.E, p_dec, ld, bufd.expert_ids,
+                              bufd.weights, bufd.permutation, bufd.expert_offsets, None,
+                              bufd.workspace, stream)
+        decode_steps(32)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        decode_steps(512)
+        torch.cuda.synchronize()
+        extras["decode_us_per_call"] = (time.perf_counter() - t0) * 1e6 / 512
+        extras["decode_tokens_per_call"] = sd.T
 
     out = {
         "metric": "routed tokens/sec + % HBM roofline (fused gate+route+dispatch); max/mean load",
