@@ -43,9 +43,22 @@ __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ 
   const int E = a.E;
   const int rows = min(kTile, a.T - tile * kTile);
   const float* src = logits + (size_t)tile * kTile * E;
-  for (int idx = threadIdx.x; idx < rows * E; idx += 512) {
-    const int tok = idx / E;
-    lz[tok * ZS + (idx - tok * E)] = src[idx];
+  // at most 8 elements per thread (64 tokens x 64 experts / 512); every load is issued
+  // before the first use, so the tile costs one memory latency, not one per element
+  constexpr int kPer = kTile * kMaxE / 512;
+  float x[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int idx = threadIdx.x + u * 512;
+    x[u] = idx < rows * E ? src[idx] : 0.0f;
+  }
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int idx = threadIdx.x + u * 512;
+    if (idx < rows * E) {
+      const int tok = idx / E;
+      lz[tok * ZS + (idx - tok * E)] = x[u];
+    }
   }
   __syncthreads();
   analyse_tile<NE, 1>(lz, ZS, mask64, &flex_lds, tile, a, ws, expert_ids, weights, nullptr);
@@ -955,6 +968,14 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   FinishPrologue pro = {0, 0ull};
   if (tile < a.ntiles) pro = finish_prologue(fl, tile, a, ws, expert_ids);  // loads overlap the sums below
   bool self = false;
+  // fixed counts of the workgroup's earlier tiles (needed by the self path; requested
+  // now so that they arrive together with everything else)
+  int wg_before = 0;
+  if (a.ntiles <= kSelfPrefixTiles) {
+#pragma unroll
+    for (int j = 0; j < kChainWaves - 1; ++j)
+      if (j < wave && t0 + j < a.ntiles) wg_before += ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane];
+  }
   if (a.ntiles <= kSelfPrefixTiles) {
     if (threadIdx.x == 0) sh_anyflex = 0;
     __syncthreads();
@@ -967,10 +988,7 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
         before += sh_before[w][lane];
         all += sh_all[w][lane];
       }
-      // this wave's tile: add the workgroup's earlier tiles
-      for (int j = 0; j < wave; ++j)
-        if (t0 + j < a.ntiles) before += ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane];
-      own_base[wave][lane] = before;
+      own_base[wave][lane] = before + wg_before;  // this wave's tile: plus the workgroup's earlier tiles
       if (wave == 0) {
         int incl = lane < a.E ? all : 0;
         const int cnt = incl;
