@@ -358,6 +358,70 @@ __device__ __forceinline__ void sort_ascending_u32(unsigned (&K)[N]) {
   }
 }
 
+// Bit mask over the CP key slots (slot = low 4 bits of a key) of the K smallest keys.
+// With K known: a partial network that finds the min(K, CP - K) extreme keys by merging
+// sorted pairs, quads, ... and keeping only that many per group; the keys are distinct.
+template <int N, int M, bool LARGEST>
+__device__ __forceinline__ void extreme_keys(const unsigned (&K)[N], unsigned (&out)[M]) {
+  // groups of G keys, each reduced to its M' = min(G, M) extreme keys, sorted (most
+  // extreme first); G doubles every round
+  unsigned cur[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) cur[i] = K[i];
+  auto better = [](unsigned x, unsigned y) { return LARGEST ? max(x, y) : min(x, y); };
+  auto worse = [](unsigned x, unsigned y) { return LARGEST ? min(x, y) : max(x, y); };
+  static_assert(M == 1 || M == 2, "at most two extreme keys");
+  if (M == 1) {
+#pragma unroll
+    for (int g = 1; g < N; g *= 2)
+#pragma unroll
+      for (int i = 0; i + g < N; i += 2 * g) cur[i] = better(cur[i], cur[i + g]);
+    out[0] = cur[0];
+  } else {
+    // pairs: (first, second)
+#pragma unroll
+    for (int i = 0; i < N; i += 2) {
+      const unsigned a = better(cur[i], cur[i + 1]), b = worse(cur[i], cur[i + 1]);
+      cur[i] = a;
+      cur[i + 1] = b;
+    }
+#pragma unroll
+    for (int g = 2; g < N; g *= 2)
+#pragma unroll
+      for (int i = 0; i + g < N; i += 2 * g) {
+        const unsigned a0 = cur[i], b0 = cur[i + 1], a1 = cur[i + g], b1 = cur[i + g + 1];
+        cur[i] = better(a0, a1);
+        cur[i + 1] = better(worse(a0, a1), better(b0, b1));
+      }
+    out[0] = cur[0];
+    out[1] = cur[1];
+  }
+}
+
+template <int CP, int KK>
+__device__ __forceinline__ unsigned smallest_k_slots(unsigned (&key)[CP], int k) {
+  unsigned sel = 0;
+  if (KK > 0 && KK <= 2 && KK < CP) {
+    unsigned ext[KK > 0 && KK <= 2 ? KK : 1];
+    extreme_keys<CP, (KK > 0 && KK <= 2 ? KK : 1), false>(key, ext);
+#pragma unroll
+    for (int i = 0; i < KK; ++i) sel |= 1u << (ext[i < 2 ? i : 0] & 15u);
+  } else if (KK > 0 && CP - KK >= 1 && CP - KK <= 2) {
+    constexpr int D = (KK > 0 && CP - KK >= 1 && CP - KK <= 2) ? CP - KK : 1;
+    unsigned ext[D];
+    extreme_keys<CP, D, true>(key, ext);
+    sel = (1u << CP) - 1u;
+#pragma unroll
+    for (int i = 0; i < D; ++i) sel &= ~(1u << (ext[i] & 15u));
+  } else {
+    sort_ascending_u32<CP>(key);
+#pragma unroll
+    for (int i = 0; i < CP; ++i)
+      if (i < k) sel |= 1u << (key[i] & 15u);
+  }
+  return sel;
+}
+
 __device__ __forceinline__ unsigned long long rotl64(unsigned long long x, int s) {  // s in [0, 63]
   return s ? (x << s) | (x >> (64 - s)) : x;
 }
@@ -470,20 +534,12 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
         unsigned key[CP];
 #pragma unroll
         for (int j = 0; j < CP; ++j) {
-          const SpecExp* m = &M[ex[j]];
-          const unsigned cnt = (unsigned)__builtin_popcountll(m->mask & earlier);
-          key[j] = ((b[j] + (unsigned)m->G + cnt) << 4) | (unsigned)j;
+          const uint4 m = *reinterpret_cast<const uint4*>(&M[ex[j]]);  // mask lo, hi, G, -
+          const unsigned cnt = (unsigned)(__builtin_popcount(m.x & (unsigned)earlier) +
+                                          __builtin_popcount(m.y & (unsigned)(earlier >> 32)));
+          key[j] = ((b[j] + m.z + cnt) << 4) | (unsigned)j;
         }
-        sort_ascending_u32<CP>(key);
-        unsigned newsel = 0;
-        if (KK > 0) {
-#pragma unroll
-          for (int i = 0; i < KK; ++i) newsel |= 1u << (key[i < CP ? i : 0] & 15u);
-        } else {
-#pragma unroll
-          for (int i = 0; i < CP; ++i)
-            if (i < k) newsel |= 1u << (key[i] & 15u);
-        }
+        unsigned newsel = smallest_k_slots<CP, KK>(key, k);
         newsel = valid ? newsel : 0u;
         const unsigned diff = sel ^ newsel;
         const unsigned long long bal = __builtin_amdgcn_ballot_w64(diff != 0u);
