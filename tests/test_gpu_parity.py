@@ -125,6 +125,50 @@ def test_window_chain_long_run():
     assert int((ref["cstar"] > k).sum()) > 2000
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(seed)
+    E = int(rng.choice([2, 3, 5, 8, 8, 8, 16, 24, 33, 48, 64, 64, 64]))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    c = int(rng.integers(k, min(E, 16) + 1))
+    T = int(rng.choice([1, 17, 64, 100, 257, 700, 1500, 4000, 9000]))
+    kind = rng.choice(["normal", "flat", "mixed", "ties", "same", "blocks"])
+    scale = float(rng.choice([0.02, 0.1, 0.5, 1.0, 3.0]))
+    if kind == "normal":
+        z = rng.standard_normal((T, E)) * scale
+    elif kind == "flat":
+        z = rng.standard_normal((T, E)) * 0.01
+    elif kind == "mixed":
+        z = rng.standard_normal((T, E)) * scale
+        pick = rng.random(T) < rng.uniform(0.02, 0.6)
+        z[pick] = rng.standard_normal((int(pick.sum()), E)) * 0.01
+    elif kind == "ties":
+        z = (rng.standard_normal(3) * scale)[rng.integers(0, 3, size=(T, E))]
+    elif kind == "same":
+        z = np.repeat(rng.standard_normal((1, E)) * scale, T, axis=0)
+    else:  # runs of identical tokens inside random stretches
+        z = rng.standard_normal((T, E)) * scale
+        for _ in range(int(rng.integers(1, 6))):
+            a = int(rng.integers(0, T))
+            z[a:min(T, a + int(rng.integers(1, 600)))] = z[a]
+    eps = float(rng.choice([2.0, 0.999, 0.9, 0.7, 0.5, 0.3]))
+    tfix = float(rng.choice([1e-30, 0.01, 0.2, 0.5, 0.8, 1.0]))
+    loads = rng.integers(0, int(rng.choice([1, 10, 1000, 100000])), size=E).astype(np.int32)
+    return z.astype(np.float32), k, c, eps, tfix, loads, bool(rng.integers(0, 2)), f"{kind} T{T} E{E} k{k} c{c}"
+
+
+def test_random_cases_against_oracle():
+    """Seeded random shapes, thresholds, load offsets and logit structures (flat,
+    peaked, mixed, exact ties, identical tokens, runs of identical tokens)."""
+    u = _util()
+    flexible = 0
+    for seed in range(5000, 5400):
+        z, k, c, eps, tfix, loads, renorm, label = _random_case(seed)
+        gpu, ref = u.check_from_logits(z, k, c, eps, tfix, loads, renormalize=renorm,
+                                       label=f"seed {seed} {label}")
+        flexible += int((ref["cstar"] > k).sum())
+    assert flexible > 100000
+
+
 def test_extreme_logits():
     """Scores that underflow the clamp, huge spreads, and all-equal rows."""
     u = _util()
