@@ -47,6 +47,8 @@ def _load():
         lib.laser_oracle_route_literal.argtypes = [vp, i32, i32, i32, i32, f64, f64, i32,
                                                    vp, vp, vp, vp, vp, vp, vp, vp]
         lib.laser_oracle_route_literal.restype = ctypes.c_int
+        lib.laser_oracle_token_stats.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
+        lib.laser_oracle_token_stats.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -112,6 +114,20 @@ def route_literal(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
     """Router in fp64 with the paper's formulas as printed, on fp64 logits."""
     return _route(_load().laser_oracle_route_literal, logits, np.float64, k, c,
                   float(eps_high), float(t_fix), loads_in, renormalize)
+
+
+def token_stats(logits, k, t_fix):
+    """Per-token top-k mass, Shannon entropy (nats) and pool size from fp32 logits."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    out = {"topk_mass": np.empty(T, dtype=np.float64), "entropy": np.empty(T, dtype=np.float64),
+           "pool_size": np.empty(T, dtype=np.int32)}
+    rc = _load().laser_oracle_token_stats(_ptr(logits), T, E, k, float(np.float32(t_fix)),
+                                          _ptr(out["topk_mass"]), _ptr(out["entropy"]),
+                                          _ptr(out["pool_size"]))
+    if rc:
+        raise ValueError(f"oracle token_stats: bad arguments ({rc})")
+    return out
 
 
 def route_from_hidden(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True):

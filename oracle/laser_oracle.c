@@ -265,6 +265,44 @@ int laser_oracle_route(const float* logits, int32_t T, int32_t E, int32_t k, int
   return ORACLE_OK;
 }
 
+/* ------------------------------------------------ per-token gate statistics -- */
+
+/* The statistics the paper reads off the gate scores to choose the thresholds
+ * (Layer Variability in Gate Score Distributions; Parameter setting and layer-wise
+ * choices), per token, from fp32 logits:
+ *   topk_mass  M_k = sum of the k largest softmax scores          (fp64)
+ *   entropy    H = - sum_i s_i ln s_i, natural logarithm           (fp64)
+ *   pool_size  m = | {i : s_i >= t_fix * s_(1)} union top-k |      (integer)
+ * The integer is decided exactly as the router decides pool membership (binary32,
+ * d_i >= fl32(ln t_fix)), so that min(c, m) is the router's working-set size. */
+int laser_oracle_token_stats(const float* logits, int32_t T, int32_t E, int32_t k, float t_fix,
+                             double* topk_mass, double* entropy, int32_t* pool_size) {
+  if (!logits && T > 0) return ORACLE_E_ARG;
+  if (T < 0 || E < 1 || E > 256 || k < 1 || k > E) return ORACLE_E_ARG;
+  if (!(t_fix > 0.0f) || !(t_fix <= 1.0f)) return ORACLE_E_ARG;
+  const float tau_ln = (float)log((double)t_fix);
+  int32_t ord[256];
+  for (int32_t t = 0; t < T; ++t) {
+    const float* z = logits + (size_t)t * E;
+    order_desc_f32(z, E, ord);
+    const double zmax = (double)z[ord[0]];
+    double Z = 0.0;
+    for (int32_t i = 0; i < E; ++i) Z += exp((double)z[i] - zmax);
+    double mk = 0.0, h = 0.0;
+    for (int32_t i = 0; i < k; ++i) mk += exp((double)z[ord[i]] - zmax) / Z;
+    for (int32_t i = 0; i < E; ++i) {
+      const double s = exp((double)z[i] - zmax) / Z;
+      if (s > 0.0) h -= s * log(s);
+    }
+    int32_t in_pool = 0;
+    for (int32_t i = 0; i < E; ++i) in_pool += ((z[i] - z[ord[0]]) >= tau_ln);
+    if (topk_mass) topk_mass[t] = mk;
+    if (entropy) entropy[t] = h;
+    if (pool_size) pool_size[t] = in_pool > k ? in_pool : k;
+  }
+  return ORACLE_OK;
+}
+
 /* ------------------------------------------------- the router, literal fp64 -- */
 
 /* Same interface on fp64 logits, formulas as printed: s = softmax(z) with libm

@@ -365,3 +365,60 @@ def test_argument_errors():
                             (2, 3, .5, 0.0), (2, 3, .5, 1.5)]:
         with pytest.raises(ValueError):
             oracle.route(z, k, c, eps, tfix, L)
+
+
+# ---------------------------------------------------- per-token gate statistics ----
+
+def test_token_stats_closed_forms():
+    """Uniform scores: M_k = k/E, H = ln E, every expert in the pool.  Two experts:
+    the binary entropy of the logistic function.  One dominant expert: H -> 0."""
+    E, k = 8, 2
+    r = oracle.token_stats(np.zeros((1, E), np.float32), k, 0.5)
+    assert abs(r["topk_mass"][0] - k / E) < 1e-15
+    assert abs(r["entropy"][0] - math.log(E)) < 1e-14
+    assert r["pool_size"][0] == E
+    a = 0.7
+    r = oracle.token_stats(np.array([[a, 0.0]], np.float32), 1, 1.0)
+    s = 1.0 / (1.0 + math.exp(-float(np.float32(a))))
+    assert abs(r["topk_mass"][0] - s) < 1e-15
+    assert abs(r["entropy"][0] - (-s * math.log(s) - (1 - s) * math.log(1 - s))) < 1e-14
+    assert r["pool_size"][0] == 1          # only the best score reaches 1.0 * s_(1)
+    z = np.zeros((1, 16), np.float32)
+    z[0, 3] = 60.0
+    r = oracle.token_stats(z, 2, 0.5)
+    assert r["entropy"][0] < 1e-20 and abs(r["topk_mass"][0] - 1.0) < 1e-15
+    assert r["pool_size"][0] == 2          # pool of one, united with the top-2
+
+
+def test_token_stats_against_scipy():
+    from scipy.special import softmax
+    from scipy.stats import entropy
+    z = wl.random_logits(77, 500, 24, scale=1.7)
+    k, tfix = 3, 0.35
+    r = oracle.token_stats(z, k, tfix)
+    s = softmax(z.astype(np.float64), axis=1)
+    np.testing.assert_allclose(r["entropy"], entropy(s, axis=1), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r["topk_mass"], np.sort(s, axis=1)[:, -k:].sum(1), rtol=0, atol=1e-13)
+    # pool size by the printed definition, on tokens with no score within 1e-6 of the cut
+    cut = tfix * s.max(1, keepdims=True)
+    safe = (np.abs(s - cut) > 1e-6 * cut).all(1)
+    assert safe.mean() > 0.9
+    m = np.maximum((s >= cut).sum(1), k)
+    assert np.array_equal(r["pool_size"][safe], m[safe])
+    # invariant under a common shift of the logits (exact: 0.5 steps are representable)
+    r2 = oracle.token_stats(z + np.float32(4.0), k, tfix)
+    np.testing.assert_allclose(r2["entropy"], r["entropy"], atol=1e-6)
+    # bounds
+    assert (r["entropy"] >= 0).all() and (r["entropy"] <= math.log(24) + 1e-12).all()
+    assert (r["topk_mass"] >= k / 24 - 1e-12).all() and (r["topk_mass"] <= 1 + 1e-12).all()
+
+
+def test_pool_size_is_the_routers_working_set_bound():
+    """min(c, m) is the working-set size the router reports for expanded tokens."""
+    z = wl.random_logits(78, 2000, 64, scale=0.6)
+    k, c, eps, tfix = 6, 10, 0.7, 0.4
+    r = oracle.token_stats(z, k, tfix)
+    ref = oracle.route(z, k, c, eps, tfix, np.zeros(64, np.int32))
+    ex = ref["expanded"].astype(bool)
+    assert ex.sum() > 100
+    assert np.array_equal(ref["cstar"][ex], np.minimum(c, r["pool_size"][ex]))
