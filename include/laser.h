@@ -107,6 +107,24 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
                             int32_t* expert_offsets, void* workspace,
                             size_t workspace_bytes, void* hip_stream);
 
+/*
+ * laser_route, and in the same pass the per-token statistics of the gate scores that
+ * the paper uses to choose eps_high and t_fix per layer (Observations: Layer
+ * Variability in Gate Score Distributions; Method: Parameter setting and layer-wise
+ * choices).  Device arrays of T entries, each may be NULL:
+ *   topk_mass   fp32  M_k, the sum of the k largest softmax scores
+ *   entropy     fp32  Shannon entropy of the scores, natural logarithm
+ *   pool_size   int32 m = |{i : s_i >= t_fix * s_(1)} united with the top-k|
+ *               (min(c, m) is the size of the working set of Algorithm 1)
+ * Plain fp32 arithmetic from the quantities the router computes anyway; they take
+ * part in no decision.  Everything else as laser_route.
+ */
+int laser_route_stats(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                      const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                      float* weights, int32_t* permutation, int32_t* expert_offsets,
+                      float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, NUL-terminated description of a return code (host pointer). */
 const char* laser_strerror(int code);
 

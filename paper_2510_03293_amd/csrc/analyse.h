@@ -177,6 +177,12 @@ __device__ __forceinline__ float group_bcast0(float v, int q) {
   const float hi = dpp_float<kRowShr4>(lo);
   return q < 4 ? lo : hi;
 }
+__device__ __forceinline__ float group_sum_f(float x, int q) {
+  x += dpp_float<kQuadXor1>(x);
+  x += dpp_float<kQuadXor2>(x);
+  const float up = dpp_float<kRowShl4>(x), down = dpp_float<kRowShr4>(x);
+  return x + (q < 4 ? up : down);
+}
 __device__ __forceinline__ int group_sum(int x, int q) {
   x += dpp_int<kQuadXor1>(x);
   x += dpp_int<kQuadXor2>(x);
@@ -187,9 +193,10 @@ __device__ __forceinline__ int group_sum(int x, int q) {
 // lz: NP partial logit tiles in LDS, [NP][kTile rows][zs floats]; a token's logit is
 // the sum of its NP partials in the order (((p0 + p1) + p2) + ...).  mask64 (64 words)
 // and flex_lds (1 word) are LDS scratch.  logits_out (global, may be NULL) receives
-// the summed logits.  CT (8 or 16) bounds the trimming size c.  Must be called by
-// all 512 threads of the workgroup.
-template <int NE, int NP, int CT>
+// the summed logits.  CT (8 or 16) bounds the trimming size c.  STATS: also write the
+// per-token statistics asked for in `a` (top-k mass, entropy, pool size; plain fp32,
+// not part of any decision).  Must be called by all 512 threads of the workgroup.
+template <int NE, int NP, int CT, bool STATS>
 __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned long long* mask64,
                                 unsigned long long* flex_lds, int tile, const RouteArgs a,
                                 const Workspace ws, int32_t* __restrict__ expert_ids,
@@ -276,6 +283,16 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   float p[NE];
 #pragma unroll
   for (int i = 0; i < NE; ++i) p[i] = (owned(i) < a.E) ? exp_fixed(clamp_exp_arg(z[i] - zmax)) : 0.0f;
+  float plogp = 0.0f;  // this lane's part of sum_i p_i * d_i
+  int above = 0;       // this lane's experts at or above the pool cut
+  if (STATS) {
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+      const float di = z[i] - zmax;
+      plogp = __builtin_fmaf(p[i], clamp_exp_arg(di), plogp);
+      above += (owned(i) < a.E && di >= a.tau_ln) ? 1 : 0;
+    }
+  }
   // the tree, top level first: stride (padded E)/2 pairs the two runs of a lane; the
   // next three strides pair lane q with q+4, q+2, q+1; the rest is inside the run
   if (NG == 2) {
@@ -318,6 +335,16 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   extra = group_sum(extra, q);
   const int cstar = k + extra;
   const bool flex = live && !mass_ok && cstar > k;
+  if (STATS) {
+    // H = -sum s_i ln s_i with s_i = p_i / Z and ln s_i = d_i - ln Z
+    const float s1 = group_sum_f(plogp, q);
+    const int inpool = group_sum(above, q);
+    if (live && q == 0) {
+      if (a.st_mass) a.st_mass[t] = sk / zsum;
+      if (a.st_entropy) a.st_entropy[t] = __builtin_logf(zsum) - s1 / zsum;
+      if (a.st_pool) a.st_pool[t] = inpool > k ? inpool : k;
+    }
+  }
 
   // ---- tokens whose experts are final: outputs, per-expert masks ----------------
   if (live && !flex) {
@@ -412,7 +439,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
 }
 
 // NE = padded experts / 8 (1, 2, 4 or 8).
-template <int NE, int NP>
+template <int NE, int NP, bool STATS = false>
 __device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int zs,
                                              unsigned long long* mask64, unsigned long long* flex_lds,
                                              int tile, const RouteArgs a, const Workspace ws,
@@ -420,9 +447,9 @@ __device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int z
                                              float* __restrict__ weights,
                                              float* __restrict__ logits_out) {
   if (a.c <= 8)
-    analyse_tile_ct<NE, NP, 8>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
+    analyse_tile_ct<NE, NP, 8, STATS>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
   else
-    analyse_tile_ct<NE, NP, 16>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
+    analyse_tile_ct<NE, NP, 16, STATS>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
 }
 
 }  // namespace laser

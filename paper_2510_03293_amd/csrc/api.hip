@@ -131,6 +131,9 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.renormalize = p->renormalize ? 1 : 0;
   a.eps_high = p->eps_high;
   a.tau_ln = (float)log((double)p->t_fix);
+  a.st_mass = nullptr;
+  a.st_entropy = nullptr;
+  a.st_pool = nullptr;
   return a;
 }
 
@@ -153,11 +156,11 @@ size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params
   return workspace_bytes(T, E, true);
 }
 
-int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
-                const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
-                float* weights, int32_t* permutation, int32_t* expert_offsets,
-                float* logits_out, void* workspace, size_t workspace_bytes_given,
-                void* hip_stream) {
+static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                      const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                      float* weights, int32_t* permutation, int32_t* expert_offsets,
+                      float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
+                      void* workspace, size_t workspace_bytes_given, void* hip_stream) {
   int rc = check_params(T, E, params);
   if (rc != LASER_OK) return rc;
   if (!w_gate || !loads_inout || !expert_offsets || !workspace) return LASER_E_NULL;
@@ -174,7 +177,10 @@ int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, in
   if (workspace_bytes_given < workspace_bytes(T, E, need_logits)) return LASER_E_WORKSPACE;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const RouteArgs a = make_args(T, E, params);
+  RouteArgs a = make_args(T, E, params);
+  a.st_mass = topk_mass;
+  a.st_entropy = entropy;
+  a.st_pool = pool_size;
   const Workspace ws = carve_workspace(workspace, T, E, need_logits);
   const bool timed = !g_profile.ev.empty() && (size_t)(2 * g_profile.used + 1) < g_profile.ev.size() && T > 0;
   if (timed && hipEventRecord(g_profile.ev[2 * g_profile.used], s) != hipSuccess) return LASER_E_LAUNCH;
@@ -194,6 +200,26 @@ int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, in
     ++g_profile.used;
   }
   return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
+}
+
+int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                float* weights, int32_t* permutation, int32_t* expert_offsets,
+                float* logits_out, void* workspace, size_t workspace_bytes_given,
+                void* hip_stream) {
+  return route_impl(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+                    expert_offsets, logits_out, nullptr, nullptr, nullptr, workspace,
+                    workspace_bytes_given, hip_stream);
+}
+
+int laser_route_stats(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                      const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                      float* weights, int32_t* permutation, int32_t* expert_offsets,
+                      float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
+                      void* workspace, size_t workspace_bytes_given, void* hip_stream) {
+  return route_impl(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+                    expert_offsets, logits_out, topk_mass, entropy, pool_size, workspace,
+                    workspace_bytes_given, hip_stream);
 }
 
 int laser_route_from_logits(const float* logits, int32_t T, int32_t E,

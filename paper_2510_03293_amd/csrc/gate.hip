@@ -86,8 +86,9 @@ __device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
 // EB: 16-expert blocks, 1 (E <= 16), 2 (E <= 32) or 4 (E <= 64).  NE: experts per
 // lane of the per-token analysis that follows in the same kernel (padded E / 8).
 // NM: chunks per wave when H == 512 * NM (the main loop is then written out with
-// deeper prefetch), 0 for any other H.
-template <int EB, int NE, int NM>
+// deeper prefetch), 0 for any other H.  STATS: the analysis also writes the per-token
+// statistics.
+template <int EB, int NE, int NM, bool STATS>
 __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a,
     const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
@@ -222,22 +223,22 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
   __syncthreads();
 
   // The eight partial tiles are summed on the fly by the analysis.
-  analyse_tile<NE, kGateWaves>(part, kPartStride, mask64, &flex_lds, tile, a, ws, expert_ids,
-                               weights, logits_out);
+  analyse_tile<NE, kGateWaves, STATS>(part, kPartStride, mask64, &flex_lds, tile, a, ws, expert_ids,
+                                      weights, logits_out);
 }
 
-template <int EB, int NE, int NM>
+template <int EB, int NE, int NM, bool STATS>
 static hipError_t launch_nm(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
                              float* logits_out, hipStream_t s) {
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM>);
+  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM, STATS>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
+  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM, STATS>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out);
   return hipGetLastError();
@@ -247,9 +248,11 @@ template <int EB, int NE>
 static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
                              float* logits_out, hipStream_t s) {
-  if (H == 2048) return launch_nm<EB, NE, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  if (H == 4096) return launch_nm<EB, NE, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  return launch_nm<EB, NE, 0>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  // (the statistics variant exists for the general loop only)
+  if (wants_stats(a)) return launch_nm<EB, NE, 0, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  if (H == 2048) return launch_nm<EB, NE, 4, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  if (H == 4096) return launch_nm<EB, NE, 8, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  return launch_nm<EB, NE, 0, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
 }
 
 hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,

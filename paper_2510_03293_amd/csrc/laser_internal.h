@@ -23,7 +23,12 @@ struct RouteArgs {
   int renormalize;  // weights over the chosen k (1) or raw softmax scores (0)
   float eps_high;   // top-k mass threshold
   float tau_ln;     // fl32(ln t_fix): pool cut-off in the logit domain
+  // optional per-token statistics, [T] each, any may be NULL (all NULL: not computed)
+  float* st_mass;      // top-k mass M_k
+  float* st_entropy;   // Shannon entropy of the scores, nats
+  int32_t* st_pool;    // pool size m (candidates above the cut, united with the top-k)
 };
+inline bool wants_stats(const RouteArgs& a) { return a.st_mass || a.st_entropy || a.st_pool; }
 
 // Device workspace carved out of the caller's buffer.  Records are written by
 // the per-token analysis, consumed by the load-ordered chain and the finishing

@@ -30,7 +30,7 @@
 
 namespace laser {
 
-template <int NE>  // padded experts / 8
+template <int NE, bool STATS>  // NE = padded experts / 8
 __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ logits,
                                                       const RouteArgs a, const Workspace ws,
                                                       int32_t* __restrict__ expert_ids,
@@ -61,27 +61,28 @@ __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ 
     }
   }
   __syncthreads();
-  analyse_tile<NE, 1>(lz, ZS, mask64, &flex_lds, tile, a, ws, expert_ids, weights, nullptr);
+  analyse_tile<NE, 1, STATS>(lz, ZS, mask64, &flex_lds, tile, a, ws, expert_ids, weights, nullptr);
 }
 
 hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
   const dim3 grid(a.ntiles), block(512);
+  const bool st = wants_stats(a);
+#define LASER_LAUNCH_ANALYSE(NE_)                                                                  \
+  if (st)                                                                                          \
+    hipLaunchKernelGGL((analyse_kernel<NE_, true>), grid, block, 0, s, logits, a, ws, expert_ids,  \
+                       weights);                                                                   \
+  else                                                                                             \
+    hipLaunchKernelGGL((analyse_kernel<NE_, false>), grid, block, 0, s, logits, a, ws, expert_ids, \
+                       weights);
   switch (a.EP) {
-    case 8:
-      hipLaunchKernelGGL(analyse_kernel<1>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
-      break;
-    case 16:
-      hipLaunchKernelGGL(analyse_kernel<2>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
-      break;
-    case 32:
-      hipLaunchKernelGGL(analyse_kernel<4>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
-      break;
-    default:
-      hipLaunchKernelGGL(analyse_kernel<8>, grid, block, 0, s, logits, a, ws, expert_ids, weights);
-      break;
+    case 8: LASER_LAUNCH_ANALYSE(1) break;
+    case 16: LASER_LAUNCH_ANALYSE(2) break;
+    case 32: LASER_LAUNCH_ANALYSE(4) break;
+    default: LASER_LAUNCH_ANALYSE(8) break;
   }
+#undef LASER_LAUNCH_ANALYSE
   return hipGetLastError();
 }
 

@@ -29,6 +29,27 @@ def run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormaliz
     return _collect(buf, loads, buf.logits)
 
 
+def run_route_stats(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, which=(True, True, True)):
+    """GPU laser_route_stats; routing outputs as run_route plus the requested statistics."""
+    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype)
+    hd, wd = to_device(hidden), to_device(w_gate)
+    T, H = hd.shape
+    E = wd.shape[0]
+    loads = torch.from_numpy(np.ascontiguousarray(loads_in, dtype=np.int32)).cuda()
+    buf = B.RouteBuffers(T, H, E, params, want_logits=True)
+    mass = torch.full((T,), -1.0, dtype=torch.float32, device="cuda") if which[0] else None
+    ent = torch.full((T,), -1.0, dtype=torch.float32, device="cuda") if which[1] else None
+    pool = torch.full((T,), -1, dtype=torch.int32, device="cuda") if which[2] else None
+    B.laser_route_stats(hd, wd, T, H, E, params, loads, buf.expert_ids, buf.weights, buf.permutation,
+                        buf.expert_offsets, buf.logits, mass, ent, pool, buf.workspace)
+    torch.cuda.synchronize()
+    out = _collect(buf, loads, buf.logits)
+    out["topk_mass"] = None if mass is None else mass.cpu().numpy()
+    out["entropy"] = None if ent is None else ent.cpu().numpy()
+    out["pool_size"] = None if pool is None else pool.cpu().numpy()
+    return out
+
+
 def run_route_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
     params = B.make_params(k, c, eps_high, t_fix, renormalize=renormalize)
     ld = torch.from_numpy(np.ascontiguousarray(logits, dtype=np.float32)).cuda()

@@ -212,6 +212,43 @@ def test_bf16_gate_and_route(T, H, E, k, c):
                   label=f"bf16 T{T} H{H} E{E}")
 
 
+STATS_SHAPES = [
+    # T, H, E, k, c, dtype
+    (300, 2048, 64, 6, 8, wl.DTYPE_BF16),
+    (130, 4096, 8, 2, 4, wl.DTYPE_BF16),
+    (65, 1000, 5, 2, 3, wl.DTYPE_BF16),
+    (700, 512, 33, 4, 12, wl.DTYPE_BF16),
+    (256, 128, 8, 2, 4, wl.DTYPE_F32),
+]
+
+
+@pytest.mark.parametrize("T,H,E,k,c,dtype", STATS_SHAPES)
+def test_token_statistics(T, H, E, k, c, dtype):
+    """Top-k mass, entropy and pool size written alongside the routing step, against
+    the oracle on the GPU's own logits; the routing outputs are those of laser_route."""
+    import oracle
+    u = _util()
+    rng = np.random.default_rng(T + H + E + 1)
+    hidden, w = wl.make_gate(rng, T, H, E, dtype, bias=np.linspace(-1.5, 1.5, E))
+    if dtype == wl.DTYPE_F32:
+        w = (w * 20).astype(np.float32)
+    loads_in = rng.integers(0, 5, E).astype(np.int32)
+    eps, tfix = 0.6, 0.3
+    plain = u.run_route(hidden, w, dtype, k, c, eps, tfix, loads_in)
+    got = u.run_route_stats(hidden, w, dtype, k, c, eps, tfix, loads_in)
+    for key in ("expert_ids", "permutation", "expert_offsets", "loads"):
+        assert np.array_equal(plain[key], got[key]), key
+    assert np.abs(plain["logits"] - got["logits"]).max() <= 1e-6
+    ref = oracle.token_stats(got["logits"], k, tfix)
+    assert np.abs(got["topk_mass"] - ref["topk_mass"]).max() <= 1e-5
+    assert np.abs(got["entropy"] - ref["entropy"]).max() <= 1e-4
+    assert np.array_equal(got["pool_size"], ref["pool_size"])
+    # any subset of the three may be asked for
+    only = u.run_route_stats(hidden, w, dtype, k, c, eps, tfix, loads_in, which=(False, True, False))
+    assert only["topk_mass"] is None and only["pool_size"] is None
+    assert np.array_equal(only["entropy"], got["entropy"])
+
+
 def test_fp32_gate_ragged():
     u = _util()
     rng = np.random.default_rng(17)
