@@ -225,6 +225,31 @@ def main():
         lo_k = loads.cpu().numpy().astype(np.float64)
         extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
 
+        # the statistics pass (laser_route_stats): cost beside the plain call, and what
+        # the synthetic gate scores look like (layer means of per-token values)
+        st_mass = torch.empty(T, dtype=torch.float32, device="cuda")
+        st_ent = torch.empty(T, dtype=torch.float32, device="cuda")
+        st_pool = torch.empty(T, dtype=torch.int32, device="cuda")
+
+        def stats_pass():
+            loads.zero_()
+            for layer in range(layers):
+                B.laser_route_stats(hidden[layer], wgate[layer], T, H, E, params[layer],
+                                    loads_of[layer], buf.expert_ids, buf.weights, buf.permutation,
+                                    buf.expert_offsets, None, st_mass, st_ent, st_pool,
+                                    buf.workspace, stream)
+        stats_pass()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        stats_pass()
+        torch.cuda.synchronize()
+        extras["route_stats"] = {
+            "us_per_layer": (time.perf_counter() - t0) * 1e6 / layers,
+            "last_layer_mean_topk_mass": float(st_mass.mean()),
+            "last_layer_mean_entropy_nats": float(st_ent.mean()),
+            "last_layer_mean_pool_size": float(st_pool.float().mean()),
+        }
+
         # run-to-run determinism: one layer twice into separate buffers, every output bit
         buf2 = B.RouteBuffers(T, H, E, params[0])
         l1 = torch.zeros(E, dtype=torch.int32, device="cuda")
