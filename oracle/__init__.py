@@ -49,6 +49,8 @@ def _load():
         lib.laser_oracle_route_literal.restype = ctypes.c_int
         lib.laser_oracle_token_stats.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
         lib.laser_oracle_token_stats.restype = ctypes.c_int
+        lib.laser_oracle_imbalance.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
+        lib.laser_oracle_imbalance.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -127,6 +129,28 @@ def token_stats(logits, k, t_fix):
                                           _ptr(out["pool_size"]))
     if rc:
         raise ValueError(f"oracle token_stats: bad arguments ({rc})")
+    return out
+
+
+def imbalance(counts, placement=None, weights=None):
+    """Imbalance factor, max violation, GPU-level imbalance per layer and the aggregates."""
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    L, E = counts.shape
+    G = 0
+    pl = wt = None
+    if placement is not None:
+        pl = np.ascontiguousarray(placement, dtype=np.float64)
+        G = pl.shape[0]
+        assert pl.shape == (G, E)
+    if weights is not None:
+        wt = np.ascontiguousarray(weights, dtype=np.float64)
+        assert wt.shape == (L,)
+    out = {"I": np.empty(L), "MV": np.empty(L), "I_gpu": np.empty(L), "agg": np.empty(2)}
+    rc = _load().laser_oracle_imbalance(_ptr(counts), L, E, None if pl is None else _ptr(pl), G,
+                                        None if wt is None else _ptr(wt), _ptr(out["I"]),
+                                        _ptr(out["MV"]), _ptr(out["I_gpu"]), _ptr(out["agg"]))
+    if rc:
+        raise ValueError(f"oracle imbalance: bad arguments ({rc})")
     return out
 
 

@@ -303,6 +303,56 @@ int laser_oracle_token_stats(const float* logits, int32_t T, int32_t E, int32_t 
   return ORACLE_OK;
 }
 
+/* ------------------------------------------------------- imbalance metrics -- */
+
+/* Expert- and GPU-level imbalance of per-layer assignment counts (Problem statement:
+ * the imbalance factor I, its aggregate over layers, and the GPU-level version under
+ * a placement matrix; Evaluation / Metrics: max violation).
+ *   counts     [L,E] tokens assigned to expert e in layer l
+ *   placement  [G,E] share of expert e served by GPU g (columns sum to 1), or NULL
+ *   weights    [L] layer weights w_l, or NULL for 1/L
+ *   I[l]       max_e N / mean_e N          MV[l] = I[l] - 1 (excess of the most loaded
+ *   Igpu[l]    max_g N_g / mean_g N_g      expert over the average, relative)
+ *   agg[0] = sum_l w_l I[l],  agg[1] = sum_l w_l Igpu[l]
+ * A layer without assignments has I = Igpu = 1 (nothing is unbalanced). */
+int laser_oracle_imbalance(const int32_t* counts, int32_t L, int32_t E, const double* placement,
+                           int32_t G, const double* weights, double* I, double* MV, double* Igpu,
+                           double* agg) {
+  if (L < 0 || E < 1 || (placement && G < 1)) return ORACLE_E_ARG;
+  double a0 = 0.0, a1 = 0.0;
+  for (int32_t l = 0; l < L; ++l) {
+    const int32_t* n = counts + (size_t)l * E;
+    double mx = 0.0, sum = 0.0;
+    for (int32_t e = 0; e < E; ++e) {
+      sum += (double)n[e];
+      if ((double)n[e] > mx) mx = (double)n[e];
+    }
+    const double il = sum > 0.0 ? mx / (sum / E) : 1.0;
+    double ig = 1.0;
+    if (placement) {
+      double gmx = 0.0, gsum = 0.0;
+      for (int32_t g = 0; g < G; ++g) {
+        double ng = 0.0;
+        for (int32_t e = 0; e < E; ++e) ng += placement[(size_t)g * E + e] * (double)n[e];
+        gsum += ng;
+        if (ng > gmx) gmx = ng;
+      }
+      ig = gsum > 0.0 ? gmx / (gsum / G) : 1.0;
+    }
+    const double w = weights ? weights[l] : 1.0 / L;
+    if (I) I[l] = il;
+    if (MV) MV[l] = il - 1.0;
+    if (Igpu) Igpu[l] = ig;
+    a0 += w * il;
+    a1 += w * ig;
+  }
+  if (agg) {
+    agg[0] = a0;
+    agg[1] = a1;
+  }
+  return ORACLE_OK;
+}
+
 /* ------------------------------------------------- the router, literal fp64 -- */
 
 /* Same interface on fp64 logits, formulas as printed: s = softmax(z) with libm

@@ -422,3 +422,57 @@ def test_pool_size_is_the_routers_working_set_bound():
     ex = ref["expanded"].astype(bool)
     assert ex.sum() > 100
     assert np.array_equal(ref["cstar"][ex], np.minimum(c, r["pool_size"][ex]))
+
+
+# ------------------------------------------------------------ imbalance metrics ----
+
+def test_imbalance_closed_forms():
+    """Equal counts: I = 1, MV = 0.  All tokens on one expert: I = E.  One GPU per
+    expert: the GPU-level figure is the expert-level one.  Everything on one GPU of
+    G: I_gpu = G.  Two experts per GPU with their counts paired up evenly: I_gpu = 1."""
+    E = 8
+    r = oracle.imbalance(np.full((1, E), 5, np.int32))
+    assert r["I"][0] == 1.0 and r["MV"][0] == 0.0 and r["agg"][0] == 1.0
+    hot = np.zeros((1, E), np.int32)
+    hot[0, 3] = 40
+    assert oracle.imbalance(hot)["I"][0] == E
+    n = np.array([[7, 1, 4, 4, 2, 6, 8, 0]], np.int32)
+    r = oracle.imbalance(n, placement=np.eye(E))
+    assert abs(r["I_gpu"][0] - r["I"][0]) < 1e-15 and abs(r["I"][0] - 8 / 4.0) < 1e-15
+    one = np.zeros((4, E))
+    one[2] = 1.0
+    assert abs(oracle.imbalance(n, placement=one)["I_gpu"][0] - 4.0) < 1e-15
+    pairs = np.zeros((4, E))
+    for g, (a, b) in enumerate([(0, 1), (2, 3), (4, 5), (6, 7)]):
+        pairs[g, a] = pairs[g, b] = 1.0
+    assert abs(oracle.imbalance(n, placement=pairs)["I_gpu"][0] - 1.0) < 1e-15
+    # replication: every expert split evenly over all GPUs balances any counts
+    assert abs(oracle.imbalance(n, placement=np.full((4, E), 0.25))["I_gpu"][0] - 1.0) < 1e-15
+    # an empty layer counts as balanced
+    assert oracle.imbalance(np.zeros((1, E), np.int32))["I"][0] == 1.0
+
+
+def test_imbalance_against_numpy_and_weights():
+    rng = np.random.default_rng(5)
+    L, E, G = 6, 16, 4
+    n = rng.integers(0, 500, size=(L, E)).astype(np.int32)
+    A = rng.random((G, E))
+    A /= A.sum(0, keepdims=True)
+    w = rng.random(L)
+    w /= w.sum()
+    r = oracle.imbalance(n, placement=A, weights=w)
+    I = n.max(1) / n.mean(1)
+    ng = n.astype(np.float64) @ A.T
+    Ig = ng.max(1) / ng.mean(1)
+    np.testing.assert_allclose(r["I"], I, rtol=1e-14)
+    np.testing.assert_allclose(r["MV"], I - 1, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(r["I_gpu"], Ig, rtol=1e-13)
+    np.testing.assert_allclose(r["agg"], [w @ I, w @ Ig], rtol=1e-13)
+    # default weights: the plain mean over layers
+    np.testing.assert_allclose(oracle.imbalance(n)["agg"][0], I.mean(), rtol=1e-14)
+    # bounds with rho = E / G experts per GPU under a pure placement of equal sizes:
+    # I / rho... the most loaded GPU holds at least the most loaded expert
+    pure = np.zeros((G, E))
+    pure[np.arange(E) % G, np.arange(E)] = 1.0
+    rp = oracle.imbalance(n, placement=pure)
+    assert (rp["I_gpu"] >= rp["I"] / (E // G) - 1e-12).all() and (rp["I_gpu"] <= rp["I"] + 1e-12).all()
