@@ -250,6 +250,14 @@ def main():
             "last_layer_mean_pool_size": float(st_pool.float().mean()),
         }
 
+        # the same figure from the device-side metrics (counts = loads after a step
+        # that started from zero loads)
+        step()
+        im = B.laser_imbalance(loads)
+        torch.cuda.synchronize()
+        extras["device_I_agg"] = float(im["agg"][0])
+        extras["device_max_violation_mean"] = float(im["MV"].mean())
+
         # run-to-run determinism: one layer twice into separate buffers, every output bit
         buf2 = B.RouteBuffers(T, H, E, params[0])
         l1 = torch.zeros(E, dtype=torch.int32, device="cuda")

@@ -125,6 +125,26 @@ int laser_route_stats(const void* hidden, const void* w_gate, int32_t T, int32_t
                       float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Imbalance metrics of per-layer assignment counts (Problem statement: imbalance
+ * factor, aggregate over layers, GPU-level imbalance under a placement; Evaluation,
+ * Metrics: max violation).  All pointers are device pointers.
+ *   counts         [L,E] int32  tokens assigned to expert e in layer l          in
+ *   placement      [G,E] fp32   share of expert e served by GPU g (columns sum  in
+ *                  to 1), or NULL: no GPU-level figure
+ *   layer_weights  [L] fp32 w_l, or NULL for 1/L                                in
+ *   I              [L] fp64     max_e N / mean_e N                              out
+ *   MV             [L] fp64     I - 1, or NULL                                  out
+ *   I_gpu          [L] fp64     max_g N_g / mean_g N_g with N_g = sum_e A[g,e] N[e]
+ *                  (required when placement is given, else may be NULL)         out
+ *   agg            [2] fp64     sum_l w_l I[l], sum_l w_l I_gpu[l] (1 without    out
+ *                  placement)
+ * A layer without assignments counts as balanced (1).  Limits: G <= 4096.
+ */
+int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, const float* placement,
+                    int32_t G, const float* layer_weights, double* I, double* MV, double* I_gpu,
+                    double* agg, void* hip_stream);
+
 /* Static, NUL-terminated description of a return code (host pointer). */
 const char* laser_strerror(int code);
 

@@ -19,7 +19,7 @@ DTYPE_BF16 = 1
 TRIM_TOP = 0
 TRIM_RANDOM = 1
 
-EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_stats", "laser_route_from_logits",
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_stats", "laser_route_from_logits", "laser_imbalance",
            "laser_strerror", "laser_profile_enable", "laser_profile_read",
            "laser_profile_event_overhead", "laser_profile_plain_read")
 
@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.laser_route_stats.argtypes = [vp, vp, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                       vp, sz, vp]
     lib.laser_route_stats.restype = ctypes.c_int
+    lib.laser_imbalance.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.laser_imbalance.restype = ctypes.c_int
     lib.laser_route_from_logits.argtypes = [vp, i32, i32, pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.laser_route_from_logits.restype = ctypes.c_int
     lib.laser_strerror.argtypes = [ctypes.c_int]
@@ -133,6 +135,21 @@ def laser_route_from_logits(logits, T, E, params, loads_inout, expert_ids, weigh
                                         _ptr(permutation), _ptr(expert_offsets), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(),
                                         _stream_handle(stream)))
+
+
+def laser_imbalance(counts, placement=None, layer_weights=None, stream=None):
+    """Imbalance metrics of device counts [L,E] (int32): dict of device fp64 tensors."""
+    L, E = counts.shape
+    G = 0 if placement is None else placement.shape[0]
+    dev = counts.device
+    out = {"I": torch.empty(L, dtype=torch.float64, device=dev),
+           "MV": torch.empty(L, dtype=torch.float64, device=dev),
+           "I_gpu": torch.empty(L, dtype=torch.float64, device=dev),
+           "agg": torch.empty(2, dtype=torch.float64, device=dev)}
+    _check(_lib.laser_imbalance(_ptr(counts), L, E, _ptr(placement), G, _ptr(layer_weights),
+                                _ptr(out["I"]), _ptr(out["MV"]), _ptr(out["I_gpu"]),
+                                _ptr(out["agg"]), _stream_handle(stream)))
+    return out
 
 
 def laser_profile_enable(max_calls: int) -> None:

@@ -1,0 +1,117 @@
+// Imbalance metrics of per-layer assignment counts (Problem statement: imbalance
+// factor I_L = max_e N / mean_e N, its weighted aggregate over layers, and the
+// GPU-level version under a placement matrix A; Evaluation, Metrics: max violation,
+// the relative excess of the most loaded expert over the average, I_L - 1).
+// fp64 on the device; one workgroup per layer, then one wavefront for the aggregates.
+#include "../../include/laser.h"
+#include "laser_internal.h"
+
+namespace laser {
+
+constexpr int kMetricThreads = 256;
+
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v = fmax(v, __shfl_xor(v, d, 64));
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// max and sum over the workgroup; result valid in every thread
+__device__ void block_max_sum(double& mx, double& sum, double* sh) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  mx = wave_max(mx);
+  sum = wave_sum(sum);
+  __syncthreads();  // sh may still be read from the previous call
+  if (lane == 0) {
+    sh[wave] = mx;
+    sh[4 + wave] = sum;
+  }
+  __syncthreads();
+  mx = fmax(fmax(sh[0], sh[1]), fmax(sh[2], sh[3]));
+  sum = ((sh[4] + sh[5]) + sh[6]) + sh[7];
+}
+
+__global__ __launch_bounds__(kMetricThreads) void imbalance_layers_kernel(
+    const int32_t* __restrict__ counts, int E, const float* __restrict__ placement, int G,
+    double* __restrict__ I, double* __restrict__ MV, double* __restrict__ Igpu) {
+  __shared__ double sh[8];
+  extern __shared__ double gload[];  // [G] when a placement is given
+  const int l = blockIdx.x;
+  const int32_t* n = counts + (size_t)l * E;
+  double mx = 0.0, sum = 0.0;
+  for (int e = threadIdx.x; e < E; e += kMetricThreads) {
+    const double v = (double)n[e];
+    mx = fmax(mx, v);
+    sum += v;
+  }
+  block_max_sum(mx, sum, sh);
+  const double il = sum > 0.0 ? mx / (sum / (double)E) : 1.0;
+  if (threadIdx.x == 0) {
+    I[l] = il;
+    if (MV) MV[l] = il - 1.0;
+  }
+  if (placement == nullptr) {
+    if (Igpu && threadIdx.x == 0) Igpu[l] = 1.0;
+    return;
+  }
+  // load of GPU g: one wavefront per g, lanes over the experts
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int g = wave; g < G; g += kMetricThreads / 64) {
+    double acc = 0.0;
+    for (int e = lane; e < E; e += 64) acc += (double)placement[(size_t)g * E + e] * (double)n[e];
+    acc = wave_sum(acc);
+    if (lane == 0) gload[g] = acc;
+  }
+  __syncthreads();
+  double gmx = 0.0, gsum = 0.0;
+  for (int g = threadIdx.x; g < G; g += kMetricThreads) {
+    gmx = fmax(gmx, gload[g]);
+    gsum += gload[g];
+  }
+  block_max_sum(gmx, gsum, sh);
+  if (Igpu && threadIdx.x == 0) Igpu[l] = gsum > 0.0 ? gmx / (gsum / (double)G) : 1.0;
+}
+
+// agg[0] = sum_l w_l I[l], agg[1] = sum_l w_l Igpu[l]; sequential in l (one lane), so
+// the result does not depend on the launch shape
+__global__ void imbalance_aggregate_kernel(const double* __restrict__ I, const double* __restrict__ Igpu,
+                                           const float* __restrict__ weights, int L,
+                                           double* __restrict__ agg) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double a0 = 0.0, a1 = 0.0;
+  for (int l = 0; l < L; ++l) {
+    const double w = weights ? (double)weights[l] : 1.0 / (double)L;
+    a0 += w * I[l];
+    a1 += w * (Igpu ? Igpu[l] : 1.0);
+  }
+  agg[0] = a0;
+  agg[1] = a1;
+}
+
+}  // namespace laser
+
+using namespace laser;
+
+extern "C" int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, const float* placement,
+                               int32_t G, const float* layer_weights, double* I, double* MV,
+                               double* I_gpu, double* agg, void* hip_stream) {
+  if (L < 0 || E < 1 || E > (1 << 20)) return LASER_E_RANGE;
+  if (placement && (G < 1 || G > 4096)) return LASER_E_RANGE;
+  if (!agg || (L > 0 && (!counts || !I))) return LASER_E_NULL;
+  if (placement && !I_gpu) return LASER_E_NULL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (L > 0) {
+    const size_t lds = placement ? (size_t)G * sizeof(double) : 0;
+    hipLaunchKernelGGL(imbalance_layers_kernel, dim3(L), dim3(kMetricThreads), lds, s, counts, E,
+                       placement, G, I, MV, I_gpu);
+    if (hipGetLastError() != hipSuccess) return LASER_E_LAUNCH;
+  }
+  hipLaunchKernelGGL(imbalance_aggregate_kernel, dim3(1), dim3(64), 0, s, I, placement ? I_gpu : nullptr,
+                     layer_weights, L, agg);
+  return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;
+}

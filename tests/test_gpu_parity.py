@@ -249,6 +249,34 @@ def test_token_statistics(T, H, E, k, c, dtype):
     assert np.array_equal(only["entropy"], got["entropy"])
 
 
+@pytest.mark.parametrize("L,E,G", [(1, 8, 0), (27, 64, 8), (5, 64, 64), (3, 1000, 7), (4, 5, 3), (0, 8, 0)])
+def test_imbalance_metrics(L, E, G):
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    rng = np.random.default_rng(L * 100 + E + G)
+    n = rng.integers(0, 3000, size=(L, E)).astype(np.int32)
+    if L > 1:
+        n[1] = 0                                     # a layer without assignments
+    A = w = None
+    if G:
+        A = rng.random((G, E)).astype(np.float32)
+        A /= A.sum(0, keepdims=True)
+        A = A.astype(np.float32)
+        w = rng.random(L).astype(np.float32)
+    out = B.laser_imbalance(torch.from_numpy(n).cuda(),
+                            None if A is None else torch.from_numpy(A).cuda(),
+                            None if w is None else torch.from_numpy(w).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.imbalance(n, None if A is None else A.astype(np.float64),
+                           None if w is None else w.astype(np.float64))
+    np.testing.assert_allclose(out["I"].cpu().numpy(), ref["I"], rtol=1e-14)
+    np.testing.assert_allclose(out["MV"].cpu().numpy(), ref["MV"], rtol=1e-12, atol=1e-14)
+    if G:
+        np.testing.assert_allclose(out["I_gpu"].cpu().numpy(), ref["I_gpu"], rtol=1e-12)
+    np.testing.assert_allclose(out["agg"].cpu().numpy(), ref["agg"] if L else [0.0, 0.0], rtol=1e-12)
+
+
 def test_fp32_gate_ragged():
     u = _util()
     rng = np.random.default_rng(17)
