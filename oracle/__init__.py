@@ -47,6 +47,14 @@ def _load():
         lib.laser_oracle_route_literal.argtypes = [vp, i32, i32, i32, i32, f64, f64, i32,
                                                    vp, vp, vp, vp, vp, vp, vp, vp]
         lib.laser_oracle_route_literal.restype = ctypes.c_int
+        u32, u64 = ctypes.c_uint32, ctypes.c_uint64
+        lib.laser_oracle_philox4x32.argtypes = [vp, vp, vp]
+        lib.laser_oracle_philox4x32.restype = None
+        lib.laser_oracle_sample_ranks.argtypes = [i32, i32, u64, u32, u64, vp]
+        lib.laser_oracle_sample_ranks.restype = None
+        lib.laser_oracle_route_random.argtypes = [vp, i32, i32, i32, i32, f32, f32, i32, u64, u32, u64,
+                                                  vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.laser_oracle_route_random.restype = ctypes.c_int
         lib.laser_oracle_token_stats.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
         lib.laser_oracle_token_stats.restype = ctypes.c_int
         lib.laser_oracle_imbalance.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
@@ -116,6 +124,50 @@ def route_literal(logits, k, c, eps_high, t_fix, loads_in, renormalize=True):
     """Router in fp64 with the paper's formulas as printed, on fp64 logits."""
     return _route(_load().laser_oracle_route_literal, logits, np.float64, k, c,
                   float(eps_high), float(t_fix), loads_in, renormalize)
+
+
+def philox4x32(ctr, key):
+    """Philox4x32-10 block: 4 counter words, 2 key words -> 4 output words."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    _load().laser_oracle_philox4x32(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def sample_ranks(m, c, seed, stream, token):
+    """The c sampled positions of a pool of m (c < m), ascending."""
+    assert 0 < c < m <= 256
+    out = np.empty(c, dtype=np.int32)
+    _load().laser_oracle_sample_ranks(m, c, seed, stream, token, _ptr(out))
+    return out
+
+
+def route_random(logits, k, c, eps_high, t_fix, loads_in, seed, stream=0, token_offset=0,
+                 renormalize=True):
+    """Router with RANDOM trimming (binary32 decisions); returns a dict as route()."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    loads_in = np.ascontiguousarray(loads_in, dtype=np.int32)
+    assert loads_in.shape == (E,)
+    out = {
+        "loads": np.empty(E, dtype=np.int32),
+        "expert_ids": np.empty((T, k), dtype=np.int32),
+        "weights": np.empty((T, k), dtype=np.float64),
+        "permutation": np.empty(T * k, dtype=np.int32),
+        "expert_offsets": np.empty(E + 1, dtype=np.int32),
+        "expanded": np.empty(T, dtype=np.uint8),
+        "cstar": np.empty(T, dtype=np.int32),
+    }
+    rc = _load().laser_oracle_route_random(
+        _ptr(logits), T, E, k, c, float(np.float32(eps_high)), float(np.float32(t_fix)),
+        int(bool(renormalize)), seed, stream, token_offset, _ptr(loads_in), _ptr(out["loads"]),
+        _ptr(out["expert_ids"]), _ptr(out["weights"]), _ptr(out["permutation"]),
+        _ptr(out["expert_offsets"]), _ptr(out["expanded"]), _ptr(out["cstar"]))
+    if rc:
+        raise ValueError(f"oracle route_random: bad arguments ({rc})")
+    return out
 
 
 def token_stats(logits, k, t_fix):

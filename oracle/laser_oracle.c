@@ -265,6 +265,129 @@ int laser_oracle_route(const float* logits, int32_t T, int32_t E, int32_t k, int
   return ORACLE_OK;
 }
 
+/* ------------------------------------------------- randomized trimming ------ */
+
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
+ * 1, 2, 3", SC 2011): a counter-based generator, 128-bit counter, 64-bit key, ten
+ * rounds of two 32x32->64 multiplications; the key is bumped by the Weyl constants
+ * after every round. */
+void laser_oracle_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* "uniformly sample c indices from the pool (without replacement)" (Algorithm 1,
+ * mode RANDOM), made reproducible: the pool is the first m positions of the score
+ * order; a partial Fisher-Yates shuffle of [0, m) takes, for draw i = 0..c-1, the
+ * i-th 32-bit word r_i of the Philox stream with key = seed and counter =
+ * (token index low, token index high, stream, i / 4), and swaps position i with
+ * position i + floor(r_i * (m - i) / 2^32).  The first c positions, listed in
+ * ascending order, are the sample.  Needs c < m <= 256. */
+void laser_oracle_sample_ranks(int32_t m, int32_t c, uint64_t seed, uint32_t stream,
+                               uint64_t token, int32_t* ranks_out) {
+  int32_t arr[256];
+  uint32_t words[4];
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  for (int32_t i = 0; i < m; ++i) arr[i] = i;
+  for (int32_t i = 0; i < c; ++i) {
+    if ((i & 3) == 0) {
+      const uint32_t ctr[4] = {(uint32_t)token, (uint32_t)(token >> 32), stream, (uint32_t)(i >> 2)};
+      laser_oracle_philox4x32(ctr, key, words);
+    }
+    const int32_t j = i + (int32_t)(((uint64_t)words[i & 3] * (uint64_t)(m - i)) >> 32);
+    const int32_t tmp = arr[i]; arr[i] = arr[j]; arr[j] = tmp;
+  }
+  for (int32_t i = 1; i < c; ++i) {            /* ascending */
+    int32_t x = arr[i];
+    int32_t j = i - 1;
+    while (j >= 0 && arr[j] > x) { arr[j + 1] = arr[j]; --j; }
+    arr[j + 1] = x;
+  }
+  for (int32_t i = 0; i < c; ++i) ranks_out[i] = arr[i];
+}
+
+/* Algorithm 1 with mode RANDOM: as laser_oracle_route, except that a pool larger
+ * than c is trimmed to a uniform sample of c of its members (positions in the score
+ * order from laser_oracle_sample_ranks, token index = token_offset + t) instead of
+ * its c best.  The sampled candidates are listed in score order, so "tiebreak:
+ * descending score" and the output order are as before.  The top-k experts need not
+ * be in the sample. */
+int laser_oracle_route_random(const float* logits, int32_t T, int32_t E, int32_t k, int32_t c,
+                              float eps_high, float t_fix, int32_t renormalize,
+                              uint64_t seed, uint32_t stream, uint64_t token_offset,
+                              const int32_t* loads_in, int32_t* loads_out,
+                              int32_t* expert_ids, double* weights,
+                              int32_t* permutation, int32_t* offsets,
+                              uint8_t* expanded, int32_t* cstar_out) {
+  int rc = check_args(T, E, k, c, eps_high, t_fix);
+  if (rc) return rc;
+  const float tau_ln = (float)log((double)t_fix);
+  int64_t L[256];
+  int32_t ord[256], chosen[256], ranks[256], cand[256];
+  float d[256], p[256];
+  for (int32_t e = 0; e < E; ++e) L[e] = loads_in[e];
+
+  for (int32_t t = 0; t < T; ++t) {
+    const float* z = logits + (size_t)t * E;
+    order_desc_f32(z, E, ord);
+    const float zmax = z[ord[0]];
+    for (int32_t i = 0; i < E; ++i) {
+      d[i] = z[i] - zmax;
+      p[i] = laser_oracle_exp(d[i] < -80.0f ? -80.0f : d[i]);
+    }
+    const float Z = laser_oracle_tree_sum(p, E);
+    float Sk = p[ord[0]];
+    for (int32_t i = 1; i < k; ++i) Sk = Sk + p[ord[i]];
+
+    int32_t cstar = k;
+    int took_branch = 0;
+    if (Sk >= eps_high * Z) {
+      for (int32_t i = 0; i < k; ++i) cand[i] = ord[i];        /* A = top-k */
+      for (int32_t i = 0; i < k; ++i) chosen[i] = i;
+    } else {
+      took_branch = 1;
+      int32_t in_pool = 0;
+      for (int32_t i = 0; i < E; ++i) in_pool += (d[i] >= tau_ln);
+      int32_t m = in_pool > k ? in_pool : k;
+      cstar = c < m ? c : m;
+      if (m > c) laser_oracle_sample_ranks(m, c, seed, stream, token_offset + (uint64_t)t, ranks);
+      else for (int32_t i = 0; i < cstar; ++i) ranks[i] = i;
+      for (int32_t i = 0; i < cstar; ++i) cand[i] = ord[ranks[i]];
+      pick_least_loaded(cand, cstar, k, L, chosen);
+    }
+
+    double denom = 0.0;
+    if (renormalize) {
+      for (int32_t i = 0; i < k; ++i) denom += exp((double)z[cand[chosen[i]]] - (double)zmax);
+    } else {
+      for (int32_t i = 0; i < E; ++i) denom += exp((double)z[i] - (double)zmax);
+    }
+    for (int32_t i = 0; i < k; ++i) {
+      int32_t e = cand[chosen[i]];
+      expert_ids[(size_t)t * k + i] = e;
+      weights[(size_t)t * k + i] = exp((double)z[e] - (double)zmax) / denom;
+    }
+    for (int32_t i = 0; i < k; ++i) L[cand[chosen[i]]] += 1;
+    if (expanded) expanded[t] = (uint8_t)took_branch;
+    if (cstar_out) cstar_out[t] = cstar;
+  }
+  for (int32_t e = 0; e < E; ++e) loads_out[e] = (int32_t)L[e];
+  build_dispatch(expert_ids, T, k, E, permutation, offsets);
+  return ORACLE_OK;
+}
+
 /* ------------------------------------------------ per-token gate statistics -- */
 
 /* The statistics the paper reads off the gate scores to choose the thresholds

@@ -476,3 +476,115 @@ def test_imbalance_against_numpy_and_weights():
     pure[np.arange(E) % G, np.arange(E)] = 1.0
     rp = oracle.imbalance(n, placement=pure)
     assert (rp["I_gpu"] >= rp["I"] / (E // G) - 1e-12).all() and (rp["I_gpu"] <= rp["I"] + 1e-12).all()
+
+
+# ----------------------------------------------------------- RANDOM trimming ----
+
+def test_philox_known_answers():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.json")) as f:
+        kat = json.load(f)["vectors"]
+    for v in kat:
+        out = oracle.philox4x32([int(x, 16) for x in v["ctr"]], [int(x, 16) for x in v["key"]])
+        assert [f"{int(x):08x}" for x in out] == v["out"]
+
+
+def test_sample_ranks_by_hand_and_properties():
+    # seed 0, stream 0, token 0: the stream starts 6627e8d5, e169c58d (first vector
+    # above).  m = 3, c = 2: draw 0 swaps position 0 with 0 + floor(0.3990 * 3) = 1,
+    # draw 1 swaps position 1 with 1 + floor(0.8805 * 2) = 2: [0,1,2] -> [1,0,2] -> [1,2,0]
+    assert oracle.sample_ranks(3, 2, 0, 0, 0).tolist() == [1, 2]
+    # fifth draw comes from the second block (counter word 3 = 1)
+    blk1 = oracle.philox4x32([7, 0, 3, 1], [11, 0])
+    r = oracle.sample_ranks(200, 5, 11, 3, 7)
+    assert len(set(r.tolist())) == 5 and (np.diff(r) > 0).all() and r.min() >= 0 and r.max() < 200
+    arr = list(range(200))
+    blk0 = oracle.philox4x32([7, 0, 3, 0], [11, 0])
+    for i, w in enumerate(list(blk0) + [blk1[0]]):
+        j = i + ((int(w) * (200 - i)) >> 32)
+        arr[i], arr[j] = arr[j], arr[i]
+    assert sorted(arr[:5]) == r.tolist()
+    # token index and seed are 64-bit: the high halves reach the generator
+    assert oracle.sample_ranks(50, 4, 1 << 40, 0, 5).tolist() != oracle.sample_ranks(50, 4, 0, 0, 5).tolist()
+    assert oracle.sample_ranks(50, 4, 9, 0, 1 << 33).tolist() != oracle.sample_ranks(50, 4, 9, 0, 0).tolist()
+
+
+def test_sample_ranks_uniform():
+    """Every position is drawn with probability c/m and every pair equally often
+    (chi-square against the uniform law, fixed seed)."""
+    m, c, n = 10, 3, 30000
+    single = np.zeros(m)
+    pair = np.zeros((m, m))
+    for t in range(n):
+        r = oracle.sample_ranks(m, c, 2025, 1, t)
+        single[r] += 1
+        for a, b in itertools.combinations(r.tolist(), 2):
+            pair[a, b] += 1
+    exp1 = n * c / m
+    chi1 = ((single - exp1) ** 2 / exp1).sum()
+    assert chi1 < 27.9                      # 9 degrees of freedom, p = 0.001
+    iu = np.triu_indices(m, 1)
+    exp2 = n * 3 / 45.0                     # 3 pairs per sample, 45 possible pairs
+    chi2 = ((pair[iu] - exp2) ** 2 / exp2).sum()
+    assert chi2 < 78.8                      # 44 degrees of freedom, p = 0.001
+
+
+def test_random_trimming_reduces_to_top_when_nothing_is_trimmed():
+    z = wl.random_logits(91, 1500, 16, scale=1.2)
+    L0 = np.arange(16, dtype=np.int32) % 4
+    # pool never larger than c = E; and a threshold that no token fails
+    for k, c, eps, tfix in [(2, 16, 2.0, 0.05), (3, 16, 0.8, 0.3), (2, 5, 1e-6, 0.01)]:
+        a = oracle.route(z, k, c, eps, tfix, L0)
+        b = oracle.route_random(z, k, c, eps, tfix, L0, seed=77)
+        for key in ("expert_ids", "loads", "permutation", "expert_offsets", "expanded", "cstar"):
+            assert np.array_equal(a[key], b[key]), key
+        np.testing.assert_allclose(a["weights"], b["weights"], atol=0)
+
+
+def test_random_trimming_against_brute_force():
+    """Tiny shapes: Algorithm 1 re-enacted in Python on top of three separately pinned
+    pieces (branch flag, pool size, sampled positions); the k least-loaded candidates by
+    sorting (load, score rank) tuples."""
+    rng = np.random.default_rng(3)
+    sampled_tokens = 0
+    top_missing = 0
+    for trial in range(60):
+        E = int(rng.integers(4, 10))
+        k = int(rng.integers(1, 4))
+        c = int(rng.integers(k, min(E, k + 3) + 1))
+        T = 40
+        z = wl.random_logits(1000 + trial, T, E, scale=0.4)
+        eps, tfix = 0.95, 0.2
+        L = rng.integers(0, 3, E).astype(np.int64)
+        seed, stream, off = 1234 + trial, trial % 3, 10 ** 10 * trial
+        ref = oracle.route_random(z, k, c, eps, tfix, L.astype(np.int32), seed, stream, off)
+        m_all = oracle.token_stats(z, k, tfix)["pool_size"]
+        for t in range(T):
+            order = np.argsort(-z[t], kind="stable")
+            if not ref["expanded"][t]:
+                A = order[:k].tolist()
+            else:
+                m = int(m_all[t])
+                if m > c:
+                    ranks = oracle.sample_ranks(m, c, seed, stream, off + t).tolist()
+                    sampled_tokens += 1
+                    top_missing += 0 not in ranks
+                else:
+                    ranks = list(range(m))
+                keyed = sorted((int(L[order[r]]), r) for r in ranks)[:k]
+                A = [int(order[r]) for r in sorted(r for _, r in keyed)]
+            assert ref["expert_ids"][t].tolist() == A, (trial, t)
+            L[A] += 1
+        assert np.array_equal(ref["loads"], L)
+    assert sampled_tokens > 200 and top_missing > 20     # the best expert is not protected
+
+
+def test_random_trimming_split_call():
+    z = wl.random_logits(92, 600, 12, scale=0.3)
+    L0 = np.zeros(12, np.int32)
+    whole = oracle.route_random(z, 2, 4, 2.0, 0.01, L0, seed=5, stream=2, token_offset=1000)
+    a = oracle.route_random(z[:250], 2, 4, 2.0, 0.01, L0, seed=5, stream=2, token_offset=1000)
+    b = oracle.route_random(z[250:], 2, 4, 2.0, 0.01, a["loads"], seed=5, stream=2, token_offset=1250)
+    assert np.array_equal(np.vstack([a["expert_ids"], b["expert_ids"]]), whole["expert_ids"])
+    assert np.array_equal(b["loads"], whole["loads"])
+    other = oracle.route_random(z, 2, 4, 2.0, 0.01, L0, seed=6, stream=2, token_offset=1000)
+    assert not np.array_equal(other["expert_ids"], whole["expert_ids"])
