@@ -43,7 +43,7 @@ extern "C" {
 #define LASER_E_RANGE (-2)       /* T, H, E, k, c, eps_high or t_fix out of range */
 #define LASER_E_ALIGN (-3)       /* row length or pointer alignment not supported */
 #define LASER_E_WORKSPACE (-4)   /* workspace smaller than laser_workspace_bytes  */
-#define LASER_E_UNSUPPORTED (-5) /* E or c above the built limit, RANDOM trimming */
+#define LASER_E_UNSUPPORTED (-5) /* E or c above the built limit                  */
 #define LASER_E_STRUCT (-6)      /* params->struct_bytes does not match           */
 #define LASER_E_LAUNCH (-7)      /* the HIP runtime refused a kernel launch       */
 
@@ -51,7 +51,7 @@ extern "C" {
 #define LASER_DTYPE_BF16 1
 
 #define LASER_TRIM_TOP 0    /* keep the c highest-scoring pool members (built)       */
-#define LASER_TRIM_RANDOM 1 /* uniform sample of the pool: returns E_UNSUPPORTED     */
+#define LASER_TRIM_RANDOM 1 /* uniform sample of c pool members, see laser_params_t  */
 
 #define LASER_MAX_E 64
 #define LASER_MAX_C 16
@@ -67,6 +67,18 @@ typedef struct laser_params {
   int32_t trim_mode;     /* LASER_TRIM_*                                            */
   int32_t renormalize;   /* 1: weights sum to 1 over the k chosen; 0: raw scores    */
   int32_t dtype;         /* LASER_DTYPE_* of hidden and w_gate (laser_route only)   */
+  /* LASER_TRIM_RANDOM only (Algorithm 1, mode RANDOM: "uniformly sample c* indices
+   * from the pool, without replacement").  The sample of a token is a function of
+   * (seed, stream, token_offset + t) alone: Philox4x32-10 with key = seed and counter
+   * = (token index low, high, stream, block); a partial Fisher-Yates shuffle of the
+   * pool's positions [0, m) in the score order swaps position i with
+   * i + floor(r_i * (m - i) / 2^32), i = 0..c-1, r_i the i-th 32-bit word of the
+   * token's stream; the first c positions are the candidates.  Pools of at most c
+   * members are not sampled.  Ignored for LASER_TRIM_TOP. */
+  uint64_t seed;         /* generator key                                           */
+  uint64_t token_offset; /* caller's index of token 0 of this call (split calls)    */
+  uint32_t stream;       /* caller's stream id, e.g. the layer                      */
+  uint32_t reserved;     /* 0                                                       */
 } laser_params_t;
 
 /* Bytes of device workspace a call with these sizes needs (0 on bad arguments).

@@ -34,6 +34,10 @@ class LaserParams(ctypes.Structure):
         ("trim_mode", ctypes.c_int32),
         ("renormalize", ctypes.c_int32),
         ("dtype", ctypes.c_int32),
+        ("seed", ctypes.c_uint64),
+        ("token_offset", ctypes.c_uint64),
+        ("stream", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -80,9 +84,10 @@ _lib = _load()
 
 
 def make_params(k: int, c: int, eps_high: float, t_fix: float, dtype: int = DTYPE_BF16,
-                renormalize: bool = True, trim_mode: int = TRIM_TOP) -> LaserParams:
+                renormalize: bool = True, trim_mode: int = TRIM_TOP, seed: int = 0,
+                stream: int = 0, token_offset: int = 0) -> LaserParams:
     return LaserParams(ctypes.sizeof(LaserParams), k, c, eps_high, t_fix, trim_mode,
-                       1 if renormalize else 0, dtype)
+                       1 if renormalize else 0, dtype, seed, token_offset, stream, 0)
 
 
 def laser_strerror(code: int) -> str:

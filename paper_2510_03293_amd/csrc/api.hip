@@ -115,7 +115,7 @@ static int check_params(int32_t T, int32_t E, const laser_params_t* p) {
   if (p->k < 1 || p->c < p->k || p->c > E) return LASER_E_RANGE;
   if (!(p->eps_high > 0.0f) || !(p->t_fix > 0.0f) || !(p->t_fix <= 1.0f)) return LASER_E_RANGE;
   if ((int64_t)T * p->k > 0x7fffffffLL) return LASER_E_RANGE;
-  if (p->trim_mode != LASER_TRIM_TOP) return LASER_E_UNSUPPORTED;
+  if (p->trim_mode != LASER_TRIM_TOP && p->trim_mode != LASER_TRIM_RANDOM) return LASER_E_RANGE;
   if (E > LASER_MAX_E || p->c > LASER_MAX_C) return LASER_E_UNSUPPORTED;
   return LASER_OK;
 }
@@ -135,6 +135,14 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.st_entropy = nullptr;
   a.st_pool = nullptr;
   return a;
+}
+
+static RandomArgs make_random(const laser_params_t* p) {
+  RandomArgs r;
+  r.seed = p->seed;
+  r.token_offset = p->token_offset;
+  r.stream = p->stream;
+  return r;
 }
 
 static int route_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
@@ -184,16 +192,27 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t
   const Workspace ws = carve_workspace(workspace, T, E, need_logits);
   const bool timed = !g_profile.ev.empty() && (size_t)(2 * g_profile.used + 1) < g_profile.ev.size() && T > 0;
   if (timed && hipEventRecord(g_profile.ev[2 * g_profile.used], s) != hipSuccess) return LASER_E_LAUNCH;
+  const bool random = params->trim_mode == LASER_TRIM_RANDOM;
   if (params->dtype == LASER_DTYPE_BF16) {
-    // gate projection and per-token analysis in one kernel
-    if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits_out, s) != hipSuccess)
+    // gate projection and per-token analysis in one kernel; RANDOM trimming takes the
+    // logits from it and analyses again with its own kernel (that mode is not tuned)
+    float* logits = random ? (logits_out ? logits_out : ws.logits) : logits_out;
+    if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits, s) != hipSuccess)
+      return LASER_E_LAUNCH;
+    if (random && launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) !=
+                      hipSuccess)
       return LASER_E_LAUNCH;
   } else {
     float* logits = logits_out ? logits_out : ws.logits;
     if (launch_gate_f32(static_cast<const float*>(hidden), static_cast<const float*>(w_gate), T, H, E,
                         logits, s) != hipSuccess)
       return LASER_E_LAUNCH;
-    if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+    if (random) {
+      if (launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
+        return LASER_E_LAUNCH;
+    } else if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) {
+      return LASER_E_LAUNCH;
+    }
   }
   if (timed) {
     if (hipEventRecord(g_profile.ev[2 * g_profile.used + 1], s) != hipSuccess) return LASER_E_LAUNCH;
@@ -236,7 +255,12 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
   const RouteArgs a = make_args(T, E, params);
   const Workspace ws = carve_workspace(workspace, T, E, true);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+  if (params->trim_mode == LASER_TRIM_RANDOM) {
+    if (launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
+      return LASER_E_LAUNCH;
+  } else if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) {
+    return LASER_E_LAUNCH;
+  }
   return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
 }
 
@@ -247,7 +271,7 @@ const char* laser_strerror(int code) {
     case LASER_E_RANGE: return "argument out of range (T, H, E, k, c, eps_high, t_fix or dtype)";
     case LASER_E_ALIGN: return "unsupported row length or pointer alignment";
     case LASER_E_WORKSPACE: return "workspace too small";
-    case LASER_E_UNSUPPORTED: return "not built: E > 64, c > 16, or RANDOM trimming";
+    case LASER_E_UNSUPPORTED: return "not built: E > 64 or c > 16";
     case LASER_E_STRUCT: return "laser_params_t.struct_bytes mismatch";
     case LASER_E_LAUNCH: return "HIP kernel launch failed";
     default: return "unknown error code";

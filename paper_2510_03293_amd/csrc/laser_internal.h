@@ -28,6 +28,12 @@ struct RouteArgs {
   float* st_entropy;   // Shannon entropy of the scores, nats
   int32_t* st_pool;    // pool size m (candidates above the cut, united with the top-k)
 };
+// Trimming mode RANDOM: what makes the sample reproducible.
+struct RandomArgs {
+  unsigned long long seed;          // generator key
+  unsigned long long token_offset;  // index of token 0 of this call in the caller's numbering
+  uint32_t stream;                  // caller's stream id (e.g. the layer)
+};
 inline bool wants_stats(const RouteArgs& a) { return a.st_mass || a.st_entropy || a.st_pool; }
 
 // Device workspace carved out of the caller's buffer.  Records are written by
@@ -76,6 +82,10 @@ hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, in
                            float* logits, hipStream_t s);
 hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s);
+// per-token analysis with RANDOM trimming, from logits [T,E]
+hipError_t launch_analyse_random(const float* logits, const RouteArgs& a, const Workspace& ws,
+                                 const RandomArgs& rnd, int32_t* expert_ids, float* weights,
+                                 hipStream_t s);
 hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                        int32_t* expert_offsets, int32_t* expert_ids, float* weights,
                        int32_t* permutation, hipStream_t s);

@@ -59,6 +59,30 @@ def run_route_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize=T
     return _collect(buf, loads, None)
 
 
+def run_random_from_logits(logits, k, c, eps_high, t_fix, loads_in, seed, stream=0, token_offset=0,
+                           renormalize=True):
+    params = B.make_params(k, c, eps_high, t_fix, renormalize=renormalize, trim_mode=B.TRIM_RANDOM,
+                           seed=seed, stream=stream, token_offset=token_offset)
+    ld = torch.from_numpy(np.ascontiguousarray(logits, dtype=np.float32)).cuda()
+    loads = torch.from_numpy(np.ascontiguousarray(loads_in, dtype=np.int32)).cuda()
+    buf = B.route_from_logits(ld, params, loads)
+    torch.cuda.synchronize()
+    return _collect(buf, loads, None)
+
+
+def check_random_from_logits(logits, k, c, eps_high, t_fix, loads_in, seed, stream=0, token_offset=0,
+                             renormalize=True, tol=1e-5, label=""):
+    gpu = run_random_from_logits(logits, k, c, eps_high, t_fix, loads_in, seed, stream, token_offset,
+                                 renormalize)
+    ref = oracle.route_random(logits, k, c, eps_high, t_fix, loads_in, seed, stream, token_offset,
+                              renormalize)
+    assert_discrete_equal(gpu, ref, label)
+    if gpu["weights"].size:
+        err = np.abs(gpu["weights"].astype(np.float64) - ref["weights"]).max()
+        assert err <= tol, f"{label}: weights max abs err {err}"
+    return gpu, ref
+
+
 def _collect(buf, loads, logits):
     out = {
         "expert_ids": buf.expert_ids.cpu().numpy(),

@@ -169,6 +169,84 @@ def test_random_cases_against_oracle():
     assert flexible > 100000
 
 
+# ------------------------------------------------------------- RANDOM trimming ----
+
+RANDOM_SHAPES = [
+    # T, E, k, c, eps, tfix, kind
+    (1, 8, 2, 4, 2.0, 1e-30, "normal"),
+    (63, 8, 2, 4, 0.9, 0.05, "normal"),
+    (500, 8, 2, 3, 2.0, 1e-30, "normal"),        # every token sampled, c = k + 1
+    (500, 8, 2, 2, 2.0, 1e-30, "normal"),        # c = k: a random k of the pool, no load dependence
+    (1000, 64, 6, 8, 2.0, 0.02, "normal"),
+    (3000, 64, 6, 16, 0.9, 0.1, "normal"),       # more than four draws per token
+    (700, 33, 4, 7, 0.8, 0.3, "normal"),
+    (900, 12, 3, 5, 0.999, 0.01, "ties"),
+    (5000, 16, 2, 4, 0.7, 0.2, "normal"),
+    (257, 64, 1, 16, 2.0, 1e-30, "normal"),
+]
+
+
+@pytest.mark.parametrize("T,E,k,c,eps,tfix,kind", RANDOM_SHAPES)
+def test_random_trimming_from_logits(T, E, k, c, eps, tfix, kind):
+    u = _util()
+    rng = np.random.default_rng(T * 17 + E)
+    logits = wl.random_logits(T + 2 * E + c, T, E, kind=kind, tie_levels=3, scale=0.5)
+    loads_in = rng.integers(0, 9, size=E).astype(np.int32)
+    for renorm in (True, False):
+        u.check_random_from_logits(logits, k, c, eps, tfix, loads_in, seed=2 ** 40 + 12345 + T,
+                                   stream=E, token_offset=2 ** 33 + 5, renormalize=renorm,
+                                   label=f"random T{T} E{E} k{k} c{c}")
+
+
+def test_random_trimming_equals_top_when_nothing_is_trimmed():
+    """With c as large as any pool the sampling never happens: the RANDOM analysis
+    kernel must then reproduce the deterministic path bit for bit."""
+    u = _util()
+    for T, E, k, c, eps, tfix in [(2000, 16, 2, 16, 0.9, 0.2), (1500, 64, 6, 16, 0.5, 0.6),
+                                  (700, 8, 2, 8, 2.0, 1e-30)]:
+        logits = wl.random_logits(T + E, T, E, scale=1.0)
+        loads_in = (np.arange(E) % 3).astype(np.int32)
+        top = u.run_route_from_logits(logits, k, c, eps, tfix, loads_in)
+        rnd = u.run_random_from_logits(logits, k, c, eps, tfix, loads_in, seed=99)
+        for key in ("expert_ids", "permutation", "expert_offsets", "loads"):
+            assert np.array_equal(top[key], rnd[key]), key
+        assert np.abs(top["weights"] - rnd["weights"]).max() <= 1e-6
+
+
+def test_random_trimming_full_path_and_split_calls():
+    """From hidden states (bf16 gate), and the same tokens in two calls with
+    token_offset carried: identical choices."""
+    import oracle
+    u = _util()
+    import torch
+    from paper_2510_03293_amd import binding as B
+    rng = np.random.default_rng(321)
+    T, H, E, k, c = 900, 512, 32, 4, 6
+    hidden, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16)
+    kw = dict(dtype=wl.DTYPE_BF16, trim_mode=B.TRIM_RANDOM, seed=7, stream=3)
+    hd, wd = u.to_device(hidden), u.to_device(w)
+
+    def run(rows, loads, off):
+        params = B.make_params(k, c, 2.0, 0.05, token_offset=off, **kw)
+        buf = B.route(hd[rows], wd, params, loads, want_logits=True)
+        torch.cuda.synchronize()
+        return buf
+    loads = torch.zeros(E, dtype=torch.int32, device="cuda")
+    whole = run(slice(0, T), loads, 100)
+    z = whole.logits.cpu().numpy()
+    assert np.abs(z - oracle.gate(hidden, w, wl.DTYPE_BF16)).max() <= 2e-3
+    ref = oracle.route_random(z, k, c, 2.0, 0.05, np.zeros(E, np.int32), 7, 3, 100)
+    assert np.array_equal(whole.expert_ids.cpu().numpy(), ref["expert_ids"])
+    assert np.array_equal(whole.permutation.cpu().numpy(), ref["permutation"])
+    assert np.array_equal(loads.cpu().numpy(), ref["loads"])
+    l2 = torch.zeros(E, dtype=torch.int32, device="cuda")
+    a = run(slice(0, 333), l2, 100)
+    ids_a = a.expert_ids.cpu().numpy().copy()
+    b = run(slice(333, T), l2, 433)
+    assert np.array_equal(np.vstack([ids_a, b.expert_ids.cpu().numpy()]), ref["expert_ids"])
+    assert np.array_equal(l2.cpu().numpy(), ref["loads"])
+
+
 def test_extreme_logits():
     """Scores that underflow the clamp, huge spreads, and all-equal rows."""
     u = _util()
