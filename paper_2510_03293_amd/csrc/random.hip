@@ -13,9 +13,10 @@
 // the score order swaps position i with i + floor(r_i * (m - i) / 2^32) for
 // i = 0..c-1; the first c positions, in ascending order, are the candidates.
 //
-// One wavefront per tile of 64 tokens, lane = token, per-token arrays in LDS.  The
-// order statistics are found by counting (E^2 compares per token): this mode is
-// written for clarity, not for speed.
+// One workgroup per tile of 64 tokens, lane = token, per-token arrays in LDS.  The
+// order statistics are found by counting (E^2 compares per token, shared by four
+// waves); everything after that is one wavefront's work.  This mode is written for
+// clarity, not for speed.
 #include "analyse.h"
 #include "laser_internal.h"
 
@@ -44,7 +45,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[3] = c3;
 }
 
-__global__ __launch_bounds__(64) void analyse_random_kernel(const float* __restrict__ logits,
+constexpr int kRandomWaves = 4;  // the counting pass is shared by 4 waves, the rest is wave 0's
+
+__global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const float* __restrict__ logits,
                                                             const RouteArgs a, const Workspace ws,
                                                             const RandomArgs rnd,
                                                             int32_t* __restrict__ expert_ids,
@@ -52,18 +55,19 @@ __global__ __launch_bounds__(64) void analyse_random_kernel(const float* __restr
   __shared__ float zl[kTile * kRowF], pl[kTile * kRowF], tl[kTile * kRowF];
   __shared__ uint8_t ordl[kTile * kRowB], arrl[kTile * kRowB];
   __shared__ unsigned long long maskl[64];
-  const int tile = blockIdx.x, lane = threadIdx.x;
+  const int tile = blockIdx.x, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
   const int E = a.E, k = a.k, c = a.c;
 
   // the tail kernel of this call polls these words; they are cleared here, one
   // kernel earlier on the same stream
-  if (tile == 0 && lane < 4) ws.status[lane] = 0;
+  if (tile == 0 && threadIdx.x < 4) ws.status[threadIdx.x] = 0;
 
   const int rows = min(kTile, a.T - tile * kTile);
   const float* src = logits + (size_t)tile * kTile * E;
-  for (int idx = lane; idx < kTile * E; idx += 64) {
+  for (int idx = threadIdx.x; idx < kTile * E; idx += 64 * kRandomWaves) {
     const int tok = idx / E;
     zl[tok * kRowF + (idx - tok * E)] = tok < rows ? src[idx] : 0.0f;
   }
@@ -76,7 +80,8 @@ __global__ __launch_bounds__(64) void analyse_random_kernel(const float* __restr
   uint8_t* arr = arrl + lane * kRowB;  // candidate positions
 
   // ---- order: logit descending, equal logits by lower index -------------------
-  for (int i = 0; i < E; ++i) {
+  // (wave w places experts w, w + 4, ...; every wave sees all 64 tokens)
+  for (int i = wave; i < E; i += kRandomWaves) {
     const float zi = z[i];
     int before = 0;
     for (int j = 0; j < E; ++j) {
@@ -85,6 +90,8 @@ __global__ __launch_bounds__(64) void analyse_random_kernel(const float* __restr
     }
     ord[before] = (uint8_t)i;
   }
+  __syncthreads();
+  if (wave != 0) return;  // (a barrier counts only the waves that are still running)
   const float zmax = z[ord[0]];
 
   // ---- scores, normaliser (fixed tree), top-k mass, pool ------------------------
@@ -201,7 +208,7 @@ hipError_t launch_analyse_random(const float* logits, const RouteArgs& a, const 
                                  const RandomArgs& rnd, int32_t* expert_ids, float* weights,
                                  hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(analyse_random_kernel, dim3(a.ntiles), dim3(64), 0, s, logits, a, ws, rnd,
+  hipLaunchKernelGGL(analyse_random_kernel, dim3(a.ntiles), dim3(64 * kRandomWaves), 0, s, logits, a, ws, rnd,
                      expert_ids, weights);
   return hipGetLastError();
 }
