@@ -821,23 +821,31 @@ struct FinishLds {
 struct FinishPrologue {
   int cstar;               // working-set size of a flexible token, else 0
   unsigned long long fm;   // the tile's flexible-token mask
+  int ids[kMaxC];          // experts of the token as the analysis left them (k entries)
 };
 
-__device__ __forceinline__ FinishPrologue finish_prologue(FinishLds* fl, int tile, const RouteArgs& a,
-                                                          const Workspace& ws,
+// Requests the loads only; nothing here waits for them.
+__device__ __forceinline__ FinishPrologue finish_prologue(int tile, const RouteArgs& a, const Workspace& ws,
                                                           const int32_t* __restrict__ expert_ids) {
   const int lane = threadIdx.x & 63;
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
   FinishPrologue p;
-  fl->mask64[lane] = 0ull;
   p.cstar = live ? ws.rec_cstar[t] : 0;
   p.fm = ws.flexmask[tile];
-  // experts of the tokens that are final already (rows of flexible tokens hold stale data;
-  // they are overwritten in finish_tile)
-  if (live)
-    for (int j = 0; j < a.k; ++j) fl->ids[lane][j] = (uint8_t)expert_ids[(size_t)t * a.k + j];
+#pragma unroll
+  for (int j = 0; j < kMaxC; ++j) p.ids[j] = (live && j < a.k) ? expert_ids[(size_t)t * a.k + j] : 0;
   return p;
+}
+
+// experts of the tokens that are final already go to LDS (rows of flexible tokens hold
+// stale data; they are overwritten in finish_tile)
+__device__ __forceinline__ void finish_commit(FinishLds* fl, const FinishPrologue& p, int k) {
+  const int lane = threadIdx.x & 63;
+  fl->mask64[lane] = 0ull;
+#pragma unroll
+  for (int j = 0; j < kMaxC; ++j)
+    if (j < k) fl->ids[lane][j] = (uint8_t)p.ids[j];
 }
 
 // One wavefront, one tile; `fl` is this wave's private LDS.
@@ -933,7 +941,9 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     for (int j = 0; j < k; ++j) {
       const int e = fl->ids[lane][j];
       const int pos = fl->before[e] + __builtin_popcountll(fl->mask64[e] & below);
-      permutation[pos] = t * k + j;
+      // (pos is a slot number by construction; the check turns any inconsistency of
+      // the inputs into a missing entry instead of a stray store)
+      if ((unsigned)pos < (unsigned)(a.T * k)) permutation[pos] = t * k + j;
     }
   }
 }
@@ -999,7 +1009,8 @@ __device__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int
   bool flex = false;
 #pragma unroll
   for (int u = 0; u < kSelfPrefixTiles / kTailThreads; ++u) flex |= fmv[u] != 0ull;
-  if (__builtin_amdgcn_ballot_w64(flex) != 0ull && lane == 0) *sh_anyflex = 1;
+  const bool any = __builtin_amdgcn_ballot_w64(flex) != 0ull;  // (all lanes take part)
+  if (lane == 0) sh_anyflex[wave] = any ? 1 : 0;
 }
 
 __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, const Workspace ws,
@@ -1015,36 +1026,40 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   }
   __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
   __shared__ int own_base[kChainWaves][64], own_offsets[64];
-  __shared__ int sh_anyflex;
+  __shared__ int sh_anyflex[kChainWaves];  // per wave: some tile it looked at holds flexible tokens
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t0 = (blockIdx.x - 1) * kChainWaves;
   const int tile = t0 + wave;
   // Small problems without flexible tokens need nothing from the chain workgroup:
   // every finishing workgroup sums the byte counts itself.
   FinishLds* fl = reinterpret_cast<FinishLds*>(tail_lds) + wave;
-  FinishPrologue pro = {0, 0ull};
-  if (tile < a.ntiles) pro = finish_prologue(fl, tile, a, ws, expert_ids);  // loads overlap the sums below
+  const bool small = a.ntiles <= kSelfPrefixTiles;
+  // (no barrier from here to the end of self_prefix: a barrier waits for every load in
+  // flight, and the point is to have all of this workgroup's loads in flight at once)
+  FinishPrologue pro;
+  pro.cstar = 0;
+  pro.fm = 0ull;
+  if (tile < a.ntiles) pro = finish_prologue(tile, a, ws, expert_ids);
   bool self = false;
-  // fixed counts of the workgroup's earlier tiles (needed by the self path; requested
-  // now so that they arrive together with everything else)
-  int wg_before = 0;
-  if (a.ntiles <= kSelfPrefixTiles) {
+  // fixed counts of the workgroup's earlier tiles (needed by the self path)
+  int wg_cnt[kChainWaves - 1];
 #pragma unroll
-    for (int j = 0; j < kChainWaves - 1; ++j)
-      if (j < wave && t0 + j < a.ntiles) wg_before += ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane];
-  }
-  if (a.ntiles <= kSelfPrefixTiles) {
-    if (threadIdx.x == 0) sh_anyflex = 0;
+  for (int j = 0; j < kChainWaves - 1; ++j)
+    wg_cnt[j] = (small && j < wave && t0 + j < a.ntiles) ? ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane] : 0;
+  if (small) {
+    self_prefix(t0, a, ws, sh_before, sh_all, sh_anyflex);
+    if (tile < a.ntiles) finish_commit(fl, pro, a.k);
     __syncthreads();
-    self_prefix(t0, a, ws, sh_before, sh_all, &sh_anyflex);
-    __syncthreads();
-    self = sh_anyflex == 0;
+    self = (sh_anyflex[0] | sh_anyflex[1] | sh_anyflex[2] | sh_anyflex[3]) == 0;
     if (self) {
       int before = 0, all = 0;
       for (int w = 0; w < kChainWaves; ++w) {
         before += sh_before[w][lane];
         all += sh_all[w][lane];
       }
+      int wg_before = 0;
+#pragma unroll
+      for (int j = 0; j < kChainWaves - 1; ++j) wg_before += wg_cnt[j];
       own_base[wave][lane] = before + wg_before;  // this wave's tile: plus the workgroup's earlier tiles
       if (wave == 0) {
         int incl = lane < a.E ? all : 0;
@@ -1058,6 +1073,8 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
       }
     }
     __syncthreads();
+  } else if (tile < a.ntiles) {
+    finish_commit(fl, pro, a.k);
   }
   if (tile >= a.ntiles) return;
   finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, self,
