@@ -371,8 +371,10 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
     ws.rec_Z[t] = zsum;
   }
 
-  if (tid < 64)
+  if (tid < 64) {
     ws.tile_fixed_cnt[(size_t)tile * 64 + tid] = (uint8_t)__builtin_popcountll(mask64[tid]);
+    ws.tile_mask[(size_t)tile * 64 + tid] = mask64[tid];
+  }
   const unsigned long long fm = *flex_lds;
   if (tid == 0) ws.flexmask[tile] = fm;
 

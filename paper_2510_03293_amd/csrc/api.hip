@@ -14,7 +14,7 @@ namespace laser {
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, base, chain_bits,
+  size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
       chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, status, total;
 };
 
@@ -32,6 +32,7 @@ static Layout layout(int T, int E, bool need_logits) {
   L.rec_lane = off;   off += align_up(slots * EP * 2);
   L.flexmask = off;   off += align_up(ntiles * 8);
   L.fixed_cnt = off;  off += align_up(ntiles * 64);
+  L.tile_mask = off;  off += align_up(ntiles * 64 * 8);
   L.base = off;       off += align_up(ntiles * 64 * 4);
   const size_t words = (size_t)T / 32 + 2;
   L.chain_bits = off; off += align_up(words * 64 * 4);
@@ -61,6 +62,7 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.rec_lane = reinterpret_cast<uint16_t*>(b + L.rec_lane);
   w.flexmask = reinterpret_cast<unsigned long long*>(b + L.flexmask);
   w.tile_fixed_cnt = reinterpret_cast<uint8_t*>(b + L.fixed_cnt);
+  w.tile_mask = reinterpret_cast<unsigned long long*>(b + L.tile_mask);
   w.tile_base = reinterpret_cast<int32_t*>(b + L.base);
   w.chain_bits = reinterpret_cast<uint32_t*>(b + L.chain_bits);
   w.chain_cum = reinterpret_cast<int32_t*>(b + L.chain_cum);

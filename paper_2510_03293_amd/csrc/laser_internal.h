@@ -49,6 +49,8 @@ struct Workspace {
   uint16_t* rec_lane;          // [slot,EP] per expert: (fixed-prefix << 4 | rank) or 0xFFFF
   unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
   uint8_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens (<= 64)
+  unsigned long long* tile_mask;   // [ntiles,64] per expert: the tile's non-flexible tokens
+                               //           assigned to it (bit = token within the tile)
   int32_t* tile_base;          // [ntiles,64] assignments of all earlier tiles, per expert
   uint8_t* rec_cids;           // [slot,16] lanes the chain reads: candidates by rank, padded
   uint8_t* rec_pref;           // [slot,16] per candidate (by rank): earlier fixed tokens of the

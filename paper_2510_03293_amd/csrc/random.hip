@@ -167,6 +167,7 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
   }
   maskl[lane] = mymask;
   ws.tile_fixed_cnt[(size_t)tile * 64 + lane] = (uint8_t)__builtin_popcountll(mymask);
+  ws.tile_mask[(size_t)tile * 64 + lane] = mymask;
   const unsigned long long fm = __builtin_amdgcn_ballot_w64(flex);
   if (lane == 0) ws.flexmask[tile] = fm;
   if (live) {

@@ -821,6 +821,7 @@ struct FinishLds {
 struct FinishPrologue {
   int cstar;               // working-set size of a flexible token, else 0
   unsigned long long fm;   // the tile's flexible-token mask
+  unsigned long long tmask;  // lane = expert: the tile's non-flexible tokens assigned to it
   int ids[kMaxC];          // experts of the token as the analysis left them (k entries)
 };
 
@@ -833,6 +834,7 @@ __device__ __forceinline__ FinishPrologue finish_prologue(int tile, const RouteA
   FinishPrologue p;
   p.cstar = live ? ws.rec_cstar[t] : 0;
   p.fm = ws.flexmask[tile];
+  p.tmask = ws.tile_mask[(size_t)tile * 64 + lane];
 #pragma unroll
   for (int j = 0; j < kMaxC; ++j) p.ids[j] = (live && j < a.k) ? expert_ids[(size_t)t * a.k + j] : 0;
   return p;
@@ -842,7 +844,7 @@ __device__ __forceinline__ FinishPrologue finish_prologue(int tile, const RouteA
 // stale data; they are overwritten in finish_tile)
 __device__ __forceinline__ void finish_commit(FinishLds* fl, const FinishPrologue& p, int k) {
   const int lane = threadIdx.x & 63;
-  fl->mask64[lane] = 0ull;
+  fl->mask64[lane] = p.tmask;  // the flexible tokens add themselves in finish_tile
 #pragma unroll
   for (int j = 0; j < kMaxC; ++j)
     if (j < k) fl->ids[lane][j] = (uint8_t)p.ids[j];
@@ -932,7 +934,8 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
   // compiler from moving reads above the other lanes' writes
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
-  if (live)
+  // (the masks came from the analysis with the non-flexible tokens in them)
+  if (cstar > 0)
     for (int j = 0; j < k; ++j) atomicOr(&fl->mask64[fl->ids[lane][j]], 1ull << lane);
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
@@ -1039,6 +1042,7 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   FinishPrologue pro;
   pro.cstar = 0;
   pro.fm = 0ull;
+  pro.tmask = 0ull;
   if (tile < a.ntiles) pro = finish_prologue(tile, a, ws, expert_ids);
   bool self = false;
   // fixed counts of the workgroup's earlier tiles (needed by the self path)
