@@ -30,10 +30,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # Valid only for the kernel sources they were taken on: the record carries their hash
 # and `traffic` is reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "20b9da794c1383d6",
+    "sources_sha256_16": "11fa697bee41d0bc",
     "workload": "deepseek",
-    "fetch_kib": 33909.43, "fetch_scale": 1.9997,
-    "write_kib": 872.08, "write_scale": 1.0,
+    "fetch_kib": 33911.70, "fetch_scale": 1.9997,
+    "write_kib": 1000.08, "write_scale": 1.0,
 }
 GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
 
