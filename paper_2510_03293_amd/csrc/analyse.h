@@ -243,10 +243,14 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       const int i = g * G + r;
       const int e = owned(i);
       const bool real = live && e < a.E;
-      if (logits_out != nullptr && real) logits_out[(size_t)t * a.E + e] = v[r];
       z[i] = real ? v[r] : kLowestLogit;
       K[i] = make_key(z[i], e);
     }
+  }
+  if (logits_out != nullptr) {  // (one uniform test instead of one per element)
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+      if (live && owned(i) < a.E) logits_out[(size_t)t * a.E + owned(i)] = z[i];
   }
   __syncthreads();  // masks zeroed before anyone ORs into them
 
