@@ -922,7 +922,7 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     int n = 0;
     for (int j = 0; j < cstar; ++j) {
       const int e = ids[j];
-      if ((chosen >> e) & 1ull) {
+      if (((chosen >> e) & 1ull) && n < k) {  // (exactly k bits are set; n < k keeps the row)
         expert_ids[(size_t)t * k + n] = e;
         weights[(size_t)t * k + n] = pv[j] / denom;
         fl->ids[lane][n] = (uint8_t)e;
