@@ -214,6 +214,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   // the tail kernel of this call polls these words; they are cleared here, one
   // kernel earlier on the same stream
   if (tile == 0 && tid < 4) ws.status[tid] = 0;
+  if (tile == 0 && tid < 64) ws.lin_copy[tid] = tid < a.E ? a.loads_in[tid] : 0;
 
   constexpr int G = NE < 4 ? NE : 4;      // consecutive experts per run
   constexpr int NG = NE / G;              // runs per lane

@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
-      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, status, total;
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, status, total;
 };
 
 static Layout layout(int T, int E, bool need_logits) {
@@ -43,6 +43,7 @@ static Layout layout(int T, int E, bool need_logits) {
   L.flex_ord = off;   off += align_up(ntiles * 4);
   L.flex_tok_base = off; off += align_up((ntiles + 1) * 4);
   L.flex_slot = off;  off += align_up((size_t)T * 4);
+  L.lin_copy = off;   off += align_up(64 * 4);
   L.status = off;     off += align_up(16);
   L.total = off + 256;
   return L;
@@ -72,6 +73,7 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.flex_ord = reinterpret_cast<int32_t*>(b + L.flex_ord);
   w.flex_tok_base = reinterpret_cast<int32_t*>(b + L.flex_tok_base);
   w.flex_slot = reinterpret_cast<int32_t*>(b + L.flex_slot);
+  w.lin_copy = reinterpret_cast<int32_t*>(b + L.lin_copy);
   w.status = reinterpret_cast<int32_t*>(b + L.status);
   return w;
 }
@@ -133,6 +135,7 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.renormalize = p->renormalize ? 1 : 0;
   a.eps_high = p->eps_high;
   a.tau_ln = (float)log((double)p->t_fix);
+  a.loads_in = nullptr;
   a.st_mass = nullptr;
   a.st_entropy = nullptr;
   a.st_pool = nullptr;
@@ -188,6 +191,7 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   RouteArgs a = make_args(T, E, params);
+  a.loads_in = loads_inout;
   a.st_mass = topk_mass;
   a.st_entropy = entropy;
   a.st_pool = pool_size;
@@ -254,7 +258,8 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
   if (T > 0 && (!logits || !expert_ids || !weights || !permutation)) return LASER_E_NULL;
   if ((uintptr_t)workspace & 255) return LASER_E_ALIGN;
   if (workspace_bytes_given < workspace_bytes(T, E, true)) return LASER_E_WORKSPACE;
-  const RouteArgs a = make_args(T, E, params);
+  RouteArgs a = make_args(T, E, params);
+  a.loads_in = loads_inout;
   const Workspace ws = carve_workspace(workspace, T, E, true);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (params->trim_mode == LASER_TRIM_RANDOM) {

@@ -23,6 +23,8 @@ struct RouteArgs {
   int renormalize;  // weights over the chosen k (1) or raw softmax scores (0)
   float eps_high;   // top-k mass threshold
   float tau_ln;     // fl32(ln t_fix): pool cut-off in the logit domain
+  const int32_t* loads_in;  // [E] the caller's counters before token 0 (copied to the workspace
+                            // by the analysis so that the tail can read them while it writes)
   // optional per-token statistics, [T] each, any may be NULL (all NULL: not computed)
   float* st_mass;      // top-k mass M_k
   float* st_entropy;   // Shannon entropy of the scores, nats
@@ -62,6 +64,7 @@ struct Workspace {
   uint32_t* chain_bits;        // [T/32+1,64] per expert: bit f%32 of word f/32 = chosen for
                                //           the f-th flexible token
   int32_t* chain_cum;          // [T/32+2,64] per expert: choices by flexible tokens < 32*w
+  int32_t* lin_copy;           // [64] loads before token 0 (0 beyond E)
   int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
 };
 

@@ -64,6 +64,7 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
   // the tail kernel of this call polls these words; they are cleared here, one
   // kernel earlier on the same stream
   if (tile == 0 && threadIdx.x < 4) ws.status[threadIdx.x] = 0;
+  if (tile == 0 && threadIdx.x < 64) ws.lin_copy[threadIdx.x] = (int)threadIdx.x < a.E ? a.loads_in[threadIdx.x] : 0;
 
   const int rows = min(kTile, a.T - tile * kTile);
   const float* src = logits + (size_t)tile * kTile * E;

@@ -133,6 +133,16 @@ constexpr int kTailThreads = kChainWaves * 64;
 constexpr int kChainBatch = 3;  // flexible tiles per LDS batch
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kSelfPrefixTiles = 1024;  // up to here finishing workgroups sum the counts themselves
+// (see "a handful of flexible tokens" below)
+constexpr int kFastMaxTiles = 256;
+constexpr int kFastTiles = 4;
+constexpr int kFastTokens = 8;
+
+__device__ __forceinline__ bool fast_path_applies(int ntiles, int nflex_tiles, int nflex_tok) {
+  return ntiles <= kFastMaxTiles && nflex_tiles > 0 && nflex_tiles <= kFastTiles &&
+         nflex_tok <= kFastTokens;
+}
+
 
 struct ChainBatch {
   int tile[kChainBatch];
@@ -677,6 +687,9 @@ __device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspac
     nflex_tiles += fl;
     nflex_tok += tk;
   }
+  // a handful of flexible tokens: the finishing workgroups resolve them themselves and
+  // write the totals; nothing to do here
+  if (fast_path_applies(ntiles, nflex_tiles, nflex_tok)) return;
   // Without flexible tokens, small problems are finished without tile_base (the
   // finishing workgroups sum the byte counts themselves): only the totals are needed.
   const bool need_tile_base = nflex_tiles > 0 || ntiles > kSelfPrefixTiles;
@@ -858,7 +871,9 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
                             const Workspace& ws, const int32_t* __restrict__ expert_offsets,
                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
                             int32_t* __restrict__ permutation, bool self, const int* own_base,
-                            const int* own_offsets) {
+                            const int* own_offsets, int fast_n = 0,
+                            const unsigned long long* fast_emask = nullptr,
+                            const int* fast_tok = nullptr) {
   const int lane = threadIdx.x & 63;
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
@@ -905,8 +920,14 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
     const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
     const float* pv = ws.rec_p + (size_t)t * 16;
     unsigned long long chosen = 0ull;
-    for (int j = 0; j < cstar; ++j)
-      chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
+    if (fast_n > 0) {
+      // the workgroup resolved the call's few flexible tokens itself (LDS)
+      for (int n = 0; n < fast_n; ++n)
+        if (fast_tok[n] == t) chosen = fast_emask[n];
+    } else {
+      for (int j = 0; j < cstar; ++j)
+        chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
+    }
     float denom = 0.0f;
     if (a.renormalize) {
       bool first = true;
@@ -1016,6 +1037,279 @@ __device__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int
   if (lane == 0) sh_anyflex[wave] = any ? 1 : 0;
 }
 
+// ---- a handful of flexible tokens: every finishing workgroup resolves them itself ----
+//
+// With thresholds like the paper's, a layer of a skewed gate has no or very few
+// flexible tokens.  Waiting for the chain workgroup then costs several dependent
+// memory round trips and two flag hand-overs for one or two chain steps.  Instead,
+// when the call has at most kFastTokens flexible tokens in at most kFastTiles tiles
+// (and at most kFastMaxTiles tiles in all, so that one batch of loads covers every
+// tile's counts), every finishing workgroup sums, beside its own prefix, the fixed
+// assignments before each flexible tile, fetches the few records and walks them with
+// the same step as the sequential chain.  All workgroups compute the same choices;
+// nobody waits for anybody, and the chain workgroup has nothing to do.
+struct FastShared {
+  int wtiles[kChainWaves];                             // per wave: flexible tiles among its 64
+  int ftile[kChainWaves][kFastTiles];                  // their indices, ascending
+  unsigned long long fmask[kChainWaves][kFastTiles];   // and masks
+  int fbefore[kFastTiles][kChainWaves][64];            // per wave: fixed assignments in tiles before
+                                                       // the f-th flexible tile, per expert
+  unsigned long long emask[kFastTokens];               // experts chosen for the n-th flexible token
+  int etok[kFastTokens];                               // its token index
+};
+
+// Finishing workgroup for ntiles <= kFastMaxTiles: tile i's counts are loaded by thread
+// group i/4 (one batch), tile i's flexible mask by thread i.
+__device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Workspace& ws,
+                             int32_t* __restrict__ loads_inout, int32_t* __restrict__ expert_offsets,
+                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
+                             int32_t* __restrict__ permutation) {
+  __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
+  __shared__ int own_base[kChainWaves][64], own_offsets[64];
+  __shared__ FastShared fs;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ntiles = a.ntiles;
+  const int t0 = (blockIdx.x - 1) * kChainWaves;
+  const int tile = t0 + wave;
+  FinishLds* fl = reinterpret_cast<FinishLds*>(tail_lds) + wave;
+
+  // ---- every load this workgroup needs first, in one go ---------------------------
+  FinishPrologue pro;
+  pro.cstar = 0;
+  pro.fm = 0ull;
+  pro.tmask = 0ull;
+  if (tile < ntiles) pro = finish_prologue(tile, a, ws, expert_ids);
+  int wg_cnt[kChainWaves - 1];
+#pragma unroll
+  for (int j = 0; j < kChainWaves - 1; ++j)
+    wg_cnt[j] = (j < wave && t0 + j < ntiles) ? ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane] : 0;
+  const int lin = ws.lin_copy[lane];
+  const unsigned long long fm_mine = (int)threadIdx.x < ntiles ? ws.flexmask[threadIdx.x] : 0ull;
+  const int sub = lane >> 4;  // which of the 4 tiles of a count load
+  const unsigned* cnt32 = reinterpret_cast<const unsigned*>(ws.tile_fixed_cnt);
+  constexpr int kBatch = kFastMaxTiles / (4 * kChainWaves);  // 16 loads cover 256 tiles
+  unsigned wd[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int tl = 4 * (wave + u * kChainWaves) + sub;
+    wd[u] = tl < ntiles ? cnt32[(size_t)tl * 16 + (lane & 15)] : 0u;
+  }
+
+  // ---- the flexible tiles (wave w looks at tiles 64w .. 64w+63) ---------------------
+  {
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(fm_mine != 0ull);
+    const int pos = __builtin_popcountll(bal & lanes_below(lane));
+    if (fm_mine != 0ull && pos < kFastTiles) {
+      fs.ftile[wave][pos] = (int)threadIdx.x;
+      fs.fmask[wave][pos] = fm_mine;
+    }
+    if (lane == 0) fs.wtiles[wave] = __builtin_popcountll(bal);
+  }
+  if (tile < ntiles) finish_commit(fl, pro, a.k);
+  __syncthreads();  // (also waits for every load above)
+  int nft = 0;
+#pragma unroll
+  for (int w = 0; w < kChainWaves; ++w) nft += fs.wtiles[w];
+  nft = __builtin_amdgcn_readfirstlane(nft);
+  // the flexible tiles in ascending order, and the number of flexible tokens
+  int ftile[kFastTiles];
+  unsigned long long fmask[kFastTiles];
+  int ntok = 0;
+#pragma unroll
+  for (int f = 0; f < kFastTiles; ++f) {
+    ftile[f] = 0x7fffffff;
+    fmask[f] = 0ull;
+  }
+  if (nft > 0 && nft <= kFastTiles) {
+    int f = 0;
+#pragma unroll
+    for (int w = 0; w < kChainWaves; ++w) {
+      const int nw = fs.wtiles[w];
+#pragma unroll
+      for (int p_ = 0; p_ < kFastTiles; ++p_) {
+        if (p_ < nw) {
+          const int tl = fs.ftile[w][p_];
+          const unsigned long long m = fs.fmask[w][p_];
+#pragma unroll
+          for (int g = 0; g < kFastTiles; ++g)
+            if (g == f) {
+              ftile[g] = tl;
+              fmask[g] = m;
+            }
+          ntok += __builtin_popcountll(m);
+          ++f;
+        }
+      }
+    }
+  }
+  ntok = __builtin_amdgcn_readfirstlane(ntok);
+  const bool fast = fast_path_applies(ntiles, nft, ntok);
+  const bool self = nft == 0;
+
+  // ---- sums of the fixed tokens' byte counts: all tiles, tiles before this workgroup's,
+  // tiles before each flexible tile ------------------------------------------------
+  unsigned a02 = 0, a13 = 0, b02 = 0, b13 = 0, c02[kFastTiles], c13[kFastTiles];
+#pragma unroll
+  for (int f = 0; f < kFastTiles; ++f) c02[f] = c13[f] = 0u;
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int tl = 4 * (wave + u * kChainWaves) + sub;
+    const unsigned lo = wd[u] & 0x00FF00FFu, hi = (wd[u] >> 8) & 0x00FF00FFu;
+    a02 += lo;
+    a13 += hi;
+    b02 += tl < t0 ? lo : 0u;
+    b13 += tl < t0 ? hi : 0u;
+    if (fast) {
+#pragma unroll
+      for (int f = 0; f < kFastTiles; ++f) {
+        c02[f] += tl < ftile[f] ? lo : 0u;
+        c13[f] += tl < ftile[f] ? hi : 0u;
+      }
+    }
+  }
+#pragma unroll
+  for (int d = 16; d < 64; d <<= 1) {
+    a02 += __shfl_xor(a02, d, 64);
+    a13 += __shfl_xor(a13, d, 64);
+    b02 += __shfl_xor(b02, d, 64);
+    b13 += __shfl_xor(b13, d, 64);
+  }
+  if (fast) {
+#pragma unroll
+    for (int f = 0; f < kFastTiles; ++f)
+#pragma unroll
+      for (int d = 16; d < 64; d <<= 1) {
+        c02[f] += __shfl_xor(c02[f], d, 64);
+        c13[f] += __shfl_xor(c13[f], d, 64);
+      }
+  }
+  if (lane < 16) {
+    const int e = 4 * lane;
+    sh_all[wave][e] = a02 & 0xFFFF;
+    sh_all[wave][e + 1] = a13 & 0xFFFF;
+    sh_all[wave][e + 2] = a02 >> 16;
+    sh_all[wave][e + 3] = a13 >> 16;
+    sh_before[wave][e] = b02 & 0xFFFF;
+    sh_before[wave][e + 1] = b13 & 0xFFFF;
+    sh_before[wave][e + 2] = b02 >> 16;
+    sh_before[wave][e + 3] = b13 >> 16;
+    if (fast) {
+#pragma unroll
+      for (int f = 0; f < kFastTiles; ++f) {
+        fs.fbefore[f][wave][e] = c02[f] & 0xFFFF;
+        fs.fbefore[f][wave][e + 1] = c13[f] & 0xFFFF;
+        fs.fbefore[f][wave][e + 2] = c02[f] >> 16;
+        fs.fbefore[f][wave][e + 3] = c13[f] >> 16;
+      }
+    }
+  }
+  __syncthreads();
+
+  if (!self && !fast) {
+    // many flexible tokens: the chain workgroup publishes what is needed
+    if (tile < ntiles)
+      finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, false,
+                  own_base[wave], own_offsets);
+    return;
+  }
+
+  int before = 0, all = 0;  // lane = expert
+#pragma unroll
+  for (int w = 0; w < kChainWaves; ++w) {
+    before += sh_before[w][lane];
+    all += sh_all[w][lane];
+  }
+#pragma unroll
+  for (int j = 0; j < kChainWaves - 1; ++j) before += wg_cnt[j];
+
+  int flex_before = 0, flex_all = 0;  // flexible choices of this lane's expert
+  if (fast) {
+    if (wave == 0) {
+      // the records first (all loads in flight together), then the walk
+      unsigned rec[kFastTokens];
+      uint4 ids[kFastTokens];
+      int base[kFastTokens], tok[kFastTokens];
+      int n = 0;
+#pragma unroll
+      for (int f = 0; f < kFastTiles; ++f) {
+        int fb = 0;
+#pragma unroll
+        for (int w = 0; w < kChainWaves; ++w) fb += fs.fbefore[f][w][lane];
+        unsigned long long m = fmask[f];
+        int r = 0;
+#pragma unroll
+        for (int i = 0; i < kFastTokens; ++i) {
+          if (m != 0ull) {
+            const int bit = __builtin_ctzll(m);
+            m &= m - 1ull;
+            const int slot = ftile[f] * kTile + r;
+            const unsigned rv = lane < a.EP ? ws.rec_lane[(size_t)slot * a.EP + lane] : 0xFFFFu;
+            const uint4 iv = reinterpret_cast<const uint4*>(ws.rec_cids)[slot];
+#pragma unroll
+            for (int g = 0; g < kFastTokens; ++g)
+              if (g == n) {
+                rec[g] = rv;
+                ids[g] = iv;
+                base[g] = lin + fb;
+                tok[g] = ftile[f] * kTile + bit;
+              }
+            ++r;
+            ++n;
+          }
+        }
+      }
+      int gflex = 0;
+#pragma unroll
+      for (int g = 0; g < kFastTokens; ++g) {
+        if (g < ntok) {
+          const bool cand = lane < a.EP && rec[g] != 0xFFFFu;
+          const unsigned key = cand ? (((unsigned)(base[g] + gflex) << 4) + rec[g]) : 0xFFFFFFFFu;
+          const bool chosen = chain_step<16>(key, cand, ids[g], a.k);
+          gflex += chosen ? 1 : 0;
+          const unsigned long long em = __builtin_amdgcn_ballot_w64(chosen);
+          if (lane == 0) {
+            fs.emask[g] = em;
+            fs.etok[g] = tok[g];
+          }
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < kFastTokens; ++g) {
+      if (g < ntok) {
+        const int bit = (int)((fs.emask[g] >> lane) & 1ull);
+        flex_all += bit;
+        flex_before += (fs.etok[g] < tile * kTile) ? bit : 0;
+      }
+    }
+  }
+
+  own_base[wave][lane] = before + flex_before;
+  const int cnt = lane < a.E ? all + flex_all : 0;
+  if (wave == 0) {
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    own_offsets[lane] = incl - cnt;
+    if (fast && blockIdx.x == 1) {
+      // the chain workgroup leaves such calls alone: the totals are written here
+      if (lane < a.E) {
+        loads_inout[lane] = lin + cnt;
+        expert_offsets[lane] = incl - cnt;
+      }
+      if (lane == a.E - 1) expert_offsets[a.E] = incl;
+    }
+  }
+  __syncthreads();
+  if (tile >= ntiles) return;
+  finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, true,
+              own_base[wave], own_offsets, fast ? ntok : 0, fs.emask, fs.etok);
+}
+
 __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, const Workspace ws,
                                                             int32_t* __restrict__ loads_inout,
                                                             int32_t* __restrict__ expert_offsets,
@@ -1025,6 +1319,10 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   extern __shared__ __align__(16) uint8_t tail_lds[];
   if (blockIdx.x == 0) {
     chain_workgroup(tail_lds, a, ws, loads_inout, expert_offsets);
+    return;
+  }
+  if (a.ntiles <= kFastMaxTiles) {
+    finish_small(tail_lds, a, ws, loads_inout, expert_offsets, expert_ids, weights, permutation);
     return;
   }
   __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];

@@ -247,6 +247,37 @@ def test_random_trimming_full_path_and_split_calls():
     assert np.array_equal(l2.cpu().numpy(), ref["loads"])
 
 
+# A handful of flexible tokens among many fixed ones: the finishing workgroups resolve
+# them without the chain workgroup (at most 8 tokens in at most 4 tiles, at most 256
+# tiles); one more token or tile and the call goes the general way.
+FEW_FLEX = [
+    # T, E, k, c, positions of the flexible tokens
+    (16384, 64, 6, 8, [9500]),
+    (16384, 64, 6, 8, [0]),
+    (16384, 64, 6, 8, [16383]),
+    (16384, 64, 6, 8, [64, 65, 66, 127, 4000, 4001, 9000, 16320]),      # 8 tokens, 4 tiles
+    (16384, 64, 6, 8, [64, 65, 66, 127, 4000, 4001, 9000, 16320, 16321]),  # 9 tokens: general path
+    (16384, 64, 6, 8, [10, 1000, 5000, 9000, 13000]),                   # 5 tiles: general path
+    (3000, 8, 2, 4, [5, 6, 7, 8, 9, 10, 11, 12]),                       # all in one tile, E = 8
+    (3000, 8, 2, 4, [2990, 2999]),                                      # in the ragged last tile
+    (1000, 33, 4, 12, [100, 500, 501, 900]),
+    (200, 16, 3, 16, [0, 63, 64, 199]),
+]
+
+
+@pytest.mark.parametrize("T,E,k,c,where", FEW_FLEX)
+def test_few_flexible_tokens(T, E, k, c, where):
+    u = _util()
+    rng = np.random.default_rng(T + E + len(where))
+    logits = wl.random_logits(T + E, T, E, kind="normal", scale=1.0)
+    hot = rng.integers(0, E, size=T)
+    logits[np.arange(T), hot] += 30.0                    # peaked: the top-k mass test passes
+    logits[where] = wl.random_logits(7, len(where), E, kind="normal", scale=0.01)   # flat
+    loads_in = rng.integers(0, 50, size=E).astype(np.int32)
+    gpu, ref = u.check_from_logits(logits, k, c, 0.9, 0.5, loads_in, label=f"few flex {where}")
+    assert np.array_equal(np.where(ref["cstar"] > k)[0], np.array(sorted(where)))
+
+
 def test_extreme_logits():
     """Scores that underflow the clamp, huge spreads, and all-equal rows."""
     u = _util()
