@@ -214,7 +214,11 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   // the tail kernel of this call polls these words; they are cleared here, one
   // kernel earlier on the same stream
   if (tile == 0 && tid < 4) ws.status[tid] = 0;
-  if (tile == 0 && tid < 64) ws.lin_copy[tid] = tid < a.E ? a.loads_in[tid] : 0;
+  // Tile 0 keeps a copy of the counters before token 0 for the tail kernel (which
+  // overwrites them in place).  Loaded here, stored at the very end: the wait for the
+  // load then costs nothing.
+  const bool lin_copier = tile == 0 && tid < 64;
+  const int lin_before = (lin_copier && tid < a.E) ? a.loads_in[tid] : 0;
 
   constexpr int G = NE < 4 ? NE : 4;      // consecutive experts per run
   constexpr int NG = NE / G;              // runs per lane
@@ -443,6 +447,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       }
     }
   }
+  if (lin_copier) ws.lin_copy[tid] = lin_before;
 }
 
 // NE = padded experts / 8 (1, 2, 4 or 8).

@@ -174,7 +174,7 @@ __device__ __forceinline__ bool poll_flag(const int* flag, int want) {
   return false;
 }
 
-__device__ void chain_prefetch(ChainBatch* dst, int batch, int ft0, int nflex_tiles, const RouteArgs& a,
+__device__ __forceinline__ void chain_prefetch(ChainBatch* dst, int batch, int ft0, int nflex_tiles, const RouteArgs& a,
                                const Workspace& ws, int hwave, int lane) {
   for (int tl = hwave; tl < kChainBatch; tl += kChainWaves - 1) {
     const int f = ft0 + batch * kChainBatch + tl;
@@ -442,7 +442,7 @@ __device__ __forceinline__ unsigned long long rotr64(unsigned long long x, int s
 
 // Producer: tokens seg*192 + half*64 + lane of the call -> ring (half = 0, 1, 2).
 template <int CP>
-__device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, const Workspace& ws,
+__device__ __forceinline__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, const Workspace& ws,
                           const int* lin_tab, int lane) {
   const int f = seg * kSpecSeg + half * 64 + lane;
   if (f >= nflex_tok) return;
@@ -472,7 +472,7 @@ __device__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, c
 // choices so far in `gflex` (lane = expert) and the bits of the unfinished output
 // word in `hist`.  KK = k when known at compile time, else 0.
 template <int CP, int KK>
-__device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
+__device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
                          int wave, int lane, int lin, int& gflex, unsigned& hist) {
   nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
   SpecTok<CP>* ring = reinterpret_cast<SpecTok<CP>*>(lds);
@@ -622,7 +622,7 @@ __device__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const 
   return decided;
 }
 
-__device__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
+__device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
                                 int32_t* __restrict__ loads_inout,
                                 int32_t* __restrict__ expert_offsets) {
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
@@ -867,7 +867,7 @@ __device__ __forceinline__ void finish_commit(FinishLds* fl, const FinishPrologu
 // If `self` is set the caller has already computed, for every expert, the number of
 // assignments in earlier tiles (own_base, LDS, 64 words) and the exclusive prefix over
 // experts of the totals (own_offsets, LDS, 64 words); nothing is awaited then.
-__device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, const RouteArgs& a,
+__device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, const RouteArgs& a,
                             const Workspace& ws, const int32_t* __restrict__ expert_offsets,
                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
                             int32_t* __restrict__ permutation, bool self, const int* own_base,
@@ -977,8 +977,8 @@ __device__ void finish_tile(FinishLds* fl, int tile, const FinishPrologue pro, c
 // when no tile holds a flexible token (then the fixed counts are all there is).
 // Lane l of a load takes experts 4*(l%16)..+3 of tile 4*j + l/16; bytes are
 // accumulated pairwise in 16-bit fields (at most 64 per tile, ntiles <= 1024).
-__device__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int (*sh_before)[64],
-                            int (*sh_all)[64], int* sh_anyflex) {
+__device__ __forceinline__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int (*sh_before)[64],
+                            int (*sh_all)[64], int* sh_anyflex, unsigned long long& fm_first) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
   const int sub = lane >> 4;  // which of the 4 tiles of a load
@@ -1030,6 +1030,7 @@ __device__ void self_prefix(int t0, const RouteArgs& a, const Workspace& ws, int
     sh_before[wave][e + 2] = b02 >> 16;
     sh_before[wave][e + 3] = b13 >> 16;
   }
+  fm_first = fmv[0];  // the mask of tile threadIdx.x
   bool flex = false;
 #pragma unroll
   for (int u = 0; u < kSelfPrefixTiles / kTailThreads; ++u) flex |= fmv[u] != 0ull;
@@ -1058,44 +1059,26 @@ struct FastShared {
   int etok[kFastTokens];                               // its token index
 };
 
-// Finishing workgroup for ntiles <= kFastMaxTiles: tile i's counts are loaded by thread
-// group i/4 (one batch), tile i's flexible mask by thread i.
-__device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Workspace& ws,
-                             int32_t* __restrict__ loads_inout, int32_t* __restrict__ expert_offsets,
-                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
-                             int32_t* __restrict__ permutation) {
-  __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
-  __shared__ int own_base[kChainWaves][64], own_offsets[64];
-  __shared__ FastShared fs;
+// Called by a whole finishing workgroup once it knows that some tile holds flexible
+// tokens (ntiles <= kFastMaxTiles: thread i looked at tile i's flexible mask, fm_mine).
+// Returns 0, having done nothing but look, if there are too many; otherwise the
+// number of flexible tokens, with own_base / own_offsets and the choices (fs.emask,
+// fs.etok) ready for finish_tile.  sh_before / sh_all hold the four waves' partial sums
+// of the fixed counts before this workgroup's tiles / of all tiles.  (Inlined by force,
+// like every helper of this kernel: a real call gives the kernel a stack, and every
+// wave of it a slower start.)
+__device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm_mine,
+                                           const int (&wg_cnt)[kChainWaves - 1], int (*sh_before)[64],
+                                           int (*sh_all)[64], int (*own_base)[64], int* own_offsets,
+                                           const RouteArgs& a, const Workspace& ws,
+                                           int32_t* __restrict__ loads_inout,
+                                           int32_t* __restrict__ expert_offsets) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
   const int t0 = (blockIdx.x - 1) * kChainWaves;
   const int tile = t0 + wave;
-  FinishLds* fl = reinterpret_cast<FinishLds*>(tail_lds) + wave;
 
-  // ---- every load this workgroup needs first, in one go ---------------------------
-  FinishPrologue pro;
-  pro.cstar = 0;
-  pro.fm = 0ull;
-  pro.tmask = 0ull;
-  if (tile < ntiles) pro = finish_prologue(tile, a, ws, expert_ids);
-  int wg_cnt[kChainWaves - 1];
-#pragma unroll
-  for (int j = 0; j < kChainWaves - 1; ++j)
-    wg_cnt[j] = (j < wave && t0 + j < ntiles) ? ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane] : 0;
-  const int lin = ws.lin_copy[lane];
-  const unsigned long long fm_mine = (int)threadIdx.x < ntiles ? ws.flexmask[threadIdx.x] : 0ull;
-  const int sub = lane >> 4;  // which of the 4 tiles of a count load
-  const unsigned* cnt32 = reinterpret_cast<const unsigned*>(ws.tile_fixed_cnt);
-  constexpr int kBatch = kFastMaxTiles / (4 * kChainWaves);  // 16 loads cover 256 tiles
-  unsigned wd[kBatch];
-#pragma unroll
-  for (int u = 0; u < kBatch; ++u) {
-    const int tl = 4 * (wave + u * kChainWaves) + sub;
-    wd[u] = tl < ntiles ? cnt32[(size_t)tl * 16 + (lane & 15)] : 0u;
-  }
-
-  // ---- the flexible tiles (wave w looks at tiles 64w .. 64w+63) ---------------------
+  // ---- the flexible tiles (wave w looked at tiles 64w .. 64w+63) ---------------------
   {
     const unsigned long long bal = __builtin_amdgcn_ballot_w64(fm_mine != 0ull);
     const int pos = __builtin_popcountll(bal & lanes_below(lane));
@@ -1105,22 +1088,22 @@ __device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Worksp
     }
     if (lane == 0) fs.wtiles[wave] = __builtin_popcountll(bal);
   }
-  if (tile < ntiles) finish_commit(fl, pro, a.k);
-  __syncthreads();  // (also waits for every load above)
+  __syncthreads();
   int nft = 0;
 #pragma unroll
   for (int w = 0; w < kChainWaves; ++w) nft += fs.wtiles[w];
   nft = __builtin_amdgcn_readfirstlane(nft);
-  // the flexible tiles in ascending order, and the number of flexible tokens
+  if (nft > kFastTiles) return 0;
+  // in ascending order, with the number of flexible tokens
   int ftile[kFastTiles];
   unsigned long long fmask[kFastTiles];
-  int ntok = 0;
 #pragma unroll
   for (int f = 0; f < kFastTiles; ++f) {
     ftile[f] = 0x7fffffff;
     fmask[f] = 0ull;
   }
-  if (nft > 0 && nft <= kFastTiles) {
+  int ntok = 0;
+  {
     int f = 0;
 #pragma unroll
     for (int w = 0; w < kChainWaves; ++w) {
@@ -1143,77 +1126,124 @@ __device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Worksp
     }
   }
   ntok = __builtin_amdgcn_readfirstlane(ntok);
-  const bool fast = fast_path_applies(ntiles, nft, ntok);
-  const bool self = nft == 0;
+  if (!fast_path_applies(ntiles, nft, ntok)) return 0;
 
-  // ---- sums of the fixed tokens' byte counts: all tiles, tiles before this workgroup's,
-  // tiles before each flexible tile ------------------------------------------------
-  unsigned a02 = 0, a13 = 0, b02 = 0, b13 = 0, c02[kFastTiles], c13[kFastTiles];
+  // ---- loads: every tile's counts once more (one batch), the records of the flexible
+  // tokens (wave 0), the counters before token 0 --------------------------------------
+  const int lin = ws.lin_copy[lane];
+  const int sub = lane >> 4;  // which of the 4 tiles of a count load
+  const unsigned* cnt32 = reinterpret_cast<const unsigned*>(ws.tile_fixed_cnt);
+  constexpr int kBatch = kFastMaxTiles / (4 * kChainWaves);  // 16 loads cover 256 tiles
+  unsigned wd[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const int tl = 4 * (wave + u * kChainWaves) + sub;
+    wd[u] = tl < ntiles ? cnt32[(size_t)tl * 16 + (lane & 15)] : 0u;
+  }
+  unsigned rec[kFastTokens];
+  uint4 ids[kFastTokens];
+  int tok[kFastTokens], tokf[kFastTokens];  // token index, index of its flexible tile
+#pragma unroll
+  for (int g = 0; g < kFastTokens; ++g) {
+    rec[g] = 0xFFFFu;
+    ids[g] = make_uint4(0, 0, 0, 0);
+    tok[g] = 0;
+    tokf[g] = 0;
+  }
+  if (wave == 0) {
+    int n = 0;
+#pragma unroll
+    for (int f = 0; f < kFastTiles; ++f) {
+      unsigned long long m = fmask[f];
+      int r = 0;
+#pragma unroll
+      for (int i = 0; i < kFastTokens; ++i) {
+        if (m != 0ull) {
+          const int bit = __builtin_ctzll(m);
+          m &= m - 1ull;
+          const int slot = ftile[f] * kTile + r;
+          const unsigned rv = lane < a.EP ? ws.rec_lane[(size_t)slot * a.EP + lane] : 0xFFFFu;
+          const uint4 iv = reinterpret_cast<const uint4*>(ws.rec_cids)[slot];
+#pragma unroll
+          for (int g = 0; g < kFastTokens; ++g)
+            if (g == n) {
+              rec[g] = rv;
+              ids[g] = iv;
+              tok[g] = ftile[f] * kTile + bit;
+              tokf[g] = f;
+            }
+          ++r;
+          ++n;
+        }
+      }
+    }
+  }
+
+  // ---- fixed assignments before each flexible tile -----------------------------------
+  unsigned c02[kFastTiles], c13[kFastTiles];
 #pragma unroll
   for (int f = 0; f < kFastTiles; ++f) c02[f] = c13[f] = 0u;
 #pragma unroll
   for (int u = 0; u < kBatch; ++u) {
     const int tl = 4 * (wave + u * kChainWaves) + sub;
     const unsigned lo = wd[u] & 0x00FF00FFu, hi = (wd[u] >> 8) & 0x00FF00FFu;
-    a02 += lo;
-    a13 += hi;
-    b02 += tl < t0 ? lo : 0u;
-    b13 += tl < t0 ? hi : 0u;
-    if (fast) {
 #pragma unroll
-      for (int f = 0; f < kFastTiles; ++f) {
-        c02[f] += tl < ftile[f] ? lo : 0u;
-        c13[f] += tl < ftile[f] ? hi : 0u;
-      }
+    for (int f = 0; f < kFastTiles; ++f) {
+      c02[f] += tl < ftile[f] ? lo : 0u;
+      c13[f] += tl < ftile[f] ? hi : 0u;
     }
   }
 #pragma unroll
-  for (int d = 16; d < 64; d <<= 1) {
-    a02 += __shfl_xor(a02, d, 64);
-    a13 += __shfl_xor(a13, d, 64);
-    b02 += __shfl_xor(b02, d, 64);
-    b13 += __shfl_xor(b13, d, 64);
-  }
-  if (fast) {
+  for (int f = 0; f < kFastTiles; ++f)
 #pragma unroll
-    for (int f = 0; f < kFastTiles; ++f)
-#pragma unroll
-      for (int d = 16; d < 64; d <<= 1) {
-        c02[f] += __shfl_xor(c02[f], d, 64);
-        c13[f] += __shfl_xor(c13[f], d, 64);
-      }
-  }
+    for (int d = 16; d < 64; d <<= 1) {
+      c02[f] += __shfl_xor(c02[f], d, 64);
+      c13[f] += __shfl_xor(c13[f], d, 64);
+    }
   if (lane < 16) {
     const int e = 4 * lane;
-    sh_all[wave][e] = a02 & 0xFFFF;
-    sh_all[wave][e + 1] = a13 & 0xFFFF;
-    sh_all[wave][e + 2] = a02 >> 16;
-    sh_all[wave][e + 3] = a13 >> 16;
-    sh_before[wave][e] = b02 & 0xFFFF;
-    sh_before[wave][e + 1] = b13 & 0xFFFF;
-    sh_before[wave][e + 2] = b02 >> 16;
-    sh_before[wave][e + 3] = b13 >> 16;
-    if (fast) {
 #pragma unroll
-      for (int f = 0; f < kFastTiles; ++f) {
-        fs.fbefore[f][wave][e] = c02[f] & 0xFFFF;
-        fs.fbefore[f][wave][e + 1] = c13[f] & 0xFFFF;
-        fs.fbefore[f][wave][e + 2] = c02[f] >> 16;
-        fs.fbefore[f][wave][e + 3] = c13[f] >> 16;
+    for (int f = 0; f < kFastTiles; ++f) {
+      fs.fbefore[f][wave][e] = c02[f] & 0xFFFF;
+      fs.fbefore[f][wave][e + 1] = c13[f] & 0xFFFF;
+      fs.fbefore[f][wave][e + 2] = c02[f] >> 16;
+      fs.fbefore[f][wave][e + 3] = c13[f] >> 16;
+    }
+  }
+  __syncthreads();
+
+  // ---- wave 0 walks the flexible tokens (lane = expert), as the sequential chain does ----
+  if (wave == 0) {
+    int fb[kFastTiles];
+#pragma unroll
+    for (int f = 0; f < kFastTiles; ++f) {
+      fb[f] = 0;
+#pragma unroll
+      for (int w = 0; w < kChainWaves; ++w) fb[f] += fs.fbefore[f][w][lane];
+    }
+    int gflex = 0;
+#pragma unroll
+    for (int g = 0; g < kFastTokens; ++g) {
+      if (g < ntok) {
+        int base = lin;
+#pragma unroll
+        for (int f = 0; f < kFastTiles; ++f) base += tokf[g] == f ? fb[f] : 0;
+        const bool cand = lane < a.EP && rec[g] != 0xFFFFu;
+        const unsigned key = cand ? (((unsigned)(base + gflex) << 4) + rec[g]) : 0xFFFFFFFFu;
+        const bool chosen = chain_step<16>(key, cand, ids[g], a.k);
+        gflex += chosen ? 1 : 0;
+        const unsigned long long em = __builtin_amdgcn_ballot_w64(chosen);
+        if (lane == 0) {
+          fs.emask[g] = em;
+          fs.etok[g] = tok[g];
+        }
       }
     }
   }
   __syncthreads();
 
-  if (!self && !fast) {
-    // many flexible tokens: the chain workgroup publishes what is needed
-    if (tile < ntiles)
-      finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, false,
-                  own_base[wave], own_offsets);
-    return;
-  }
-
-  int before = 0, all = 0;  // lane = expert
+  // ---- as on the path without flexible tokens, plus the flexible choices ------------
+  int before = 0, all = 0, flex_before = 0, flex_all = 0;  // lane = expert
 #pragma unroll
   for (int w = 0; w < kChainWaves; ++w) {
     before += sh_before[w][lane];
@@ -1221,70 +1251,14 @@ __device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Worksp
   }
 #pragma unroll
   for (int j = 0; j < kChainWaves - 1; ++j) before += wg_cnt[j];
-
-  int flex_before = 0, flex_all = 0;  // flexible choices of this lane's expert
-  if (fast) {
-    if (wave == 0) {
-      // the records first (all loads in flight together), then the walk
-      unsigned rec[kFastTokens];
-      uint4 ids[kFastTokens];
-      int base[kFastTokens], tok[kFastTokens];
-      int n = 0;
 #pragma unroll
-      for (int f = 0; f < kFastTiles; ++f) {
-        int fb = 0;
-#pragma unroll
-        for (int w = 0; w < kChainWaves; ++w) fb += fs.fbefore[f][w][lane];
-        unsigned long long m = fmask[f];
-        int r = 0;
-#pragma unroll
-        for (int i = 0; i < kFastTokens; ++i) {
-          if (m != 0ull) {
-            const int bit = __builtin_ctzll(m);
-            m &= m - 1ull;
-            const int slot = ftile[f] * kTile + r;
-            const unsigned rv = lane < a.EP ? ws.rec_lane[(size_t)slot * a.EP + lane] : 0xFFFFu;
-            const uint4 iv = reinterpret_cast<const uint4*>(ws.rec_cids)[slot];
-#pragma unroll
-            for (int g = 0; g < kFastTokens; ++g)
-              if (g == n) {
-                rec[g] = rv;
-                ids[g] = iv;
-                base[g] = lin + fb;
-                tok[g] = ftile[f] * kTile + bit;
-              }
-            ++r;
-            ++n;
-          }
-        }
-      }
-      int gflex = 0;
-#pragma unroll
-      for (int g = 0; g < kFastTokens; ++g) {
-        if (g < ntok) {
-          const bool cand = lane < a.EP && rec[g] != 0xFFFFu;
-          const unsigned key = cand ? (((unsigned)(base[g] + gflex) << 4) + rec[g]) : 0xFFFFFFFFu;
-          const bool chosen = chain_step<16>(key, cand, ids[g], a.k);
-          gflex += chosen ? 1 : 0;
-          const unsigned long long em = __builtin_amdgcn_ballot_w64(chosen);
-          if (lane == 0) {
-            fs.emask[g] = em;
-            fs.etok[g] = tok[g];
-          }
-        }
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < kFastTokens; ++g) {
-      if (g < ntok) {
-        const int bit = (int)((fs.emask[g] >> lane) & 1ull);
-        flex_all += bit;
-        flex_before += (fs.etok[g] < tile * kTile) ? bit : 0;
-      }
+  for (int g = 0; g < kFastTokens; ++g) {
+    if (g < ntok) {
+      const int bit = (int)((fs.emask[g] >> lane) & 1ull);
+      flex_all += bit;
+      flex_before += (fs.etok[g] < tile * kTile) ? bit : 0;
     }
   }
-
   own_base[wave][lane] = before + flex_before;
   const int cnt = lane < a.E ? all + flex_all : 0;
   if (wave == 0) {
@@ -1295,7 +1269,7 @@ __device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Worksp
       if (lane >= d) incl += up;
     }
     own_offsets[lane] = incl - cnt;
-    if (fast && blockIdx.x == 1) {
+    if (blockIdx.x == 1) {
       // the chain workgroup leaves such calls alone: the totals are written here
       if (lane < a.E) {
         loads_inout[lane] = lin + cnt;
@@ -1305,9 +1279,7 @@ __device__ void finish_small(uint8_t* tail_lds, const RouteArgs& a, const Worksp
     }
   }
   __syncthreads();
-  if (tile >= ntiles) return;
-  finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, true,
-              own_base[wave], own_offsets, fast ? ntok : 0, fs.emask, fs.etok);
+  return ntok;
 }
 
 __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, const Workspace ws,
@@ -1321,13 +1293,10 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
     chain_workgroup(tail_lds, a, ws, loads_inout, expert_offsets);
     return;
   }
-  if (a.ntiles <= kFastMaxTiles) {
-    finish_small(tail_lds, a, ws, loads_inout, expert_offsets, expert_ids, weights, permutation);
-    return;
-  }
   __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
   __shared__ int own_base[kChainWaves][64], own_offsets[64];
   __shared__ int sh_anyflex[kChainWaves];  // per wave: some tile it looked at holds flexible tokens
+  __shared__ FastShared fs;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t0 = (blockIdx.x - 1) * kChainWaves;
   const int tile = t0 + wave;
@@ -1343,13 +1312,15 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   pro.tmask = 0ull;
   if (tile < a.ntiles) pro = finish_prologue(tile, a, ws, expert_ids);
   bool self = false;
+  int fast_n = 0;  // flexible tokens resolved by this workgroup itself
   // fixed counts of the workgroup's earlier tiles (needed by the self path)
   int wg_cnt[kChainWaves - 1];
 #pragma unroll
   for (int j = 0; j < kChainWaves - 1; ++j)
     wg_cnt[j] = (small && j < wave && t0 + j < a.ntiles) ? ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane] : 0;
   if (small) {
-    self_prefix(t0, a, ws, sh_before, sh_all, sh_anyflex);
+    unsigned long long fm_mine = 0ull;
+    self_prefix(t0, a, ws, sh_before, sh_all, sh_anyflex, fm_mine);
     if (tile < a.ntiles) finish_commit(fl, pro, a.k);
     __syncthreads();
     self = (sh_anyflex[0] | sh_anyflex[1] | sh_anyflex[2] | sh_anyflex[3]) == 0;
@@ -1375,12 +1346,18 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
       }
     }
     __syncthreads();
+    // a handful of flexible tokens: resolved here, by every workgroup for itself
+    if (!self && a.ntiles <= kFastMaxTiles) {
+      fast_n = finish_fast(fs, fm_mine, wg_cnt, sh_before, sh_all, own_base, own_offsets, a, ws, loads_inout,
+                           expert_offsets);
+      self = fast_n > 0;
+    }
   } else if (tile < a.ntiles) {
     finish_commit(fl, pro, a.k);
   }
   if (tile >= a.ntiles) return;
   finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, self,
-              own_base[wave], own_offsets);
+              own_base[wave], own_offsets, fast_n, fs.emask, fs.etok);
 }
 
 hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
