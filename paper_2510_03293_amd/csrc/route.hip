@@ -824,6 +824,33 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     __hip_atomic_store(&ws.status[kStatusPhase], 2, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- a handful of flexible tokens: every finishing workgroup resolves them itself ----
+//
+// With thresholds like the paper's, a layer of a skewed gate has no or very few
+// flexible tokens.  Waiting for the chain workgroup then costs several dependent
+// memory round trips and two flag hand-overs for one or two chain steps.  Instead,
+// when the call has at most kFastTokens flexible tokens in at most kFastTiles tiles
+// (and at most kFastMaxTiles tiles in all, so that one batch of loads covers every
+// tile's counts), every finishing workgroup sums, beside its own prefix, the fixed
+// assignments before each flexible tile, fetches the few records and walks them with
+// the same step as the sequential chain.  All workgroups compute the same choices;
+// nobody waits for anybody, and the chain workgroup has nothing to do.
+struct FastShared {
+  unsigned long long bal[kChainWaves];          // wave w: which of tiles 64w .. 64w+63 are flexible
+  unsigned long long fmtile[kFastMaxTiles];     // flexible-token mask of a flexible tile
+  int fbefore[kFastTiles][kChainWaves][64];     // per wave: fixed assignments in the tiles before
+                                                // the f-th flexible tile, per expert
+  // the n-th flexible token of the call:
+  unsigned rec[kFastTokens][64];                // its record row (lane = expert)
+  uint4 cids[kFastTokens];                      // candidate experts by rank, padded
+  uint8_t rids[kFastTokens][kMaxC];             // candidate experts by rank
+  float p[kFastTokens][kMaxC];                  // their probabilities
+  float Z[kFastTokens];                         // the softmax denominator
+  int tok[kFastTokens];                         // token index
+  int tokf[kFastTokens];                        // index of its flexible tile
+  unsigned long long emask[kFastTokens];        // the experts chosen for it
+};
+
 struct FinishLds {
   unsigned long long mask64[64];
   int before[64];  // per expert: slots of all earlier experts + of this expert in earlier tiles
@@ -871,9 +898,7 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
                             const Workspace& ws, const int32_t* __restrict__ expert_offsets,
                             int32_t* __restrict__ expert_ids, float* __restrict__ weights,
                             int32_t* __restrict__ permutation, bool self, const int* own_base,
-                            const int* own_offsets, int fast_n = 0,
-                            const unsigned long long* fast_emask = nullptr,
-                            const int* fast_tok = nullptr) {
+                            const int* own_offsets, int fast_n = 0, const FastShared* fast = nullptr) {
   const int lane = threadIdx.x & 63;
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
@@ -917,38 +942,40 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
   if (cstar > 0) {
     const int f = f0 + __builtin_popcountll(fm & lanes_below(lane));
     const unsigned* cw = ws.chain_bits + (size_t)(f >> 5) * 64;
-    const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
-    const float* pv = ws.rec_p + (size_t)t * 16;
-    unsigned long long chosen = 0ull;
-    if (fast_n > 0) {
-      // the workgroup resolved the call's few flexible tokens itself (LDS)
-      for (int n = 0; n < fast_n; ++n)
-        if (fast_tok[n] == t) chosen = fast_emask[n];
-    } else {
-      for (int j = 0; j < cstar; ++j)
-        chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
-    }
-    float denom = 0.0f;
-    if (a.renormalize) {
-      bool first = true;
-      for (int j = 0; j < cstar; ++j) {
-        if ((chosen >> ids[j]) & 1ull) {
-          denom = first ? pv[j] : denom + pv[j];
-          first = false;
+    // (called twice so that each copy knows its address space: LDS or memory)
+    auto write_row = [&](const uint8_t* ids, const float* pv, float Z, unsigned long long chosen) {
+      float denom = Z;
+      if (a.renormalize) {
+        bool first = true;
+        for (int j = 0; j < cstar; ++j) {
+          if ((chosen >> ids[j]) & 1ull) {
+            denom = first ? pv[j] : denom + pv[j];
+            first = false;
+          }
         }
       }
-    } else {
-      denom = ws.rec_Z[t];
-    }
-    int n = 0;
-    for (int j = 0; j < cstar; ++j) {
-      const int e = ids[j];
-      if (((chosen >> e) & 1ull) && n < k) {  // (exactly k bits are set; n < k keeps the row)
-        expert_ids[(size_t)t * k + n] = e;
-        weights[(size_t)t * k + n] = pv[j] / denom;
-        fl->ids[lane][n] = (uint8_t)e;
-        ++n;
+      int n = 0;
+      for (int j = 0; j < cstar; ++j) {
+        const int e = ids[j];
+        if (((chosen >> e) & 1ull) && n < k) {  // (exactly k bits are set; n < k keeps the row)
+          expert_ids[(size_t)t * k + n] = e;
+          weights[(size_t)t * k + n] = pv[j] / denom;
+          fl->ids[lane][n] = (uint8_t)e;
+          ++n;
+        }
       }
+    };
+    if (fast_n > 0) {
+      // the workgroup resolved the call's few flexible tokens itself: all is in LDS
+      int n = 0;
+      for (int i = 0; i < fast_n; ++i) n = fast->tok[i] == t ? i : n;
+      write_row(fast->rids[n], fast->p[n], fast->Z[n], fast->emask[n]);
+    } else {
+      const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
+      unsigned long long chosen = 0ull;
+      for (int j = 0; j < cstar; ++j)
+        chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
+      write_row(ids, ws.rec_p + (size_t)t * 16, a.renormalize ? 0.0f : ws.rec_Z[t], chosen);
     }
   }
   // LDS traffic of one wavefront is processed in order; the fences only stop the
@@ -1038,42 +1065,23 @@ __device__ __forceinline__ void self_prefix(int t0, const RouteArgs& a, const Wo
   if (lane == 0) sh_anyflex[wave] = any ? 1 : 0;
 }
 
-// ---- a handful of flexible tokens: every finishing workgroup resolves them itself ----
-//
-// With thresholds like the paper's, a layer of a skewed gate has no or very few
-// flexible tokens.  Waiting for the chain workgroup then costs several dependent
-// memory round trips and two flag hand-overs for one or two chain steps.  Instead,
-// when the call has at most kFastTokens flexible tokens in at most kFastTiles tiles
-// (and at most kFastMaxTiles tiles in all, so that one batch of loads covers every
-// tile's counts), every finishing workgroup sums, beside its own prefix, the fixed
-// assignments before each flexible tile, fetches the few records and walks them with
-// the same step as the sequential chain.  All workgroups compute the same choices;
-// nobody waits for anybody, and the chain workgroup has nothing to do.
-struct FastShared {
-  int wtiles[kChainWaves];                             // per wave: flexible tiles among its 64
-  int ftile[kChainWaves][kFastTiles];                  // their indices, ascending
-  unsigned long long fmask[kChainWaves][kFastTiles];   // and masks
-  int fbefore[kFastTiles][kChainWaves][64];            // per wave: fixed assignments in tiles before
-                                                       // the f-th flexible tile, per expert
-  unsigned long long emask[kFastTokens];               // experts chosen for the n-th flexible token
-  int etok[kFastTokens];                               // its token index
-};
-
 // Called by a whole finishing workgroup once it knows that some tile holds flexible
 // tokens (ntiles <= kFastMaxTiles: thread i looked at tile i's flexible mask, fm_mine).
 // Returns 0, having done nothing but look, if there are too many; otherwise the
 // number of flexible tokens, with own_base / own_offsets and the choices (fs.emask,
-// fs.etok) ready for finish_tile.  sh_before / sh_all hold the four waves' partial sums
-// of the fixed counts before this workgroup's tiles / of all tiles.  (Inlined by force,
-// like every helper of this kernel: a real call gives the kernel a stack, and every
-// wave of it a slower start.)
+// fs.tok) ready for finish_tile.  sh_before / sh_all hold the four waves' partial sums
+// of the fixed counts before this workgroup's tiles / of all tiles.  A lone wavefront
+// issues an instruction every few cycles only, so the point here is few instructions:
+// per-token state lives in LDS and the loops over tokens are not unrolled.  (Inlined
+// by force, like every helper of this kernel: a real call gives the kernel a stack,
+// and every wave of it a slower start.)
 __device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm_mine,
                                            const int (&wg_cnt)[kChainWaves - 1], int (*sh_before)[64],
                                            int (*sh_all)[64], int (*own_base)[64], int* own_offsets,
                                            const RouteArgs& a, const Workspace& ws,
                                            int32_t* __restrict__ loads_inout,
                                            int32_t* __restrict__ expert_offsets) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
   const int t0 = (blockIdx.x - 1) * kChainWaves;
   const int tile = t0 + wave;
@@ -1081,55 +1089,101 @@ __device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm
   // ---- the flexible tiles (wave w looked at tiles 64w .. 64w+63) ---------------------
   {
     const unsigned long long bal = __builtin_amdgcn_ballot_w64(fm_mine != 0ull);
-    const int pos = __builtin_popcountll(bal & lanes_below(lane));
-    if (fm_mine != 0ull && pos < kFastTiles) {
-      fs.ftile[wave][pos] = (int)threadIdx.x;
-      fs.fmask[wave][pos] = fm_mine;
-    }
-    if (lane == 0) fs.wtiles[wave] = __builtin_popcountll(bal);
+    if (fm_mine != 0ull) fs.fmtile[threadIdx.x] = fm_mine;
+    if (lane == 0) fs.bal[wave] = bal;
   }
   __syncthreads();
+  unsigned long long bal[kChainWaves];
   int nft = 0;
 #pragma unroll
-  for (int w = 0; w < kChainWaves; ++w) nft += fs.wtiles[w];
-  nft = __builtin_amdgcn_readfirstlane(nft);
+  for (int w = 0; w < kChainWaves; ++w) {
+    const unsigned long long b = fs.bal[w];
+    bal[w] = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(b >> 32)) << 32) |
+             (unsigned)__builtin_amdgcn_readfirstlane((unsigned)b);
+    nft += __builtin_popcountll(bal[w]);
+  }
   if (nft > kFastTiles) return 0;
-  // in ascending order, with the number of flexible tokens
+  // in ascending order, with their masks and the number of flexible tokens
   int ftile[kFastTiles];
   unsigned long long fmask[kFastTiles];
+  int ntok = 0;
 #pragma unroll
   for (int f = 0; f < kFastTiles; ++f) {
     ftile[f] = 0x7fffffff;
     fmask[f] = 0ull;
-  }
-  int ntok = 0;
-  {
-    int f = 0;
+    if (f < nft) {
+      int tl = 0;
+      bool found = false;
 #pragma unroll
-    for (int w = 0; w < kChainWaves; ++w) {
-      const int nw = fs.wtiles[w];
-#pragma unroll
-      for (int p_ = 0; p_ < kFastTiles; ++p_) {
-        if (p_ < nw) {
-          const int tl = fs.ftile[w][p_];
-          const unsigned long long m = fs.fmask[w][p_];
-#pragma unroll
-          for (int g = 0; g < kFastTiles; ++g)
-            if (g == f) {
-              ftile[g] = tl;
-              fmask[g] = m;
-            }
-          ntok += __builtin_popcountll(m);
-          ++f;
+      for (int w = 0; w < kChainWaves; ++w) {
+        if (!found && bal[w] != 0ull) {
+          tl = 64 * w + __builtin_ctzll(bal[w]);
+          bal[w] &= bal[w] - 1ull;
+          found = true;
         }
       }
+      ftile[f] = tl;
+      const unsigned long long m = fs.fmtile[tl];
+      fmask[f] = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(m >> 32)) << 32) |
+                 (unsigned)__builtin_amdgcn_readfirstlane((unsigned)m);
+      ntok += __builtin_popcountll(fmask[f]);
     }
   }
-  ntok = __builtin_amdgcn_readfirstlane(ntok);
   if (!fast_path_applies(ntiles, nft, ntok)) return 0;
 
-  // ---- loads: every tile's counts once more (one batch), the records of the flexible
-  // tokens (wave 0), the counters before token 0 --------------------------------------
+  // ---- lane n < ntok: the n-th flexible token of the call ---------------------------
+  int my_tok = 0, my_slot = 0, my_f = 0;
+  {
+    int r = lane;
+#pragma unroll
+    for (int f = 0; f < kFastTiles - 1; ++f) {
+      const int pc = __builtin_popcountll(fmask[f]);
+      if (my_f == f && r >= pc) {
+        r -= pc;
+        my_f = f + 1;
+      }
+    }
+    unsigned long long m = fmask[0];
+    int tl = ftile[0];
+#pragma unroll
+    for (int f = 1; f < kFastTiles; ++f) {
+      m = my_f == f ? fmask[f] : m;
+      tl = my_f == f ? ftile[f] : tl;
+    }
+    if (lane < ntok) {
+      for (int i = 0; i < r; ++i) m &= m - 1ull;  // (r < kFastTokens)
+      my_tok = tl * kTile + __builtin_ctzll(m);
+      my_slot = tl * kTile + r;
+    }
+  }
+
+  // ---- loads: wave w fetches what belongs to tokens w and w + 4; every wave the
+  // tiles' counts once more (one batch; they are near, having just been read) ----------
+  static_assert(kFastTokens <= 2 * kChainWaves, "two tokens per wave");
+  static_assert(kFastMaxTiles == kTailThreads, "thread i looks at tile i");
+  unsigned rv[2];
+  float pv[2];
+  int tk[2], tf[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int n = wave + h * kChainWaves;
+    rv[h] = 0xFFFFu;
+    pv[h] = 0.0f;
+    tk[h] = tf[h] = 0;
+    if (n < ntok) {
+      const int slot = __builtin_amdgcn_readlane(my_slot, n);
+      tk[h] = __builtin_amdgcn_readlane(my_tok, n);
+      tf[h] = __builtin_amdgcn_readlane(my_f, n);
+      // lanes 0..EP-1: the record row; then 4 lanes each for the two id rows, 16 for the
+      // probabilities, one for the denominator -- as bits, sorted out after the wait
+      if (lane < a.EP) rv[h] = ws.rec_lane[(size_t)slot * a.EP + lane];
+      const unsigned* extra = lane < 4    ? reinterpret_cast<const unsigned*>(ws.rec_cids) + (size_t)slot * 4 + lane
+                              : lane < 8  ? reinterpret_cast<const unsigned*>(ws.rec_ids) + (size_t)tk[h] * 4 + (lane - 4)
+                              : lane < 24 ? reinterpret_cast<const unsigned*>(ws.rec_p) + (size_t)tk[h] * 16 + (lane - 8)
+                                          : reinterpret_cast<const unsigned*>(ws.rec_Z) + tk[h];
+      if (lane < 25) pv[h] = __uint_as_float(*extra);
+    }
+  }
   const int lin = ws.lin_copy[lane];
   const int sub = lane >> 4;  // which of the 4 tiles of a count load
   const unsigned* cnt32 = reinterpret_cast<const unsigned*>(ws.tile_fixed_cnt);
@@ -1140,104 +1194,65 @@ __device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm
     const int tl = 4 * (wave + u * kChainWaves) + sub;
     wd[u] = tl < ntiles ? cnt32[(size_t)tl * 16 + (lane & 15)] : 0u;
   }
-  unsigned rec[kFastTokens];
-  uint4 ids[kFastTokens];
-  int tok[kFastTokens], tokf[kFastTokens];  // token index, index of its flexible tile
 #pragma unroll
-  for (int g = 0; g < kFastTokens; ++g) {
-    rec[g] = 0xFFFFu;
-    ids[g] = make_uint4(0, 0, 0, 0);
-    tok[g] = 0;
-    tokf[g] = 0;
-  }
-  if (wave == 0) {
-    int n = 0;
-#pragma unroll
-    for (int f = 0; f < kFastTiles; ++f) {
-      unsigned long long m = fmask[f];
-      int r = 0;
-#pragma unroll
-      for (int i = 0; i < kFastTokens; ++i) {
-        if (m != 0ull) {
-          const int bit = __builtin_ctzll(m);
-          m &= m - 1ull;
-          const int slot = ftile[f] * kTile + r;
-          const unsigned rv = lane < a.EP ? ws.rec_lane[(size_t)slot * a.EP + lane] : 0xFFFFu;
-          const uint4 iv = reinterpret_cast<const uint4*>(ws.rec_cids)[slot];
-#pragma unroll
-          for (int g = 0; g < kFastTokens; ++g)
-            if (g == n) {
-              rec[g] = rv;
-              ids[g] = iv;
-              tok[g] = ftile[f] * kTile + bit;
-              tokf[g] = f;
-            }
-          ++r;
-          ++n;
-        }
+  for (int h = 0; h < 2; ++h) {
+    const int n = wave + h * kChainWaves;
+    if (n < ntok) {
+      fs.rec[n][lane] = rv[h];
+      const unsigned bits = __float_as_uint(pv[h]);
+      if (lane < 4) reinterpret_cast<unsigned*>(&fs.cids[n])[lane] = bits;
+      else if (lane < 8) reinterpret_cast<unsigned*>(fs.rids[n])[lane - 4] = bits;
+      else if (lane < 24) fs.p[n][lane - 8] = pv[h];
+      else if (lane == 24) fs.Z[n] = pv[h];
+      if (lane == 0) {
+        fs.tok[n] = tk[h];
+        fs.tokf[n] = tf[h];
       }
     }
   }
 
   // ---- fixed assignments before each flexible tile -----------------------------------
-  unsigned c02[kFastTiles], c13[kFastTiles];
 #pragma unroll
-  for (int f = 0; f < kFastTiles; ++f) c02[f] = c13[f] = 0u;
+  for (int f = 0; f < kFastTiles; ++f) {
+    if (f < nft) {
+      unsigned c02 = 0u, c13 = 0u;
 #pragma unroll
-  for (int u = 0; u < kBatch; ++u) {
-    const int tl = 4 * (wave + u * kChainWaves) + sub;
-    const unsigned lo = wd[u] & 0x00FF00FFu, hi = (wd[u] >> 8) & 0x00FF00FFu;
+      for (int u = 0; u < kBatch; ++u) {
+        const int tl = 4 * (wave + u * kChainWaves) + sub;
+        c02 += tl < ftile[f] ? (wd[u] & 0x00FF00FFu) : 0u;
+        c13 += tl < ftile[f] ? ((wd[u] >> 8) & 0x00FF00FFu) : 0u;
+      }
 #pragma unroll
-    for (int f = 0; f < kFastTiles; ++f) {
-      c02[f] += tl < ftile[f] ? lo : 0u;
-      c13[f] += tl < ftile[f] ? hi : 0u;
-    }
-  }
-#pragma unroll
-  for (int f = 0; f < kFastTiles; ++f)
-#pragma unroll
-    for (int d = 16; d < 64; d <<= 1) {
-      c02[f] += __shfl_xor(c02[f], d, 64);
-      c13[f] += __shfl_xor(c13[f], d, 64);
-    }
-  if (lane < 16) {
-    const int e = 4 * lane;
-#pragma unroll
-    for (int f = 0; f < kFastTiles; ++f) {
-      fs.fbefore[f][wave][e] = c02[f] & 0xFFFF;
-      fs.fbefore[f][wave][e + 1] = c13[f] & 0xFFFF;
-      fs.fbefore[f][wave][e + 2] = c02[f] >> 16;
-      fs.fbefore[f][wave][e + 3] = c13[f] >> 16;
+      for (int d = 16; d < 64; d <<= 1) {
+        c02 += __shfl_xor(c02, d, 64);
+        c13 += __shfl_xor(c13, d, 64);
+      }
+      if (lane < 16) {
+        const int e = 4 * lane;
+        fs.fbefore[f][wave][e] = c02 & 0xFFFF;
+        fs.fbefore[f][wave][e + 1] = c13 & 0xFFFF;
+        fs.fbefore[f][wave][e + 2] = c02 >> 16;
+        fs.fbefore[f][wave][e + 3] = c13 >> 16;
+      }
     }
   }
   __syncthreads();
 
   // ---- wave 0 walks the flexible tokens (lane = expert), as the sequential chain does ----
   if (wave == 0) {
-    int fb[kFastTiles];
-#pragma unroll
-    for (int f = 0; f < kFastTiles; ++f) {
-      fb[f] = 0;
-#pragma unroll
-      for (int w = 0; w < kChainWaves; ++w) fb[f] += fs.fbefore[f][w][lane];
-    }
     int gflex = 0;
+    for (int n = 0; n < ntok; ++n) {
+      const int f = __builtin_amdgcn_readfirstlane(fs.tokf[n]);
+      int base = lin + gflex;
 #pragma unroll
-    for (int g = 0; g < kFastTokens; ++g) {
-      if (g < ntok) {
-        int base = lin;
-#pragma unroll
-        for (int f = 0; f < kFastTiles; ++f) base += tokf[g] == f ? fb[f] : 0;
-        const bool cand = lane < a.EP && rec[g] != 0xFFFFu;
-        const unsigned key = cand ? (((unsigned)(base + gflex) << 4) + rec[g]) : 0xFFFFFFFFu;
-        const bool chosen = chain_step<16>(key, cand, ids[g], a.k);
-        gflex += chosen ? 1 : 0;
-        const unsigned long long em = __builtin_amdgcn_ballot_w64(chosen);
-        if (lane == 0) {
-          fs.emask[g] = em;
-          fs.etok[g] = tok[g];
-        }
-      }
+      for (int w = 0; w < kChainWaves; ++w) base += fs.fbefore[f][w][lane];
+      const unsigned rec = fs.rec[n][lane];
+      const bool cand = lane < a.EP && rec != 0xFFFFu;
+      const unsigned key = cand ? (((unsigned)base << 4) + rec) : 0xFFFFFFFFu;
+      const bool chosen = chain_step<16>(key, cand, fs.cids[n], a.k);
+      gflex += chosen ? 1 : 0;
+      const unsigned long long em = __builtin_amdgcn_ballot_w64(chosen);
+      if (lane == 0) fs.emask[n] = em;
     }
   }
   __syncthreads();
@@ -1251,13 +1266,10 @@ __device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm
   }
 #pragma unroll
   for (int j = 0; j < kChainWaves - 1; ++j) before += wg_cnt[j];
-#pragma unroll
-  for (int g = 0; g < kFastTokens; ++g) {
-    if (g < ntok) {
-      const int bit = (int)((fs.emask[g] >> lane) & 1ull);
-      flex_all += bit;
-      flex_before += (fs.etok[g] < tile * kTile) ? bit : 0;
-    }
+  for (int n = 0; n < ntok; ++n) {
+    const int bit = (int)((fs.emask[n] >> lane) & 1ull);
+    flex_all += bit;
+    flex_before += (fs.tok[n] < tile * kTile) ? bit : 0;
   }
   own_base[wave][lane] = before + flex_before;
   const int cnt = lane < a.E ? all + flex_all : 0;
@@ -1357,7 +1369,7 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
   }
   if (tile >= a.ntiles) return;
   finish_tile(fl, tile, pro, a, ws, expert_offsets, expert_ids, weights, permutation, self,
-              own_base[wave], own_offsets, fast_n, fs.emask, fs.etok);
+              own_base[wave], own_offsets, fast_n, &fs);
 }
 
 hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
