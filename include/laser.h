@@ -109,6 +109,27 @@ int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, in
                 void* hip_stream);
 
 /*
+ * B independent routing problems of one size in one call: the layers (or layer x
+ * micro-batch pairs) whose inputs are all at hand.  Algorithm 1 orders the tokens of
+ * ONE layer's batch (its counters start at that layer's loads); different layers and
+ * batches share nothing, so their chains run side by side, one workgroup each, and the
+ * projections share one launch.  Every array is that of laser_route with a leading
+ * dimension B, problems stored back to back:
+ *   hidden [B,T,H], w_gate [B,E,H], loads_inout [B,E], expert_ids and weights [B,T,k],
+ *   permutation [B,T*k] (slot numbers t*k+j local to the problem), expert_offsets
+ *   [B,E+1], logits_out [B,T,E] or NULL,
+ *   workspace >= B * laser_workspace_bytes(T,H,E,params) bytes, 256-byte aligned.
+ * Each problem's result is exactly laser_route's on its slices.  With
+ * LASER_TRIM_RANDOM problem b draws with stream id params->stream + b.
+ * 0 <= B <= 65535; B = 0 does nothing.
+ */
+int laser_route_batched(const void* hidden, const void* w_gate, int32_t B, int32_t T, int32_t H,
+                        int32_t E, const laser_params_t* params, int32_t* loads_inout,
+                        int32_t* expert_ids, float* weights, int32_t* permutation,
+                        int32_t* expert_offsets, float* logits_out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/*
  * The same step starting after the gate function, from given fp32 logits [T,E]
  * (Algorithm 1's input is the score vector; scores are softmax(logits)).
  * params->dtype is ignored.

@@ -19,7 +19,7 @@ DTYPE_BF16 = 1
 TRIM_TOP = 0
 TRIM_RANDOM = 1
 
-EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_stats", "laser_route_from_logits", "laser_imbalance",
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance",
            "laser_strerror", "laser_profile_enable", "laser_profile_read",
            "laser_profile_event_overhead", "laser_profile_plain_read")
 
@@ -59,6 +59,8 @@ def _load() -> ctypes.CDLL:
     lib.laser_workspace_bytes.restype = sz
     lib.laser_route.argtypes = [vp, vp, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.laser_route.restype = ctypes.c_int
+    lib.laser_route_batched.argtypes = [vp, vp, i32, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.laser_route_batched.restype = ctypes.c_int
     lib.laser_route_stats.argtypes = [vp, vp, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                       vp, sz, vp]
     lib.laser_route_stats.restype = ctypes.c_int
@@ -119,6 +121,17 @@ def laser_route(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weight
                             _ptr(loads_inout), _ptr(expert_ids), _ptr(weights), _ptr(permutation),
                             _ptr(expert_offsets), _ptr(logits_out), _ptr(workspace),
                             workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def laser_route_batched(hidden, w_gate, B, T, H, E, params, loads_inout, expert_ids, weights,
+                        permutation, expert_offsets, logits_out, workspace, stream=None) -> None:
+    """B independent problems of one size in one call; every tensor has a leading dimension B."""
+    _check(_lib.laser_route_batched(_ptr(hidden), _ptr(w_gate), B, T, H, E, ctypes.byref(params),
+                                    _ptr(loads_inout), _ptr(expert_ids), _ptr(weights),
+                                    _ptr(permutation), _ptr(expert_offsets), _ptr(logits_out),
+                                    _ptr(workspace),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                    _stream_handle(stream)))
 
 
 def laser_route_stats(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights,

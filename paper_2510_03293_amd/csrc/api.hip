@@ -139,6 +139,8 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.st_mass = nullptr;
   a.st_entropy = nullptr;
   a.st_pool = nullptr;
+  a.nbatch = 1;
+  a.ws_stride = 0;
   return a;
 }
 
@@ -169,13 +171,16 @@ size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params
   return workspace_bytes(T, E, true);
 }
 
-static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+// B problems of one size, every array of problem b right behind that of problem b - 1.
+static int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int32_t H, int32_t E,
                       const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
                       float* weights, int32_t* permutation, int32_t* expert_offsets,
                       float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
                       void* workspace, size_t workspace_bytes_given, void* hip_stream) {
   int rc = check_params(T, E, params);
   if (rc != LASER_OK) return rc;
+  if (B < 0 || B > 65535) return LASER_E_RANGE;  // (the problem index is a grid dimension)
+  if (B == 0) return LASER_OK;
   if (!w_gate || !loads_inout || !expert_offsets || !workspace) return LASER_E_NULL;
   if (T > 0 && (!hidden || !expert_ids || !weights || !permutation)) return LASER_E_NULL;
   if (H < 1) return LASER_E_RANGE;
@@ -187,10 +192,13 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t
   }
   if ((uintptr_t)workspace & 255) return LASER_E_ALIGN;
   const bool need_logits = true;  // the layout always reserves the logits block
-  if (workspace_bytes_given < workspace_bytes(T, E, need_logits)) return LASER_E_WORKSPACE;
+  const size_t ws_one = workspace_bytes(T, E, need_logits);  // a multiple of 256
+  if (workspace_bytes_given / (size_t)B < ws_one) return LASER_E_WORKSPACE;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   RouteArgs a = make_args(T, E, params);
+  a.nbatch = B;
+  a.ws_stride = ws_one;
   a.loads_in = loads_inout;
   a.st_mass = topk_mass;
   a.st_entropy = entropy;
@@ -203,20 +211,24 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t T, int32_t
     // gate projection and per-token analysis in one kernel; RANDOM trimming takes the
     // logits from it and analyses again with its own kernel (that mode is not tuned)
     float* logits = random ? (logits_out ? logits_out : ws.logits) : logits_out;
-    if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits, s) != hipSuccess)
+    const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);
+    if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits, lstride, s) !=
+        hipSuccess)
       return LASER_E_LAUNCH;
-    if (random && launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) !=
-                      hipSuccess)
+    if (random && launch_analyse_random(logits, lstride, a, ws, make_random(params), expert_ids, weights,
+                                        s) != hipSuccess)
       return LASER_E_LAUNCH;
   } else {
     float* logits = logits_out ? logits_out : ws.logits;
-    if (launch_gate_f32(static_cast<const float*>(hidden), static_cast<const float*>(w_gate), T, H, E,
-                        logits, s) != hipSuccess)
+    const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);
+    if (launch_gate_f32(static_cast<const float*>(hidden), static_cast<const float*>(w_gate), T, H, E, B,
+                        logits, lstride, s) != hipSuccess)
       return LASER_E_LAUNCH;
     if (random) {
-      if (launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
+      if (launch_analyse_random(logits, lstride, a, ws, make_random(params), expert_ids, weights, s) !=
+          hipSuccess)
         return LASER_E_LAUNCH;
-    } else if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) {
+    } else if (launch_analyse(logits, lstride, a, ws, expert_ids, weights, s) != hipSuccess) {
       return LASER_E_LAUNCH;
     }
   }
@@ -232,7 +244,17 @@ int laser_route(const void* hidden, const void* w_gate, int32_t T, int32_t H, in
                 float* weights, int32_t* permutation, int32_t* expert_offsets,
                 float* logits_out, void* workspace, size_t workspace_bytes_given,
                 void* hip_stream) {
-  return route_impl(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+  return route_impl(hidden, w_gate, 1, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+                    expert_offsets, logits_out, nullptr, nullptr, nullptr, workspace,
+                    workspace_bytes_given, hip_stream);
+}
+
+int laser_route_batched(const void* hidden, const void* w_gate, int32_t B, int32_t T, int32_t H,
+                        int32_t E, const laser_params_t* params, int32_t* loads_inout,
+                        int32_t* expert_ids, float* weights, int32_t* permutation,
+                        int32_t* expert_offsets, float* logits_out, void* workspace,
+                        size_t workspace_bytes_given, void* hip_stream) {
+  return route_impl(hidden, w_gate, B, T, H, E, params, loads_inout, expert_ids, weights, permutation,
                     expert_offsets, logits_out, nullptr, nullptr, nullptr, workspace,
                     workspace_bytes_given, hip_stream);
 }
@@ -242,7 +264,7 @@ int laser_route_stats(const void* hidden, const void* w_gate, int32_t T, int32_t
                       float* weights, int32_t* permutation, int32_t* expert_offsets,
                       float* logits_out, float* topk_mass, float* entropy, int32_t* pool_size,
                       void* workspace, size_t workspace_bytes_given, void* hip_stream) {
-  return route_impl(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+  return route_impl(hidden, w_gate, 1, T, H, E, params, loads_inout, expert_ids, weights, permutation,
                     expert_offsets, logits_out, topk_mass, entropy, pool_size, workspace,
                     workspace_bytes_given, hip_stream);
 }
@@ -263,9 +285,9 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
   const Workspace ws = carve_workspace(workspace, T, E, true);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (params->trim_mode == LASER_TRIM_RANDOM) {
-    if (launch_analyse_random(logits, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
+    if (launch_analyse_random(logits, 0, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
       return LASER_E_LAUNCH;
-  } else if (launch_analyse(logits, a, ws, expert_ids, weights, s) != hipSuccess) {
+  } else if (launch_analyse(logits, 0, a, ws, expert_ids, weights, s) != hipSuccess) {
     return LASER_E_LAUNCH;
   }
   return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
@@ -275,7 +297,7 @@ const char* laser_strerror(int code) {
   switch (code) {
     case LASER_OK: return "ok";
     case LASER_E_NULL: return "a required pointer is NULL";
-    case LASER_E_RANGE: return "argument out of range (T, H, E, k, c, eps_high, t_fix or dtype)";
+    case LASER_E_RANGE: return "argument out of range (B, T, H, E, k, c, eps_high, t_fix or dtype)";
     case LASER_E_ALIGN: return "unsupported row length or pointer alignment";
     case LASER_E_WORKSPACE: return "workspace too small";
     case LASER_E_UNSUPPORTED: return "not built: E > 64 or c > 16";

@@ -87,15 +87,26 @@ __device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
 // lane of the per-token analysis that follows in the same kernel (padded E / 8).
 // NM: chunks per wave when H == 512 * NM (the main loop is then written out with
 // deeper prefetch), 0 for any other H.  STATS: the analysis also writes the per-token
-// statistics.
-template <int EB, int NE, int NM, bool STATS>
+// statistics.  BATCH: blockIdx.y is the problem of a batched call (a kernel of its own:
+// the longer prologue would delay the first loads of the single-problem kernel).
+template <int EB, int NE, int NM, bool STATS, bool BATCH>
 __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
-    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a,
-    const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
-    float* __restrict__ logits_out) {
+    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a0,
+    const Workspace ws0, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
+    float* __restrict__ logits_out, size_t logits_stride) {
   extern __shared__ __align__(16) unsigned char gate_lds[];
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
+  const int prob = BATCH ? blockIdx.y : 0;
+  const RouteArgs a = BATCH ? problem_args(a0, prob) : a0;
+  const Workspace ws = BATCH ? problem_workspace(ws0, (size_t)prob * a0.ws_stride) : ws0;
+  if (BATCH) {
+    hidden += (size_t)prob * a.T * H;
+    w += (size_t)prob * a.E * H;
+    expert_ids += (size_t)prob * a.T * a.k;
+    weights += (size_t)prob * a.T * a.k;
+    logits_out = logits_out != nullptr ? logits_out + (size_t)prob * logits_stride : nullptr;
+  }
   const int T = a.T, E = a.E;
   const int tile = blockIdx.x;
   const int wave = threadIdx.x >> 6;
@@ -130,7 +141,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
   unsigned char* st_wr = strip + lrow * kRowBytes + lpiece * 16;
   unsigned char* st_rd = strip + (lane & 15) * kRowBytes + (lane >> 4) * 16;
 
-  const int nfull = H >> 6;
+  const int nfull = NM > 0 ? 8 * NM : H >> 6;  // (a constant when the loop is written out: no division below)
   const int nmine = (nfull - wave_u + kGateWaves - 1) / kGateWaves;  // chunks wave, wave+8, ...
   // Every tile starts its walk over the contraction axis at a different chunk, so
   // that the workgroups running at the same time do not all read the same column
@@ -227,43 +238,54 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
                                       weights, logits_out);
 }
 
-template <int EB, int NE, int NM, bool STATS>
-static hipError_t launch_nm(const void* hidden, const void* w, int H, const RouteArgs& a,
+template <int EB, int NE, int NM, bool STATS, bool BATCH>
+static hipError_t launch_nmb(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
-                             float* logits_out, hipStream_t s) {
+                             float* logits_out, size_t logits_stride, hipStream_t s) {
   static bool attr_set = false;
-  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM, STATS>);
+  const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM, STATS>), dim3(a.ntiles), dim3(kGateThreads), kGateLdsBytes, s,
+  hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>), dim3(a.ntiles, a.nbatch), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
-                     expert_ids, weights, logits_out);
+                     expert_ids, weights, logits_out, logits_stride);
   return hipGetLastError();
+}
+
+template <int EB, int NE, int NM, bool STATS>
+static hipError_t launch_nm(const void* hidden, const void* w, int H, const RouteArgs& a,
+                            const Workspace& ws, int32_t* expert_ids, float* weights,
+                            float* logits_out, size_t logits_stride, hipStream_t s) {
+  if (a.nbatch > 1)
+    return launch_nmb<EB, NE, NM, STATS, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out,
+                                               logits_stride, s);
+  return launch_nmb<EB, NE, NM, STATS, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out,
+                                              logits_stride, s);
 }
 
 template <int EB, int NE>
 static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
-                             float* logits_out, hipStream_t s) {
+                             float* logits_out, size_t logits_stride, hipStream_t s) {
   // (the statistics variant exists for the general loop only)
-  if (wants_stats(a)) return launch_nm<EB, NE, 0, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  if (H == 2048) return launch_nm<EB, NE, 4, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  if (H == 4096) return launch_nm<EB, NE, 8, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  return launch_nm<EB, NE, 0, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  if (wants_stats(a)) return launch_nm<EB, NE, 0, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+  if (H == 2048) return launch_nm<EB, NE, 4, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+  if (H == 4096) return launch_nm<EB, NE, 8, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+  return launch_nm<EB, NE, 0, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
 }
 
 hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
                                     const Workspace& ws, int32_t* expert_ids, float* weights,
-                                    float* logits_out, hipStream_t s) {
+                                    float* logits_out, size_t logits_stride, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
   switch (a.EP) {
-    case 8: return launch_one<1, 1>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    case 16: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    case 32: return launch_one<2, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-    default: return launch_one<4, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    case 8: return launch_one<1, 1>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+    case 16: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+    case 32: return launch_one<2, 4>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+    default: return launch_one<4, 8>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
   }
 }
 
@@ -271,7 +293,11 @@ hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, co
 // multiply-add accumulation in h order.  Meant for small fp32 problems.
 __global__ __launch_bounds__(256) void gate_f32_kernel(const float* __restrict__ hidden,
                                                        const float* __restrict__ w, int T, int H,
-                                                       int E, float* __restrict__ logits) {
+                                                       int E, float* __restrict__ logits,
+                                                       size_t logits_stride) {
+  hidden += (size_t)blockIdx.y * T * H;
+  w += (size_t)blockIdx.y * E * H;
+  logits += (size_t)blockIdx.y * logits_stride;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long long)T * E) return;
   const int t = (int)(idx / E);
@@ -289,12 +315,13 @@ __global__ __launch_bounds__(256) void gate_f32_kernel(const float* __restrict__
   logits[idx] = acc;
 }
 
-hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E,
-                           float* logits, hipStream_t s) {
+hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E, int nbatch,
+                           float* logits, size_t logits_stride, hipStream_t s) {
   const long long total = (long long)T * E;
   if (total == 0) return hipSuccess;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL(gate_f32_kernel, dim3(blocks), dim3(256), 0, s, hidden, w, T, H, E, logits);
+  hipLaunchKernelGGL(gate_f32_kernel, dim3(blocks, nbatch), dim3(256), 0, s, hidden, w, T, H, E, logits,
+                     logits_stride);
   return hipGetLastError();
 }
 

@@ -29,6 +29,9 @@ struct RouteArgs {
   float* st_mass;      // top-k mass M_k
   float* st_entropy;   // Shannon entropy of the scores, nats
   int32_t* st_pool;    // pool size m (candidates above the cut, united with the top-k)
+  // batched calls: the kernels run with the problem index in blockIdx.y
+  int nbatch;          // problems in the call (1: all of the above is the one problem's)
+  size_t ws_stride;    // bytes from one problem's workspace to the next
 };
 // Trimming mode RANDOM: what makes the sample reproducible.
 struct RandomArgs {
@@ -68,6 +71,45 @@ struct Workspace {
   int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
 };
 
+// Problem b of a batched call.  All problems share the sizes; every array of problem
+// b follows that of problem b - 1 without a gap, the workspaces ws_stride bytes apart.
+__device__ __forceinline__ RouteArgs problem_args(const RouteArgs& a0, int b) {
+  RouteArgs a = a0;
+  a.loads_in = a0.loads_in + (size_t)b * a0.E;
+  if (a0.st_mass) a.st_mass = a0.st_mass + (size_t)b * a0.T;
+  if (a0.st_entropy) a.st_entropy = a0.st_entropy + (size_t)b * a0.T;
+  if (a0.st_pool) a.st_pool = a0.st_pool + (size_t)b * a0.T;
+  return a;
+}
+template <typename P>
+__device__ __forceinline__ P* shifted(P* p, size_t bytes) {
+  return reinterpret_cast<P*>(reinterpret_cast<char*>(p) + bytes);
+}
+__device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size_t bytes) {
+  Workspace w;
+  w.logits = shifted(w0.logits, bytes);
+  w.rec_cstar = shifted(w0.rec_cstar, bytes);
+  w.rec_ids = shifted(w0.rec_ids, bytes);
+  w.rec_p = shifted(w0.rec_p, bytes);
+  w.rec_Z = shifted(w0.rec_Z, bytes);
+  w.rec_lane = shifted(w0.rec_lane, bytes);
+  w.flexmask = shifted(w0.flexmask, bytes);
+  w.tile_fixed_cnt = shifted(w0.tile_fixed_cnt, bytes);
+  w.tile_mask = shifted(w0.tile_mask, bytes);
+  w.tile_base = shifted(w0.tile_base, bytes);
+  w.rec_cids = shifted(w0.rec_cids, bytes);
+  w.rec_pref = shifted(w0.rec_pref, bytes);
+  w.flex_list = shifted(w0.flex_list, bytes);
+  w.flex_ord = shifted(w0.flex_ord, bytes);
+  w.flex_tok_base = shifted(w0.flex_tok_base, bytes);
+  w.flex_slot = shifted(w0.flex_slot, bytes);
+  w.chain_bits = shifted(w0.chain_bits, bytes);
+  w.chain_cum = shifted(w0.chain_cum, bytes);
+  w.lin_copy = shifted(w0.lin_copy, bytes);
+  w.status = shifted(w0.status, bytes);
+  return w;
+}
+
 constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished
 constexpr int kStatusFlexTiles = 1;  // number of tiles that hold flexible tokens
 constexpr int kStatusError = 2;      // a bounded wait in the tail kernel ran out
@@ -79,18 +121,22 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits);
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
 
 // Launchers (enqueue only; return the HIP error of the launch).
-// gate projection fused with the per-token analysis (logits_out may be NULL)
+// gate projection fused with the per-token analysis (logits_out may be NULL;
+// logits_stride: floats from one problem's logits to the next)
 hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
                                     const Workspace& ws, int32_t* expert_ids, float* weights,
-                                    float* logits_out, hipStream_t s);
-hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E,
-                           float* logits, hipStream_t s);
-hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
+                                    float* logits_out, size_t logits_stride, hipStream_t s);
+// (problem b of `nbatch`: hidden + b*T*H, w + b*E*H -> logits + b*logits_stride floats)
+hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E, int nbatch,
+                           float* logits, size_t logits_stride, hipStream_t s);
+// (logits_stride: floats from one problem's logits to the next)
+hipError_t launch_analyse(const float* logits, size_t logits_stride, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s);
 // per-token analysis with RANDOM trimming, from logits [T,E]
-hipError_t launch_analyse_random(const float* logits, const RouteArgs& a, const Workspace& ws,
-                                 const RandomArgs& rnd, int32_t* expert_ids, float* weights,
-                                 hipStream_t s);
+// (problem b draws with stream id rnd.stream + b)
+hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                 const Workspace& ws, const RandomArgs& rnd, int32_t* expert_ids,
+                                 float* weights, hipStream_t s);
 hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                        int32_t* expert_offsets, int32_t* expert_ids, float* weights,
                        int32_t* permutation, hipStream_t s);

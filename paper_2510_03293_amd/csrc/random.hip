@@ -48,10 +48,19 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 constexpr int kRandomWaves = 4;  // the counting pass is shared by 4 waves, the rest is wave 0's
 
 __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const float* __restrict__ logits,
-                                                            const RouteArgs a, const Workspace ws,
-                                                            const RandomArgs rnd,
+                                                            size_t logits_stride, const RouteArgs a0,
+                                                            const Workspace ws0, const RandomArgs rnd0,
                                                             int32_t* __restrict__ expert_ids,
                                                             float* __restrict__ weights) {
+  // blockIdx.y: the problem of a batched call; it draws with its own stream id
+  const int prob = blockIdx.y;
+  const RouteArgs a = problem_args(a0, prob);
+  const Workspace ws = problem_workspace(ws0, (size_t)prob * a0.ws_stride);
+  RandomArgs rnd = rnd0;
+  rnd.stream += (uint32_t)prob;
+  logits += (size_t)prob * logits_stride;
+  expert_ids += (size_t)prob * a.T * a.k;
+  weights += (size_t)prob * a.T * a.k;
   __shared__ float zl[kTile * kRowF], pl[kTile * kRowF], tl[kTile * kRowF];
   __shared__ uint8_t ordl[kTile * kRowB], arrl[kTile * kRowB];
   __shared__ unsigned long long maskl[64];
@@ -206,12 +215,12 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
   }
 }
 
-hipError_t launch_analyse_random(const float* logits, const RouteArgs& a, const Workspace& ws,
-                                 const RandomArgs& rnd, int32_t* expert_ids, float* weights,
-                                 hipStream_t s) {
+hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                 const Workspace& ws, const RandomArgs& rnd, int32_t* expert_ids,
+                                 float* weights, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(analyse_random_kernel, dim3(a.ntiles), dim3(64 * kRandomWaves), 0, s, logits, a, ws, rnd,
-                     expert_ids, weights);
+  hipLaunchKernelGGL(analyse_random_kernel, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s, logits,
+                     logits_stride, a, ws, rnd, expert_ids, weights);
   return hipGetLastError();
 }
 

@@ -32,13 +32,21 @@ namespace laser {
 
 template <int NE, bool STATS>  // NE = padded experts / 8
 __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ logits,
-                                                      const RouteArgs a, const Workspace ws,
+                                                      size_t logits_stride, const RouteArgs a0,
+                                                      const Workspace ws0,
                                                       int32_t* __restrict__ expert_ids,
                                                       float* __restrict__ weights) {
   constexpr int ZS = 8 * NE + 8;
   __shared__ __align__(16) float lz[kTile * ZS];
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
+  // blockIdx.y: the problem of a batched call
+  const int prob = blockIdx.y;
+  const RouteArgs a = problem_args(a0, prob);
+  const Workspace ws = problem_workspace(ws0, (size_t)prob * a0.ws_stride);
+  logits += (size_t)prob * logits_stride;
+  expert_ids += (size_t)prob * a.T * a.k;
+  weights += (size_t)prob * a.T * a.k;
   const int tile = blockIdx.x;
   const int E = a.E;
   const int rows = min(kTile, a.T - tile * kTile);
@@ -64,18 +72,18 @@ __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ 
   analyse_tile<NE, 1, STATS>(lz, ZS, mask64, &flex_lds, tile, a, ws, expert_ids, weights, nullptr);
 }
 
-hipError_t launch_analyse(const float* logits, const RouteArgs& a, const Workspace& ws,
+hipError_t launch_analyse(const float* logits, size_t logits_stride, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
-  const dim3 grid(a.ntiles), block(512);
+  const dim3 grid(a.ntiles, a.nbatch), block(512);
   const bool st = wants_stats(a);
 #define LASER_LAUNCH_ANALYSE(NE_)                                                                  \
   if (st)                                                                                          \
-    hipLaunchKernelGGL((analyse_kernel<NE_, true>), grid, block, 0, s, logits, a, ws, expert_ids,  \
-                       weights);                                                                   \
+    hipLaunchKernelGGL((analyse_kernel<NE_, true>), grid, block, 0, s, logits, logits_stride, a,   \
+                       ws, expert_ids, weights);                                                   \
   else                                                                                             \
-    hipLaunchKernelGGL((analyse_kernel<NE_, false>), grid, block, 0, s, logits, a, ws, expert_ids, \
-                       weights);
+    hipLaunchKernelGGL((analyse_kernel<NE_, false>), grid, block, 0, s, logits, logits_stride, a,  \
+                       ws, expert_ids, weights);
   switch (a.EP) {
     case 8: LASER_LAUNCH_ANALYSE(1) break;
     case 16: LASER_LAUNCH_ANALYSE(2) break;
@@ -1294,13 +1302,26 @@ __device__ __forceinline__ int finish_fast(FastShared& fs, unsigned long long fm
   return ntok;
 }
 
-__global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, const Workspace ws,
+template <bool BATCH>  // blockIdx.y is the problem of a batched call (a kernel of its own: the
+                       // longer prologue would delay the first loads of the single-problem kernel)
+__global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a0, const Workspace ws0,
                                                             int32_t* __restrict__ loads_inout,
                                                             int32_t* __restrict__ expert_offsets,
                                                             int32_t* __restrict__ expert_ids,
                                                             float* __restrict__ weights,
                                                             int32_t* __restrict__ permutation) {
   extern __shared__ __align__(16) uint8_t tail_lds[];
+  // (each problem has its own chain workgroup)
+  const int prob = BATCH ? blockIdx.y : 0;
+  const RouteArgs a = BATCH ? problem_args(a0, prob) : a0;
+  const Workspace ws = BATCH ? problem_workspace(ws0, (size_t)prob * a0.ws_stride) : ws0;
+  if (BATCH) {
+    loads_inout += (size_t)prob * a.E;
+    expert_offsets += (size_t)prob * (a.E + 1);
+    expert_ids += (size_t)prob * a.T * a.k;
+    weights += (size_t)prob * a.T * a.k;
+    permutation += (size_t)prob * a.T * a.k;
+  }
   if (blockIdx.x == 0) {
     chain_workgroup(tail_lds, a, ws, loads_inout, expert_offsets);
     return;
@@ -1372,20 +1393,29 @@ __global__ __launch_bounds__(kTailThreads) void tail_kernel(const RouteArgs a, c
               own_base[wave], own_offsets, fast_n, &fs);
 }
 
-hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
-                       int32_t* expert_offsets, int32_t* expert_ids, float* weights,
-                       int32_t* permutation, hipStream_t s) {
+template <bool BATCH>
+static hipError_t launch_tail_b(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                                int32_t* expert_offsets, int32_t* expert_ids, float* weights,
+                                int32_t* permutation, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tail_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tail_kernel<BATCH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int grid = 1 + (a.ntiles + kChainWaves - 1) / kChainWaves;
-  hipLaunchKernelGGL(tail_kernel, dim3(grid), dim3(kTailThreads), kChainLdsBytes, s, a, ws, loads_inout,
-                     expert_offsets, expert_ids, weights, permutation);
+  hipLaunchKernelGGL(tail_kernel<BATCH>, dim3(grid, a.nbatch), dim3(kTailThreads), kChainLdsBytes, s, a, ws,
+                     loads_inout, expert_offsets, expert_ids, weights, permutation);
   return hipGetLastError();
+}
+
+hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
+                       int32_t* expert_offsets, int32_t* expert_ids, float* weights,
+                       int32_t* permutation, hipStream_t s) {
+  if (a.nbatch > 1)
+    return launch_tail_b<true>(a, ws, loads_inout, expert_offsets, expert_ids, weights, permutation, s);
+  return launch_tail_b<false>(a, ws, loads_inout, expert_offsets, expert_ids, weights, permutation, s);
 }
 
 }  // namespace laser

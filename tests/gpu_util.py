@@ -136,3 +136,34 @@ def check_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormal
         werr = np.abs(gpu["weights"].astype(np.float64) - ref["weights"]).max()
         assert werr <= tol, f"{label}: weights max abs err {werr} > {tol}"
     return gpu, ref
+
+
+def run_route_batched(hiddens, w_gates, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True,
+                      want_logits=True, trim_mode=None, seed=0, stream=0):
+    """GPU laser_route_batched on lists of per-problem numpy inputs; list of output dicts."""
+    nb = len(hiddens)
+    kw = {} if trim_mode is None else dict(trim_mode=trim_mode, seed=seed, stream=stream)
+    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, renormalize=renormalize, **kw)
+    hd = torch.stack([to_device(h) for h in hiddens])
+    wd = torch.stack([to_device(w) for w in w_gates])
+    T, H = hiddens[0].shape
+    E = w_gates[0].shape[0]
+    loads = torch.from_numpy(np.ascontiguousarray(np.stack(loads_in), dtype=np.int32)).cuda()
+    one = B.laser_workspace_bytes(T, H, E, params)
+    ws = torch.empty(nb * one, dtype=torch.uint8, device="cuda")
+    ids = torch.full((nb, T, k), -1, dtype=torch.int32, device="cuda")
+    wts = torch.full((nb, T, k), -1.0, dtype=torch.float32, device="cuda")
+    perm = torch.full((nb, T * k), -1, dtype=torch.int32, device="cuda")
+    offs = torch.full((nb, E + 1), -1, dtype=torch.int32, device="cuda")
+    logits = torch.full((nb, T, E), -1.0, dtype=torch.float32, device="cuda") if want_logits else None
+    B.laser_route_batched(hd, wd, nb, T, H, E, params, loads, ids, wts, perm, offs, logits, ws)
+    torch.cuda.synchronize()
+    out = []
+    for b in range(nb):
+        d = {"expert_ids": ids[b].cpu().numpy(), "weights": wts[b].cpu().numpy(),
+             "permutation": perm[b].cpu().numpy(), "expert_offsets": offs[b].cpu().numpy(),
+             "loads": loads[b].cpu().numpy()}
+        if logits is not None:
+            d["logits"] = logits[b].cpu().numpy()
+        out.append(d)
+    return out

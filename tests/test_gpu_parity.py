@@ -386,6 +386,90 @@ def test_imbalance_metrics(L, E, G):
     np.testing.assert_allclose(out["agg"].cpu().numpy(), ref["agg"] if L else [0.0, 0.0], rtol=1e-12)
 
 
+BATCHED = [
+    # B, T, H, E, k, c, dtype, eps_high, t_fix
+    (3, 200, 2048, 64, 6, 8, wl.DTYPE_BF16, 0.6, 0.3),
+    (5, 65, 1000, 5, 2, 3, wl.DTYPE_BF16, 0.6, 0.3),
+    (2, 1500, 512, 16, 2, 6, wl.DTYPE_BF16, 2.0, 0.01),     # every token flexible: window evaluation
+    (7, 64, 2048, 64, 6, 8, wl.DTYPE_BF16, 0.4, 0.8),       # decode-sized problems
+    (4, 256, 128, 8, 2, 4, wl.DTYPE_F32, 0.6, 0.3),
+    (1, 130, 4096, 8, 2, 4, wl.DTYPE_BF16, 0.6, 0.3),
+]
+
+
+@pytest.mark.parametrize("nb,T,H,E,k,c,dtype,eps,tfix", BATCHED)
+def test_batched_call_equals_single_calls(nb, T, H, E, k, c, dtype, eps, tfix):
+    """Every problem of a batched call: logits against the fp64 gate, decisions and
+    tables against the oracle on those logits, and everything bit for bit what a call
+    of its own gives."""
+    import oracle
+    u = _util()
+    rng = np.random.default_rng(nb * 1000 + T + H + E)
+    hs, ws_, ls = [], [], []
+    for b in range(nb):
+        h, w = wl.make_gate(rng, T, H, E, dtype, bias=np.linspace(-1.0, 1.0, E) * (b % 3))
+        hs.append(h)
+        ws_.append(w)
+        ls.append(rng.integers(0, 5 + 40 * b, E).astype(np.int32))
+    got = u.run_route_batched(hs, ws_, dtype, k, c, eps, tfix, ls)
+    tol = u.TOL_LOGIT[dtype]
+    for b in range(nb):
+        label = f"batched problem {b} of {nb}"
+        z = oracle.gate(hs[b], ws_[b], dtype)
+        assert np.abs(got[b]["logits"].astype(np.float64) - z).max() <= tol, label
+        ref = oracle.route(got[b]["logits"], k, c, eps, tfix, ls[b])
+        u.assert_discrete_equal(got[b], ref, label)
+        assert np.abs(got[b]["weights"].astype(np.float64) - ref["weights"]).max() <= tol, label
+        single = u.run_route(hs[b], ws_[b], dtype, k, c, eps, tfix, ls[b])
+        for key in ("logits", "expert_ids", "weights", "permutation", "expert_offsets", "loads"):
+            assert np.array_equal(got[b][key], single[key]), f"{label}: {key} differs from the single call"
+
+
+def test_batched_call_random_trimming_and_no_logits():
+    """RANDOM trimming in a batch: problem b draws with stream id stream + b.  Without
+    a logits buffer the results are the same."""
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    nb, T, H, E, k, c = 3, 300, 512, 32, 2, 5
+    rng = np.random.default_rng(77)
+    hs, ws_, ls = [], [], []
+    for b in range(nb):
+        h, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16)
+        hs.append(h)
+        ws_.append(wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(w) * 0.25))    # flat scores: big pools
+        ls.append(rng.integers(0, 9, E).astype(np.int32))
+    got = u.run_route_batched(hs, ws_, wl.DTYPE_BF16, k, c, 0.9, 0.05, ls, trim_mode=B.TRIM_RANDOM,
+                              seed=1234, stream=5)
+    blind = u.run_route_batched(hs, ws_, wl.DTYPE_BF16, k, c, 0.9, 0.05, ls, trim_mode=B.TRIM_RANDOM,
+                                seed=1234, stream=5, want_logits=False)
+    sampled = 0
+    for b in range(nb):
+        ref = oracle.route_random(got[b]["logits"], k, c, 0.9, 0.05, ls[b], 1234, 5 + b, 0)
+        u.assert_discrete_equal(got[b], ref, f"batched random problem {b}")
+        assert np.abs(got[b]["weights"].astype(np.float64) - ref["weights"]).max() <= 1e-5
+        for key in ("expert_ids", "weights", "permutation", "expert_offsets", "loads"):
+            assert np.array_equal(got[b][key], blind[b][key]), key
+        pool = oracle.token_stats(got[b]["logits"], k, 0.05)["pool_size"]
+        sampled += int(((pool > c) & (ref["expanded"] == 1)).sum())
+    assert sampled > 0
+
+
+def test_batched_call_argument_errors_and_empty():
+    import torch
+    from paper_2510_03293_amd import binding as B
+    p = B.make_params(2, 4, 0.5, 0.5)
+    dummy = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    B.laser_route_batched(None, None, 0, 64, 64, 8, p, None, None, None, None, None, None, None)  # B = 0
+    with pytest.raises(B.LaserError):
+        B.laser_route_batched(dummy, dummy, -1, 64, 64, 8, p, dummy, dummy, dummy, dummy, dummy, None, dummy)
+    with pytest.raises(B.LaserError):      # workspace for one problem only
+        one = B.laser_workspace_bytes(64, 64, 8, p)
+        ws = torch.zeros(one, dtype=torch.uint8, device="cuda")
+        big = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+        B.laser_route_batched(big, big, 2, 64, 64, 8, p, big, big, big, big, big, None, ws)
+
+
 def test_fp32_gate_ragged():
     u = _util()
     rng = np.random.default_rng(17)
