@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
-      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, status, total;
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, status, total;
 };
 
 static Layout layout(int T, int E, bool need_logits) {
@@ -44,6 +44,7 @@ static Layout layout(int T, int E, bool need_logits) {
   L.flex_tok_base = off; off += align_up((ntiles + 1) * 4);
   L.flex_slot = off;  off += align_up((size_t)T * 4);
   L.lin_copy = off;   off += align_up(64 * 4);
+  L.pool = off;       off += align_up((size_t)T * 4);
   L.status = off;     off += align_up(16);
   L.total = off + 256;
   return L;
@@ -74,6 +75,7 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits) {
   w.flex_tok_base = reinterpret_cast<int32_t*>(b + L.flex_tok_base);
   w.flex_slot = reinterpret_cast<int32_t*>(b + L.flex_slot);
   w.lin_copy = reinterpret_cast<int32_t*>(b + L.lin_copy);
+  w.pool = reinterpret_cast<int32_t*>(b + L.pool);
   w.status = reinterpret_cast<int32_t*>(b + L.status);
   return w;
 }
@@ -139,6 +141,7 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.st_mass = nullptr;
   a.st_entropy = nullptr;
   a.st_pool = nullptr;
+  a.pool_in_ws = 0;
   a.nbatch = 1;
   a.ws_stride = 0;
   return a;
@@ -207,16 +210,20 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t
   const bool timed = !g_profile.ev.empty() && (size_t)(2 * g_profile.used + 1) < g_profile.ev.size() && T > 0;
   if (timed && hipEventRecord(g_profile.ev[2 * g_profile.used], s) != hipSuccess) return LASER_E_LAUNCH;
   const bool random = params->trim_mode == LASER_TRIM_RANDOM;
+  // RANDOM trimming with c > k: the deterministic analysis, told to leave the pool sizes,
+  // then a second look at the tokens whose pool exceeds c.  With c == k a sampled token
+  // is not load-dependent but its experts are the sample: the stand-alone analysis.
+  const bool resample = random && params->c > params->k;
+  if (resample && !a.st_pool) a.pool_in_ws = 1;
   if (params->dtype == LASER_DTYPE_BF16) {
-    // gate projection and per-token analysis in one kernel; RANDOM trimming takes the
-    // logits from it and analyses again with its own kernel (that mode is not tuned)
     float* logits = random ? (logits_out ? logits_out : ws.logits) : logits_out;
     const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);
     if (launch_gate_analyse_bf16(hidden, w_gate, H, a, ws, expert_ids, weights, logits, lstride, s) !=
         hipSuccess)
       return LASER_E_LAUNCH;
-    if (random && launch_analyse_random(logits, lstride, a, ws, make_random(params), expert_ids, weights,
-                                        s) != hipSuccess)
+    if (random && (resample ? launch_random_resample(logits, lstride, a, ws, make_random(params), s)
+                            : launch_analyse_random(logits, lstride, a, ws, make_random(params), expert_ids,
+                                                    weights, s)) != hipSuccess)
       return LASER_E_LAUNCH;
   } else {
     float* logits = logits_out ? logits_out : ws.logits;
@@ -224,12 +231,14 @@ static int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t
     if (launch_gate_f32(static_cast<const float*>(hidden), static_cast<const float*>(w_gate), T, H, E, B,
                         logits, lstride, s) != hipSuccess)
       return LASER_E_LAUNCH;
-    if (random) {
+    if (random && !resample) {
       if (launch_analyse_random(logits, lstride, a, ws, make_random(params), expert_ids, weights, s) !=
           hipSuccess)
         return LASER_E_LAUNCH;
-    } else if (launch_analyse(logits, lstride, a, ws, expert_ids, weights, s) != hipSuccess) {
-      return LASER_E_LAUNCH;
+    } else {
+      if (launch_analyse(logits, lstride, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+      if (resample && launch_random_resample(logits, lstride, a, ws, make_random(params), s) != hipSuccess)
+        return LASER_E_LAUNCH;
     }
   }
   if (timed) {
@@ -284,11 +293,16 @@ int laser_route_from_logits(const float* logits, int32_t T, int32_t E,
   a.loads_in = loads_inout;
   const Workspace ws = carve_workspace(workspace, T, E, true);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (params->trim_mode == LASER_TRIM_RANDOM) {
+  const bool random = params->trim_mode == LASER_TRIM_RANDOM;
+  const bool resample = random && params->c > params->k;  // (see route_impl)
+  if (resample) a.pool_in_ws = 1;
+  if (random && !resample) {
     if (launch_analyse_random(logits, 0, a, ws, make_random(params), expert_ids, weights, s) != hipSuccess)
       return LASER_E_LAUNCH;
-  } else if (launch_analyse(logits, 0, a, ws, expert_ids, weights, s) != hipSuccess) {
-    return LASER_E_LAUNCH;
+  } else {
+    if (launch_analyse(logits, 0, a, ws, expert_ids, weights, s) != hipSuccess) return LASER_E_LAUNCH;
+    if (resample && launch_random_resample(logits, 0, a, ws, make_random(params), s) != hipSuccess)
+      return LASER_E_LAUNCH;
   }
   return route_tail(a, ws, loads_inout, expert_ids, weights, permutation, expert_offsets, s);
 }

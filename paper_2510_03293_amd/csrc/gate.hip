@@ -98,8 +98,9 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
   const int prob = BATCH ? blockIdx.y : 0;
-  const RouteArgs a = BATCH ? problem_args(a0, prob) : a0;
+  RouteArgs a = BATCH ? problem_args(a0, prob) : a0;
   const Workspace ws = BATCH ? problem_workspace(ws0, (size_t)prob * a0.ws_stride) : ws0;
+  if (STATS && a.pool_in_ws) a.st_pool = ws.pool;
   if (BATCH) {
     hidden += (size_t)prob * a.T * H;
     w += (size_t)prob * a.E * H;

@@ -29,6 +29,8 @@ struct RouteArgs {
   float* st_mass;      // top-k mass M_k
   float* st_entropy;   // Shannon entropy of the scores, nats
   int32_t* st_pool;    // pool size m (candidates above the cut, united with the top-k)
+  int pool_in_ws;      // 1: nobody asked for st_pool but RANDOM trimming needs the pool sizes:
+                       // the kernels write and read them in the workspace (Workspace::pool)
   // batched calls: the kernels run with the problem index in blockIdx.y
   int nbatch;          // problems in the call (1: all of the above is the one problem's)
   size_t ws_stride;    // bytes from one problem's workspace to the next
@@ -39,7 +41,7 @@ struct RandomArgs {
   unsigned long long token_offset;  // index of token 0 of this call in the caller's numbering
   uint32_t stream;                  // caller's stream id (e.g. the layer)
 };
-inline bool wants_stats(const RouteArgs& a) { return a.st_mass || a.st_entropy || a.st_pool; }
+inline bool wants_stats(const RouteArgs& a) { return a.st_mass || a.st_entropy || a.st_pool || a.pool_in_ws; }
 
 // Device workspace carved out of the caller's buffer.  Records are written by
 // the per-token analysis, consumed by the load-ordered chain and the finishing
@@ -68,6 +70,7 @@ struct Workspace {
                                //           the f-th flexible token
   int32_t* chain_cum;          // [T/32+2,64] per expert: choices by flexible tokens < 32*w
   int32_t* lin_copy;           // [64] loads before token 0 (0 beyond E)
+  int32_t* pool;               // [T] pool sizes, when RANDOM trimming needs them (see pool_in_ws)
   int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
 };
 
@@ -106,6 +109,7 @@ __device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size
   w.chain_bits = shifted(w0.chain_bits, bytes);
   w.chain_cum = shifted(w0.chain_cum, bytes);
   w.lin_copy = shifted(w0.lin_copy, bytes);
+  w.pool = shifted(w0.pool, bytes);
   w.status = shifted(w0.status, bytes);
   return w;
 }
@@ -132,11 +136,15 @@ hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, in
 // (logits_stride: floats from one problem's logits to the next)
 hipError_t launch_analyse(const float* logits, size_t logits_stride, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s);
-// per-token analysis with RANDOM trimming, from logits [T,E]
-// (problem b draws with stream id rnd.stream + b)
+// per-token analysis with RANDOM trimming, from logits [T,E]: the whole analysis
+// (problem b draws with stream id rnd.stream + b) ...
 hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,
                                  const Workspace& ws, const RandomArgs& rnd, int32_t* expert_ids,
                                  float* weights, hipStream_t s);
+// ... or, behind the deterministic analysis run with pool sizes (c > k only), a second
+// look at the tokens whose pool exceeds c: their records are rewritten for the sample
+hipError_t launch_random_resample(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                  const Workspace& ws, const RandomArgs& rnd, hipStream_t s);
 hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                        int32_t* expert_offsets, int32_t* expert_ids, float* weights,
                        int32_t* permutation, hipStream_t s);

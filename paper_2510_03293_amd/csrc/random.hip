@@ -13,10 +13,13 @@
 // the score order swaps position i with i + floor(r_i * (m - i) / 2^32) for
 // i = 0..c-1; the first c positions, in ascending order, are the candidates.
 //
-// One workgroup per tile of 64 tokens, lane = token, per-token arrays in LDS.  The
-// order statistics are found by counting (E^2 compares per token, shared by four
-// waves); everything after that is one wavefront's work.  This mode is written for
-// clarity, not for speed.
+// Two kernels.  analyse_random_kernel is the whole analysis in this mode: one workgroup
+// per tile of 64 tokens, lane = token, per-token arrays in LDS, order statistics by
+// counting (E^2 compares per token, shared by four waves), everything after that one
+// wavefront's work; written for clarity, and used where c == k (a sampled token is then
+// not load-dependent, but its experts are the sample).  Where c > k the deterministic
+// analysis already gives everything but the candidates of the tokens it trimmed, and
+// random_resample_kernel only redoes those.
 #include "analyse.h"
 #include "laser_internal.h"
 
@@ -213,6 +216,128 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
       if (in) row[e] = (uint16_t)((pref << 4) | j);
     }
   }
+}
+
+// RANDOM trimming with c > k, behind the deterministic analysis.  That analysis has
+// written, for every token, what the RANDOM mode would write too -- except the
+// candidates of the tokens it trimmed: load-dependent tokens whose pool is larger than c
+// (working-set size c in both modes).  Those are found here by (rec_cstar > 0, pool
+// size > c); their c candidates are drawn instead of taken from the top, and their
+// records are written again.  Fixed tokens, masks, counts and the flexible-token masks
+// are not touched: none of them depends on which candidates a flexible token has.
+// One workgroup per tile; tiles without such a token cost two loads per lane.
+__global__ __launch_bounds__(64 * kRandomWaves) void random_resample_kernel(const float* __restrict__ logits,
+                                                             size_t logits_stride, const RouteArgs a0,
+                                                             const Workspace ws0, const RandomArgs rnd0) {
+  const int prob = blockIdx.y;  // the problem of a batched call; it draws with its own stream id
+  const RouteArgs a = problem_args(a0, prob);
+  const Workspace ws = problem_workspace(ws0, (size_t)prob * a0.ws_stride);
+  RandomArgs rnd = rnd0;
+  rnd.stream += (uint32_t)prob;
+  logits += (size_t)prob * logits_stride;
+  __shared__ float zl[kTile * kRowF];
+  __shared__ uint8_t ordl[kTile * kRowB], arrl[kTile * kRowB];
+  __shared__ unsigned long long maskl[64];
+  const int tile = blockIdx.x, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int t = tile * kTile + lane;
+  const bool live = t < a.T;
+  const int E = a.E, k = a.k, c = a.c;
+  const int32_t* pool = a.pool_in_ws ? ws.pool : a.st_pool;
+
+  const int cst = live ? (int)ws.rec_cstar[t] : 0;
+  const int m = live ? pool[t] : 0;
+  const bool sampled = cst > 0 && m > c;  // (then cst == c)
+  const unsigned long long smask = __builtin_amdgcn_ballot_w64(sampled);  // the same in all four waves
+  if (smask == 0ull) return;
+
+  const int rows = min(kTile, a.T - tile * kTile);
+  const float* src = logits + (size_t)tile * kTile * E;
+  for (int idx = threadIdx.x; idx < kTile * E; idx += 64 * kRandomWaves) {
+    const int tok = idx / E;
+    zl[tok * kRowF + (idx - tok * E)] = tok < rows ? src[idx] : 0.0f;
+  }
+  if (wave == 0) maskl[lane] = ws.tile_mask[(size_t)tile * 64 + lane];
+  const unsigned long long fm = ws.flexmask[tile];
+  __syncthreads();
+
+  const float* z = zl + lane * kRowF;
+  uint8_t* ord = ordl + lane * kRowB;  // expert at each position of the score order
+  uint8_t* arr = arrl + lane * kRowB;  // candidate positions
+
+  // ---- order: logit descending, equal logits by lower index (wave w places experts
+  // w, w + 4, ...) -----------------------------------------------------------------
+  if (sampled) {
+    for (int i = wave; i < E; i += kRandomWaves) {
+      const float zi = z[i];
+      int before = 0;
+      for (int j = 0; j < E; ++j) {
+        const float zj = z[j];
+        before += (zj > zi || (zj == zi && j < i)) ? 1 : 0;
+      }
+      ord[before] = (uint8_t)i;
+    }
+  }
+  __syncthreads();
+  if (wave != 0 || !sampled) return;
+  const float zmax = z[ord[0]];
+
+  // ---- the sample: positions in the score order, ascending -----------------------
+  for (int i = 0; i < m; ++i) arr[i] = (uint8_t)i;
+  const unsigned long long g = rnd.token_offset + (unsigned long long)t;
+  uint32_t wv[4] = {0u, 0u, 0u, 0u};
+  for (int i = 0; i < c; ++i) {
+    if ((i & 3) == 0)
+      philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), rnd.stream, (uint32_t)(i >> 2), (uint32_t)rnd.seed,
+                    (uint32_t)(rnd.seed >> 32), wv);
+    const uint32_t r = (i & 3) == 0 ? wv[0] : (i & 3) == 1 ? wv[1] : (i & 3) == 2 ? wv[2] : wv[3];
+    const int j = i + (int)__umulhi(r, (uint32_t)(m - i));
+    const uint8_t tmp = arr[i];
+    arr[i] = arr[j];
+    arr[j] = tmp;
+  }
+  for (int i = 1; i < c; ++i) {  // insertion sort of the first c
+    const uint8_t x = arr[i];
+    int j = i - 1;
+    while (j >= 0 && arr[j] > x) {
+      arr[j + 1] = arr[j];
+      --j;
+    }
+    arr[j + 1] = x;
+  }
+
+  // ---- the token's records, as the analysis writes them --------------------------
+  const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(lane));
+  const unsigned long long below = lanes_below(lane);
+  int padlane = E;  // ranks beyond the working set point the chain at a lane that holds no candidate
+  if (E == 64) {
+    unsigned used = 0;
+    for (int j = 0; j < c; ++j) {
+      const int e = ord[arr[j]];
+      if (e < 32) used |= 1u << e;
+    }
+    padlane = __builtin_ctz(~used);  // at most 16 of the 32 low experts are candidates
+  }
+  uint16_t* row = ws.rec_lane + (size_t)slot * a.EP;
+  for (int e = 0; e < a.EP; ++e) row[e] = (uint16_t)0xFFFF;
+  for (int j = 0; j < kMaxC; ++j) {
+    const bool in = j < c;
+    const int e = in ? (int)ord[arr[j]] : 0;
+    const int pref = in ? __builtin_popcountll(maskl[e] & below) : 0xFF;
+    ws.rec_ids[(size_t)t * 16 + j] = (uint8_t)e;
+    ws.rec_p[(size_t)t * 16 + j] = in ? exp_fixed(clamp_exp_arg(z[e] - zmax)) : 0.0f;
+    ws.rec_cids[(size_t)slot * 16 + j] = (uint8_t)(in ? e : padlane);
+    ws.rec_pref[(size_t)slot * 16 + j] = (uint8_t)pref;
+    if (in) row[e] = (uint16_t)((pref << 4) | j);
+  }
+}
+
+hipError_t launch_random_resample(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                  const Workspace& ws, const RandomArgs& rnd, hipStream_t s) {
+  if (a.ntiles == 0) return hipSuccess;
+  hipLaunchKernelGGL(random_resample_kernel, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s, logits,
+                     logits_stride, a, ws, rnd);
+  return hipGetLastError();
 }
 
 hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,

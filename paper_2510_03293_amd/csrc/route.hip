@@ -42,8 +42,9 @@ __global__ __launch_bounds__(512) void analyse_kernel(const float* __restrict__ 
   __shared__ unsigned long long flex_lds;
   // blockIdx.y: the problem of a batched call
   const int prob = blockIdx.y;
-  const RouteArgs a = problem_args(a0, prob);
+  RouteArgs a = problem_args(a0, prob);
   const Workspace ws = problem_workspace(ws0, (size_t)prob * a0.ws_stride);
+  if (STATS && a.pool_in_ws) a.st_pool = ws.pool;
   logits += (size_t)prob * logits_stride;
   expert_ids += (size_t)prob * a.T * a.k;
   weights += (size_t)prob * a.T * a.k;
