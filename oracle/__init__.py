@@ -59,6 +59,8 @@ def _load():
         lib.laser_oracle_token_stats.restype = ctypes.c_int
         lib.laser_oracle_imbalance.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp]
         lib.laser_oracle_imbalance.restype = ctypes.c_int
+        lib.laser_oracle_percentiles.argtypes = [vp, i32, vp, i32, vp]
+        lib.laser_oracle_percentiles.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -203,6 +205,17 @@ def imbalance(counts, placement=None, weights=None):
                                         _ptr(out["MV"]), _ptr(out["I_gpu"]), _ptr(out["agg"]))
     if rc:
         raise ValueError(f"oracle imbalance: bad arguments ({rc})")
+    return out
+
+
+def percentiles(values, q):
+    """q-th percentiles (q in [0, 100]) of a 1-D array, linear interpolation between ranks."""
+    v = np.ascontiguousarray(values, dtype=np.float64).ravel()
+    qq = np.ascontiguousarray(q, dtype=np.float64).ravel()
+    out = np.empty(len(qq))
+    rc = _load().laser_oracle_percentiles(_ptr(v), len(v), _ptr(qq), len(qq), _ptr(out))
+    if rc:
+        raise ValueError(f"oracle percentiles: bad arguments ({rc})")
     return out
 
 

@@ -476,6 +476,42 @@ int laser_oracle_imbalance(const int32_t* counts, int32_t L, int32_t E, const do
   return ORACLE_OK;
 }
 
+/* Percentiles of n values (Evaluation, Metrics: I_agg is summarised by its 50th and
+ * 95th percentile across batches).  The paper does not say how a percentile that falls
+ * between two batches is read; the reading here is the common one: sort ascending, the
+ * q-th percentile sits at position h = (n - 1) q / 100 of the sorted list and is
+ * interpolated linearly between the two neighbours, x[lo] + (h - lo)(x[lo+1] - x[lo]).
+ * P50 of an odd number of values is the middle one, P0 the smallest, P100 the largest. */
+int laser_oracle_percentiles(const double* values, int32_t n, const double* q, int32_t nq,
+                             double* out) {
+  if (n < 1 || nq < 0) return ORACLE_E_ARG;
+  double* x = (double*)malloc((size_t)n * sizeof(double));
+  if (!x) return ORACLE_E_ARG;
+  for (int32_t i = 0; i < n; ++i) x[i] = values[i];
+  for (int32_t i = 1; i < n; ++i) { /* insertion sort */
+    const double v = x[i];
+    int32_t j = i - 1;
+    while (j >= 0 && x[j] > v) {
+      x[j + 1] = x[j];
+      --j;
+    }
+    x[j + 1] = v;
+  }
+  for (int32_t i = 0; i < nq; ++i) {
+    if (!(q[i] >= 0.0 && q[i] <= 100.0)) {
+      free(x);
+      return ORACLE_E_ARG;
+    }
+    const double h = (double)(n - 1) * q[i] / 100.0;
+    int32_t lo = (int32_t)h; /* h >= 0: truncation is the floor */
+    if (lo > n - 1) lo = n - 1;
+    const int32_t hi = lo + 1 < n ? lo + 1 : lo;
+    out[i] = x[lo] + (h - (double)lo) * (x[hi] - x[lo]);
+  }
+  free(x);
+  return ORACLE_OK;
+}
+
 /* ------------------------------------------------- the router, literal fp64 -- */
 
 /* Same interface on fp64 logits, formulas as printed: s = softmax(z) with libm

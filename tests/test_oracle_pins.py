@@ -478,6 +478,30 @@ def test_imbalance_against_numpy_and_weights():
     assert (rp["I_gpu"] >= rp["I"] / (E // G) - 1e-12).all() and (rp["I_gpu"] <= rp["I"] + 1e-12).all()
 
 
+def test_percentiles_hand_values_and_library():
+    """Worked by hand: five values, positions h = 4q/100.  P50 is the middle value,
+    P95 sits 0.8 of the way from the 4th to the 5th, P25 is the 2nd, P0/P100 the ends.
+    Then against the numerical library's default percentile on random data, and the
+    properties that pin the definition: monotone in q, invariant under permutation, a
+    constant list gives the constant, two values interpolate linearly."""
+    v = [3.0, 1.0, 10.0, 2.0, 4.0]                       # sorted: 1 2 3 4 10
+    got = oracle.percentiles(v, [0, 25, 50, 95, 100, 10])
+    np.testing.assert_allclose(got, [1.0, 2.0, 3.0, 4.0 + 0.8 * 6.0, 10.0, 1.4], rtol=0, atol=1e-14)
+    rng = np.random.default_rng(11)
+    for n in (1, 2, 7, 100, 1001):
+        x = rng.random(n) * 9 + 1
+        q = np.array([0, 1, 33.3, 50, 95, 99.9, 100])
+        np.testing.assert_allclose(oracle.percentiles(x, q), np.percentile(x, q), rtol=1e-14)
+        np.testing.assert_allclose(oracle.percentiles(x[::-1], q), oracle.percentiles(x, q), rtol=0)
+        assert np.all(np.diff(oracle.percentiles(x, np.linspace(0, 100, 41))) >= 0)
+    assert np.all(oracle.percentiles([2.5] * 9, [0, 50, 95]) == 2.5)
+    np.testing.assert_allclose(oracle.percentiles([1.0, 3.0], [50, 95]), [2.0, 2.9], atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.percentiles([1.0], [101])
+    with pytest.raises(ValueError):
+        oracle.percentiles([], [50])
+
+
 # ----------------------------------------------------------- RANDOM trimming ----
 
 def test_philox_known_answers():
