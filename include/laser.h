@@ -178,6 +178,19 @@ int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, const float* pl
                     int32_t G, const float* layer_weights, double* I, double* MV, double* I_gpu,
                     double* agg, void* hip_stream);
 
+/*
+ * Percentiles of n values on the device, e.g. of the aggregate imbalance factor of n
+ * batches (Evaluation, Metrics: the aggregate is summarised by its 50th and 95th
+ * percentile across batches).  The q-th percentile sits at position (n-1)*q/100 of the
+ * ascending list and is interpolated linearly between its two neighbours.
+ *   values  [n] fp64, device pointer, no NaN                       in
+ *   q       [nq] fp64, HOST pointer, each in [0, 100]              in
+ *   out     [nq] fp64, device pointer                              out
+ * Limits: 1 <= n <= 4096 (more: LASER_E_UNSUPPORTED), nq <= 16.
+ */
+int laser_percentiles(const double* values, int32_t n, const double* q, int32_t nq, double* out,
+                      void* hip_stream);
+
 /* Static, NUL-terminated description of a return code (host pointer). */
 const char* laser_strerror(int code);
 

@@ -19,7 +19,7 @@ DTYPE_BF16 = 1
 TRIM_TOP = 0
 TRIM_RANDOM = 1
 
-EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance",
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance", "laser_percentiles",
            "laser_strerror", "laser_profile_enable", "laser_profile_read",
            "laser_profile_event_overhead", "laser_profile_plain_read")
 
@@ -66,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.laser_route_stats.restype = ctypes.c_int
     lib.laser_imbalance.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.laser_imbalance.restype = ctypes.c_int
+    lib.laser_percentiles.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), i32, vp, vp]
+    lib.laser_percentiles.restype = ctypes.c_int
     lib.laser_route_from_logits.argtypes = [vp, i32, i32, pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.laser_route_from_logits.restype = ctypes.c_int
     lib.laser_strerror.argtypes = [ctypes.c_int]
@@ -167,6 +169,16 @@ def laser_imbalance(counts, placement=None, layer_weights=None, stream=None):
     _check(_lib.laser_imbalance(_ptr(counts), L, E, _ptr(placement), G, _ptr(layer_weights),
                                 _ptr(out["I"]), _ptr(out["MV"]), _ptr(out["I_gpu"]),
                                 _ptr(out["agg"]), _stream_handle(stream)))
+    return out
+
+
+def laser_percentiles(values, q, stream=None):
+    """q-th percentiles (host sequence, each in [0, 100]) of a device fp64 vector; device fp64 [len(q)]."""
+    qs = [float(x) for x in q]
+    qa = (ctypes.c_double * max(len(qs), 1))(*qs)
+    out = torch.empty(len(qs), dtype=torch.float64, device=values.device)
+    _check(_lib.laser_percentiles(_ptr(values), values.numel(), qa, len(qs), _ptr(out),
+                                  _stream_handle(stream)))
     return out
 
 

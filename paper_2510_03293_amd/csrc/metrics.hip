@@ -93,9 +93,61 @@ __global__ void imbalance_aggregate_kernel(const double* __restrict__ I, const d
   agg[1] = a1;
 }
 
+// Percentiles of n values: every value's rank by counting (value, then index, so equal
+// values get distinct ranks), the sorted list in LDS, then one lane per percentile reads
+// its two neighbours.  One workgroup; n <= kMaxPercentileValues.
+constexpr int kMaxPercentileValues = 4096;
+constexpr int kMaxPercentiles = 16;
+struct PercentileArgs {
+  double q[kMaxPercentiles];
+  int nq;
+};
+
+__global__ __launch_bounds__(kMetricThreads) void percentile_kernel(const double* __restrict__ values, int n,
+                                                                    const PercentileArgs pa,
+                                                                    double* __restrict__ out) {
+  __shared__ double raw[kMaxPercentileValues], sorted[kMaxPercentileValues];
+  for (int i = threadIdx.x; i < n; i += kMetricThreads) raw[i] = values[i];
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += kMetricThreads) {
+    const double v = raw[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const double u = raw[j];
+      rank += (u < v || (u == v && j < i)) ? 1 : 0;
+    }
+    sorted[rank] = v;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < pa.nq) {
+    const double h = (double)(n - 1) * pa.q[threadIdx.x] / 100.0;
+    int lo = (int)h;
+    lo = lo > n - 1 ? n - 1 : lo;
+    const int hi = lo + 1 < n ? lo + 1 : lo;
+    out[threadIdx.x] = sorted[lo] + (h - (double)lo) * (sorted[hi] - sorted[lo]);
+  }
+}
+
 }  // namespace laser
 
 using namespace laser;
+
+extern "C" int laser_percentiles(const double* values, int32_t n, const double* q, int32_t nq,
+                                 double* out, void* hip_stream) {
+  if (n < 1 || nq < 0 || nq > kMaxPercentiles) return LASER_E_RANGE;
+  if (n > kMaxPercentileValues) return LASER_E_UNSUPPORTED;
+  if (nq == 0) return LASER_OK;
+  if (!values || !q || !out) return LASER_E_NULL;
+  PercentileArgs pa;
+  pa.nq = nq;
+  for (int i = 0; i < kMaxPercentiles; ++i) {
+    pa.q[i] = i < nq ? q[i] : 0.0;
+    if (i < nq && !(q[i] >= 0.0 && q[i] <= 100.0)) return LASER_E_RANGE;
+  }
+  hipLaunchKernelGGL(percentile_kernel, dim3(1), dim3(kMetricThreads), 0, static_cast<hipStream_t>(hip_stream),
+                     values, n, pa, out);
+  return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;
+}
 
 extern "C" int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, const float* placement,
                                int32_t G, const float* layer_weights, double* I, double* MV,

@@ -470,6 +470,24 @@ def test_batched_call_argument_errors_and_empty():
         B.laser_route_batched(big, big, 2, 64, 64, 8, p, big, big, big, big, big, None, ws)
 
 
+@pytest.mark.parametrize("n", [1, 2, 5, 100, 1001, 4096])
+def test_percentiles_on_device(n):
+    """Percentiles over batches: the device result against the oracle (same fp64
+    operations, so equal to the last bit), with repeated values in the list."""
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    rng = np.random.default_rng(n)
+    x = np.round(rng.random(n) * 9 + 1, 2)               # rounding makes ties
+    q = [0, 1, 33.3, 50, 95, 99.9, 100]
+    got = B.laser_percentiles(torch.from_numpy(x).cuda(), q).cpu().numpy()
+    assert np.array_equal(got, oracle.percentiles(x, q))
+    with pytest.raises(B.LaserError):
+        B.laser_percentiles(torch.zeros(4097, dtype=torch.float64, device="cuda"), [50])
+    with pytest.raises(B.LaserError):
+        B.laser_percentiles(torch.zeros(4, dtype=torch.float64, device="cuda"), [101.0])
+
+
 def test_fp32_gate_ragged():
     u = _util()
     rng = np.random.default_rng(17)
