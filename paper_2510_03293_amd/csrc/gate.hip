@@ -243,13 +243,10 @@ template <int EB, int NE, int NM, bool STATS, bool BATCH>
 static hipError_t launch_nmb(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
                              float* logits_out, size_t logits_stride, hipStream_t s) {
-  static bool attr_set = false;
+  static LdsAttr allowed;
   const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGateLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  const hipError_t e = allow_dynamic_lds(fn, kGateLdsBytes, allowed);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>), dim3(a.ntiles, a.nbatch), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out, logits_stride);

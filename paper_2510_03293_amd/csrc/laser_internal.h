@@ -124,6 +124,23 @@ Workspace carve_workspace(void* base, int T, int E, bool need_logits);
 
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
 
+// Large dynamic LDS must be allowed per kernel and per device before the first launch.
+// `done` is the kernel's own record of the devices it has been allowed on.
+constexpr int kMaxDevices = 64;
+struct LdsAttr {
+  bool done[kMaxDevices] = {};
+};
+inline hipError_t allow_dynamic_lds(const void* fn, int bytes, LdsAttr& rec) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool known = dev >= 0 && dev < kMaxDevices;
+  if (known && rec.done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && known) rec.done[dev] = true;
+  return e;
+}
+
 // Launchers (enqueue only; return the HIP error of the launch).
 // gate projection fused with the per-token analysis (logits_out may be NULL;
 // logits_stride: floats from one problem's logits to the next)

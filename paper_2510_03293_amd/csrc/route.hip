@@ -1398,13 +1398,10 @@ template <bool BATCH>
 static hipError_t launch_tail_b(const RouteArgs& a, const Workspace& ws, int32_t* loads_inout,
                                 int32_t* expert_offsets, int32_t* expert_ids, float* weights,
                                 int32_t* permutation, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tail_kernel<BATCH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttr allowed;
+  const hipError_t e =
+      allow_dynamic_lds(reinterpret_cast<const void*>(&tail_kernel<BATCH>), kChainLdsBytes, allowed);
+  if (e != hipSuccess) return e;
   const int grid = 1 + (a.ntiles + kChainWaves - 1) / kChainWaves;
   hipLaunchKernelGGL(tail_kernel<BATCH>, dim3(grid, a.nbatch), dim3(kTailThreads), kChainLdsBytes, s, a, ws,
                      loads_inout, expert_offsets, expert_ids, weights, permutation);
