@@ -461,6 +461,16 @@ def test_batched_call_argument_errors_and_empty():
     p = B.make_params(2, 4, 0.5, 0.5)
     dummy = torch.zeros(1024, dtype=torch.uint8, device="cuda")
     B.laser_route_batched(None, None, 0, 64, 64, 8, p, None, None, None, None, None, None, None)  # B = 0
+    # three problems without tokens: offsets zeroed, loads untouched
+    E = 8
+    loads = torch.arange(3 * E, dtype=torch.int32, device="cuda").reshape(3, E).contiguous()
+    offs = torch.full((3, E + 1), -1, dtype=torch.int32, device="cuda")
+    wg = torch.zeros((3, E, 64), dtype=torch.bfloat16, device="cuda")
+    ws0 = torch.zeros(3 * B.laser_workspace_bytes(0, 64, E, p), dtype=torch.uint8, device="cuda")
+    B.laser_route_batched(None, wg, 3, 0, 64, E, p, loads, None, None, None, offs, None, ws0)
+    torch.cuda.synchronize()
+    assert torch.equal(offs, torch.zeros_like(offs))
+    assert torch.equal(loads.cpu(), torch.arange(3 * E, dtype=torch.int32).reshape(3, E))
     with pytest.raises(B.LaserError):
         B.laser_route_batched(dummy, dummy, -1, 64, 64, 8, p, dummy, dummy, dummy, dummy, dummy, None, dummy)
     with pytest.raises(B.LaserError):      # workspace for one problem only
