@@ -455,6 +455,37 @@ def test_batched_call_random_trimming_and_no_logits():
     assert sampled > 0
 
 
+def test_random_trimming_with_statistics_in_one_call():
+    """laser_route_stats in RANDOM mode: the pool sizes the caller asked for are the ones
+    the resampling pass works from (no copy in the workspace then)."""
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    T, H, E, k, c = 500, 512, 32, 2, 5
+    rng = np.random.default_rng(5)
+    h, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16)
+    w = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(w) * 0.25)
+    loads_in = rng.integers(0, 9, E).astype(np.int32)
+    params = B.make_params(k, c, 0.9, 0.05, dtype=wl.DTYPE_BF16, trim_mode=B.TRIM_RANDOM, seed=99, stream=3)
+    hd, wd = u.to_device(h), u.to_device(w)
+    loads = torch.from_numpy(loads_in.copy()).cuda()
+    buf = B.RouteBuffers(T, H, E, params, want_logits=True)
+    pool = torch.full((T,), -1, dtype=torch.int32, device="cuda")
+    B.laser_route_stats(hd, wd, T, H, E, params, loads, buf.expert_ids, buf.weights, buf.permutation,
+                        buf.expert_offsets, buf.logits, None, None, pool, buf.workspace)
+    torch.cuda.synchronize()
+    z = buf.logits.cpu().numpy()
+    ref = oracle.route_random(z, k, c, 0.9, 0.05, loads_in, 99, 3, 0)
+    got = {"expert_ids": buf.expert_ids.cpu().numpy(), "weights": buf.weights.cpu().numpy(),
+           "permutation": buf.permutation.cpu().numpy(), "expert_offsets": buf.expert_offsets.cpu().numpy(),
+           "loads": loads.cpu().numpy()}
+    u.assert_discrete_equal(got, ref, "random + stats")
+    st = oracle.token_stats(z, k, 0.05)
+    assert np.array_equal(pool.cpu().numpy(), st["pool_size"])
+    assert int(((st["pool_size"] > c) & (ref["expanded"] == 1)).sum()) > 0
+
+
 def test_batched_call_argument_errors_and_empty():
     import torch
     from paper_2510_03293_amd import binding as B
