@@ -353,6 +353,7 @@ constexpr int kSpecMinTokens = 256;           // fewer flexible tokens: sequenti
 constexpr int kSpecCheckSweeps = 8;           // progress is judged over this many sweeps ...
 // ... in which at least this many tokens must retire (measured: a sweep costs about
 // 0.56 / 0.96 us for 4 / 8 candidates, a sequential step 0.12 / 0.17 us)
+constexpr int kSpecGuessProgress = 26 * kSpecCheckSweeps;  // (without guesses at most 32 per sweep retire)
 constexpr int spec_min_progress(int cp) { return cp <= 4 ? 40 : cp <= 8 ? 48 : 56; }
 
 template <int CP>
@@ -450,9 +451,13 @@ __device__ __forceinline__ unsigned long long rotr64(unsigned long long x, int s
 }
 
 // Producer: tokens seg*192 + half*64 + lane of the call -> ring (half = 0, 1, 2).
-template <int CP>
+// Bit 31 of a counter marks the rank as part of the token's first tentative choice: the
+// k least loaded candidates by the counters without any flexible choice.  Any first
+// guess gives the same final result; a good one saves the sweep a token otherwise
+// needs only to get a tentative choice, and lets the tokens behind it retire with it.
+template <int CP, int KK, bool GUESS>
 __device__ __forceinline__ void spec_fill(SpecTok<CP>* ring, int seg, int half, int nflex_tok, const Workspace& ws,
-                          const int* lin_tab, int lane) {
+                          const int* lin_tab, int lane, int k) {
   const int f = seg * kSpecSeg + half * 64 + lane;
   if (f >= nflex_tok) return;
   const int slot = ws.flex_slot[f];
@@ -469,18 +474,23 @@ __device__ __forceinline__ void spec_fill(SpecTok<CP>* ring, int seg, int half, 
     const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
     base[j] = ws.tile_base[(size_t)tile * 64 + e] + lin_tab[e];
   }
+  unsigned bj[CP], key[CP];
 #pragma unroll
   for (int j = 0; j < CP; ++j) {
     const unsigned pf = (pfw[j >> 2] >> (8 * (j & 3))) & 255u;
-    dst->b[j] = pf == 0xFFu ? kSpecInvalid : (unsigned)base[j] + pf;
+    bj[j] = pf == 0xFFu ? kSpecInvalid : (unsigned)base[j] + pf;
+    key[j] = (bj[j] << 4) | (unsigned)j;
   }
+  const unsigned guess = GUESS ? smallest_k_slots<CP, KK>(key, k) : 0u;
+#pragma unroll
+  for (int j = 0; j < CP; ++j) dst->b[j] = bj[j] | (((guess >> j) & 1u) << 31);
 }
 
 // Runs the window evaluation from flexible token 0.  All four waves call it.  Returns
 // (to every wave) the number of flexible tokens decided; wave 0 leaves the flexible
 // choices so far in `gflex` (lane = expert) and the bits of the unfinished output
 // word in `hist`.  KK = k when known at compile time, else 0.
-template <int CP, int KK>
+template <int CP, int KK, bool GUESS>
 __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
                          int wave, int lane, int lin, int& gflex, unsigned& hist) {
   nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
@@ -497,8 +507,8 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const Rout
   __syncthreads();
   const bool producer = wave != 0;
   if (producer) {
-    spec_fill<CP>(ring, 0, wave - 1, nflex_tok, ws, lin_tab, lane);
-    spec_fill<CP>(ring, 1, wave - 1, nflex_tok, ws, lin_tab, lane);
+    spec_fill<CP, KK, GUESS>(ring, 0, wave - 1, nflex_tok, ws, lin_tab, lane, k);
+    spec_fill<CP, KK, GUESS>(ring, 1, wave - 1, nflex_tok, ws, lin_tab, lane, k);
   }
   __syncthreads();
 
@@ -519,13 +529,17 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const Rout
   int pn = 0, w = 0, gflushed = 0;
   int sweeps = 0, done_mark = 0, total_sweeps = 0;
   bool bail = false;
+  // First guesses pay where whole windows retire at once (tokens that rarely compete);
+  // where a sweep ends at an early conflict anyway they only add their insertion.  They
+  // are used while the last run of sweeps retired more than kSpecGuessProgress tokens.
+  bool guess_on = GUESS;
   int decided = 0;
   const unsigned long long lane_bit = 1ull << lane, lb = lanes_below(lane);
 
   const int nep = (nflex_tok + kSpecSeg - 1) / kSpecSeg;
   for (int ep = 0; ep < nep; ++ep) {
     if (producer) {
-      spec_fill<CP>(ring, ep + 2, wave - 1, nflex_tok, ws, lin_tab, lane);
+      spec_fill<CP, KK, GUESS>(ring, ep + 2, wave - 1, nflex_tok, ws, lin_tab, lane, k);
     } else {
       const int avail = min(nflex_tok, (ep + 2) * kSpecSeg);
       const int target = min(nflex_tok, (ep + 1) * kSpecSeg);
@@ -533,22 +547,38 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const Rout
         const int head = done & 63;
         // this lane's token of the window [done, done + 64)
         const int f_lane = done + ((lane - head) & 63);
-        if (f_lane < avail && cur_f != f_lane) {
+        const bool enters = f_lane < avail && cur_f != f_lane;
+        if (enters) {
           ridx += 64;
           ridx = ridx >= kSpecRing ? ridx - kSpecRing : ridx;
           const SpecTok<CP>* src = &ring[ridx];
           const uint4 ids = src->ids;
           const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
+          sel = 0;
 #pragma unroll
           for (int j = 0; j < CP; ++j) {
             ex[j] = (idw[j >> 2] >> (8 * (j & 3))) & 255;
-            b[j] = src->b[j];
+            b[j] = src->b[j];  // (bit 31, the guess, drops out of the key's shift below)
+          }
+          if (GUESS && guess_on) {
+#pragma unroll
+            for (int j = 0; j < CP; ++j) sel |= (b[j] >> 31) << j;  // the producer's first guess
           }
           cur_f = f_lane;
-          sel = 0;
         }
         const bool valid = cur_f == f_lane;
         if (!valid) sel = 0;
+        if (GUESS && guess_on && __builtin_amdgcn_ballot_w64(enters) != 0ull) {
+          // the guesses join the masks before anybody counts (the lane's bit is clear:
+          // the token that held the lane took its bits along when it retired)
+          if (enters) {
+#pragma unroll
+            for (int j = 0; j < CP; ++j)
+              if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
+          }
+          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+          __builtin_amdgcn_wave_barrier();
+        }
         const unsigned long long hb = lanes_below(head);
         const unsigned long long earlier = lane >= head ? (lb & ~hb) : (~hb | lb);
         unsigned key[CP];
@@ -570,32 +600,39 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const Rout
             if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
         }
         sel = newsel;
-        // tokens up to the first changed one are final (at most 32 per sweep: a token
-        // needs a sweep to get a tentative choice, so more is rare)
+        // tokens up to the first changed one are final
         const unsigned long long rot = rotr64(bal, head);
         const int q = rot ? __builtin_ctzll(rot) : 64;
-        const int fin = min(min(q + 1, avail - done), 32);
+        // (without guesses more than 32 is rare: a token needs a sweep to get a choice)
+        const int fin = min(min(q + 1, avail - done), GUESS ? 64 : 32);
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __builtin_amdgcn_wave_barrier();
         {  // lane = expert
-          const unsigned long long finmask = rotl64((1ull << fin) - 1ull, head);
-          const unsigned long long mk = M[lane].mask;
-          const unsigned long long fbits = mk & finmask;
-          G += __builtin_popcountll(fbits);
-          M[lane].mask = mk & ~finmask;
+          unsigned long long mk = M[lane].mask;
+          // tokens done + off .. + part - 1 (part <= 32: what the output takes at a time)
+          auto retire = [&](int off, int part) {
+            const int h2 = (head + off) & 63;
+            const unsigned long long finmask = rotl64((1ull << part) - 1ull, h2);
+            const unsigned long long fbits = mk & finmask;
+            G += __builtin_popcountll(fbits);
+            mk &= ~finmask;
+            const unsigned ob = (unsigned)rotr64(fbits, h2);  // bit i: token done + off + i
+            pend |= (unsigned long long)ob << pn;             // pn < 32 bits were held
+            pn += part;
+            if (pn >= 32) {
+              const unsigned word = (unsigned)pend;
+              gflushed += __builtin_popcount(word);
+              ws.chain_bits[(size_t)w * 64 + lane] = word;
+              ws.chain_cum[(size_t)(w + 1) * 64 + lane] = gflushed;
+              pend >>= 32;
+              pn -= 32;
+              ++w;
+            }
+          };
+          retire(0, min(fin, 32));
+          if (GUESS && fin > 32) retire(32, fin - 32);
+          M[lane].mask = mk;
           M[lane].G = G;
-          const unsigned ob = (unsigned)rotr64(fbits, head);  // bit i: token done + i
-          pend |= (unsigned long long)ob << pn;               // pn < 32 bits were held
-          pn += fin;
-          if (pn >= 32) {
-            const unsigned word = (unsigned)pend;
-            gflushed += __builtin_popcount(word);
-            ws.chain_bits[(size_t)w * 64 + lane] = word;
-            ws.chain_cum[(size_t)(w + 1) * 64 + lane] = gflushed;
-            pend >>= 32;
-            pn -= 32;
-            ++w;
-          }
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __builtin_amdgcn_wave_barrier();
@@ -608,6 +645,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const Rout
               done * kSpecCheckSweeps < spec_min_progress(CP) * total_sweeps &&
               nflex_tok - done > 2 * kSpecSeg)
             bail = true;
+          if (GUESS) guess_on = done - done_mark >= kSpecGuessProgress;
           sweeps = 0;
           done_mark = done;
         }
@@ -802,15 +840,19 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   int decided = 0;
   unsigned hist0 = 0;
   if (use_spec) {
+    // First guesses (GUESS) where tokens rarely compete: many experts per candidate.
+    // With few experts every sweep ends at an early conflict and they only cost.
+#define LASER_SPEC_WALK(CP_, KK_)                                                                   \
+  (a.E >= 4 * CP_ ? spec_walk<CP_, KK_, true>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
+                  : spec_walk<CP_, KK_, false>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0))
     if (a.c <= 4) {
-      decided = a.k == 2 ? spec_walk<4, 2>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0)
-                         : spec_walk<4, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+      decided = a.k == 2 ? LASER_SPEC_WALK(4, 2) : LASER_SPEC_WALK(4, 0);
     } else if (a.c <= 8) {
-      decided = a.k == 6 ? spec_walk<8, 6>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0)
-                         : spec_walk<8, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+      decided = a.k == 6 ? LASER_SPEC_WALK(8, 6) : LASER_SPEC_WALK(8, 0);
     } else {
-      decided = spec_walk<16, 0>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0);
+      decided = LASER_SPEC_WALK(16, 0);
     }
+#undef LASER_SPEC_WALK
   }
   if (decided < nflex_tok) {
     // the rest (or everything) one token after the other

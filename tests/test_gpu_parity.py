@@ -95,6 +95,21 @@ def test_window_chain_sizes(T, E, k, c):
     u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"window T{T} E{E} k{k} c{c}")
 
 
+@pytest.mark.parametrize("T", [257, 577, 2000])
+@pytest.mark.parametrize("E,k,c", [(64, 2, 4), (64, 3, 4), (64, 5, 8), (64, 6, 16), (16, 6, 8), (15, 2, 4)])
+def test_window_chain_variants(T, E, k, c):
+    """The window evaluation exists with and without first guesses (chosen by the number
+    of experts per candidate) and for 4, 8 and 16 candidates, k fixed at compile time or
+    not: every variant, with unrelated candidate sets (windows retire whole) and with
+    scores flat enough that neighbours compete."""
+    u = _util()
+    rng = np.random.default_rng(T * 11 + E + c)
+    for scale in (1.0, 0.05):
+        logits = wl.random_logits(T + E + c, T, E, kind="normal", scale=scale)
+        loads_in = rng.integers(0, 30, size=E).astype(np.int32)
+        u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"window variant T{T} E{E} k{k} c{c} s{scale}")
+
+
 @pytest.mark.parametrize("E,k,c,T1,T2", [(64, 6, 8, 3001, 3000), (8, 2, 4, 1237, 5000),
                                          (64, 6, 12, 700, 2500), (16, 4, 8, 5000, 0)])
 def test_window_chain_gives_way_to_sequential(E, k, c, T1, T2):
