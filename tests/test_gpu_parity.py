@@ -293,6 +293,22 @@ def test_few_flexible_tokens(T, E, k, c, where):
     assert np.array_equal(np.where(ref["cstar"] > k)[0], np.array(sorted(where)))
 
 
+@pytest.mark.parametrize("T,E,k,c", [(1, 1, 1, 1), (100, 1, 1, 1), (300, 2, 2, 2), (64, 16, 16, 16),
+                                     (1000, 16, 15, 16), (129, 64, 16, 16), (5000, 64, 1, 16), (70, 3, 3, 3)])
+def test_limits_of_the_parameters(T, E, k, c):
+    """One expert, every expert chosen, the largest k and c, counters near the 2^27
+    limit -- from logits and through the bf16 gate."""
+    u = _util()
+    rng = np.random.default_rng(T + 100 * E + k)
+    for eps, tfix in [(2.0, 1e-30), (0.5, 0.5)]:
+        z = (rng.standard_normal((T, E)) * 0.5).astype(np.float32)
+        loads = rng.integers(0, 2 ** 26, size=E).astype(np.int32)
+        label = f"limits T{T} E{E} k{k} c{c} eps{eps}"
+        u.check_from_logits(z, k, c, eps, tfix, loads, label=label)
+        h, w = wl.make_gate(rng, T, 64, E, wl.DTYPE_BF16)
+        u.check_route(h, w, wl.DTYPE_BF16, k, c, eps, tfix, loads, label="bf16 " + label)
+
+
 def test_extreme_logits():
     """Scores that underflow the clamp, huge spreads, and all-equal rows."""
     u = _util()
