@@ -242,7 +242,7 @@ __global__ __launch_bounds__(64 * kRandomWaves) void random_resample_kernel(cons
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int t = tile * kTile + lane;
   const bool live = t < a.T;
-  const int E = a.E, k = a.k, c = a.c;
+  const int E = a.E, c = a.c;
   const int32_t* pool = a.pool_in_ws ? ws.pool : a.st_pool;
 
   const int cst = live ? (int)ws.rec_cstar[t] : 0;
