@@ -66,25 +66,39 @@ def cpu_baseline(name, preset, budget_s):
     import oracle
     from synth import workloads as wl
     s = wl.SHAPES[name]
-    spent, tokens, layers_done = 0.0, 0, 0
+    spent, spent_route, tokens, layers_done = 0.0, 0.0, 0, 0
     expanded, flexible = [], []
     for layer in range(s.layers):
         inp = wl.layer_inputs(name, layer)
         eps, tfix = wl.thresholds(name, layer, preset)
         t0 = time.perf_counter()
-        out = oracle.route_from_hidden(inp["hidden"], inp["w_gate"], s.dtype, s.k, s.c, eps, tfix,
-                                       inp["loads_in"])
-        spent += time.perf_counter() - t0
+        z = oracle.gate(inp["hidden"], inp["w_gate"], s.dtype).astype(np.float32)
+        t1 = time.perf_counter()
+        out = oracle.route(z, s.k, s.c, eps, tfix, inp["loads_in"])
+        t2 = time.perf_counter()
+        spent += t2 - t0
+        spent_route += t2 - t1
         tokens += s.T
         layers_done += 1
         expanded.append(float(out["expanded"].mean()))
         flexible.append(float((out["cstar"] > s.k).mean()))
         if spent >= budget_s:
             break
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return {
         "value": tokens / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
         "sample": f"layers 0..{layers_done - 1} of the {name} workload ({tokens} tokens), gate + "
                   f"routing + dispatch, {spent:.1f} s on one host core",
+        "routing_and_dispatch_only_tokens_per_s": tokens / spent_route,
+        "host": {"cpu": cpu_model, "logical_cpus": os.cpu_count()},
     }, float(np.mean(expanded)), float(np.mean(flexible))
 
 
