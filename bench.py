@@ -257,11 +257,19 @@ def main():
         t0 = time.perf_counter()
         stats_pass()
         torch.cuda.synchronize()
+        us_stats = (time.perf_counter() - t0) * 1e6 / layers
+        # the layer summaries the thresholds are chosen from, by the library's own kernel
+        m_mean, m_q = B.laser_summary_f32(st_mass, [5, 50, 95])
+        e_mean, e_q = B.laser_summary_f32(st_ent, [50])
+        p_mean, p_q = B.laser_summary_f32(st_pool.float(), [50, 95])
         extras["route_stats"] = {
-            "us_per_layer": (time.perf_counter() - t0) * 1e6 / layers,
-            "last_layer_mean_topk_mass": float(st_mass.mean()),
-            "last_layer_mean_entropy_nats": float(st_ent.mean()),
-            "last_layer_mean_pool_size": float(st_pool.float().mean()),
+            "us_per_layer": us_stats,
+            "last_layer_mean_topk_mass": float(m_mean),
+            "last_layer_topk_mass_p5_p50_p95": [float(v) for v in m_q.cpu()],
+            "last_layer_mean_entropy_nats": float(e_mean),
+            "last_layer_median_entropy_nats": float(e_q[0]),
+            "last_layer_mean_pool_size": float(p_mean),
+            "last_layer_pool_size_p50_p95": [float(v) for v in p_q.cpu()],
         }
 
         # trimming mode RANDOM on the same inputs (the deterministic analysis with pool

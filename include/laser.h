@@ -191,6 +191,22 @@ int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, const float* pl
 int laser_percentiles(const double* values, int32_t n, const double* q, int32_t nq, double* out,
                       void* hip_stream);
 
+/*
+ * Mean and percentiles of n fp32 values on the device: a layer's per-token top-k mass
+ * or entropy from laser_route_stats, summarised the way the paper looks at the gate
+ * scores layer by layer (Observations: Layer Variability in Gate Score Distributions;
+ * Method: Parameter setting and layer-wise choices).  Percentiles as laser_percentiles
+ * (position (n-1)*q/100, linear interpolation; the order statistics are exact), the
+ * mean in fp64.  Integer statistics (pool sizes) are converted to fp32 by the caller.
+ *   values  [n] fp32, device pointer, no NaN                       in
+ *   q       [nq] fp64, HOST pointer, each in [0, 100], nq <= 16    in
+ *   mean    fp64, device pointer, or NULL                          out
+ *   out     [nq] fp64, device pointer (may be NULL if nq = 0)      out
+ * One workgroup, no scratch memory; time grows with n * nq.
+ */
+int laser_summary_f32(const float* values, int32_t n, const double* q, int32_t nq, double* mean,
+                      double* out, void* hip_stream);
+
 /* Static, NUL-terminated description of a return code (host pointer). */
 const char* laser_strerror(int code);
 

@@ -19,7 +19,7 @@ DTYPE_BF16 = 1
 TRIM_TOP = 0
 TRIM_RANDOM = 1
 
-EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance", "laser_percentiles",
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance", "laser_percentiles", "laser_summary_f32",
            "laser_strerror", "laser_profile_enable", "laser_profile_read",
            "laser_profile_event_overhead", "laser_profile_plain_read")
 
@@ -68,6 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.laser_imbalance.restype = ctypes.c_int
     lib.laser_percentiles.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), i32, vp, vp]
     lib.laser_percentiles.restype = ctypes.c_int
+    lib.laser_summary_f32.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), i32, vp, vp, vp]
+    lib.laser_summary_f32.restype = ctypes.c_int
     lib.laser_route_from_logits.argtypes = [vp, i32, i32, pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.laser_route_from_logits.restype = ctypes.c_int
     lib.laser_strerror.argtypes = [ctypes.c_int]
@@ -180,6 +182,17 @@ def laser_percentiles(values, q, stream=None):
     _check(_lib.laser_percentiles(_ptr(values), values.numel(), qa, len(qs), _ptr(out),
                                   _stream_handle(stream)))
     return out
+
+
+def laser_summary_f32(values, q, stream=None):
+    """(mean, percentiles) of a device fp32 vector: device fp64 scalar and fp64 [len(q)]."""
+    qs = [float(x) for x in q]
+    qa = (ctypes.c_double * max(len(qs), 1))(*qs)
+    mean = torch.empty((), dtype=torch.float64, device=values.device)
+    out = torch.empty(len(qs), dtype=torch.float64, device=values.device)
+    _check(_lib.laser_summary_f32(_ptr(values), values.numel(), qa, len(qs), _ptr(mean), _ptr(out),
+                                  _stream_handle(stream)))
+    return mean, out
 
 
 def laser_profile_enable(max_calls: int) -> None:

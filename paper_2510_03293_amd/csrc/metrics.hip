@@ -128,9 +128,101 @@ __global__ __launch_bounds__(kMetricThreads) void percentile_kernel(const double
   }
 }
 
+// Mean and percentiles of n fp32 values (a layer's per-token statistic): one workgroup,
+// no scratch memory.  An order statistic is found exactly by radix selection on the
+// values' order-preserving 32-bit codes, a byte at a time from the top: histogram of the
+// byte among the values that share the prefix found so far, then the bin that holds the
+// wanted rank.  The mean is a fixed-shape fp64 sum (per thread in index order, then a
+// tree), so it does not depend on anything but n.
+constexpr int kSummaryThreads = 1024;
+
+__device__ __forceinline__ unsigned order_code(float v) {  // a < b  <=>  code(a) < code(b)
+  const unsigned u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float code_value(unsigned c) {
+  return __uint_as_float((c & 0x80000000u) ? (c & 0x7FFFFFFFu) : ~c);
+}
+
+// rank-th smallest (rank in [0, n)) of the values; called by the whole workgroup
+__device__ unsigned select_code(const float* __restrict__ values, int n, int rank, unsigned* hist,
+                                unsigned* sh) {
+  unsigned prefix = 0, mask = 0;
+  int want = rank;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = threadIdx.x; i < 256; i += kSummaryThreads) hist[i] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kSummaryThreads) {
+      const unsigned c = order_code(values[i]);
+      if ((c & mask) == prefix) atomicAdd(&hist[(c >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      unsigned cum = 0;
+      int bin = 0;
+      for (; bin < 255; ++bin) {
+        if (cum + hist[bin] > (unsigned)want) break;
+        cum += hist[bin];
+      }
+      sh[0] = (unsigned)bin;
+      sh[1] = cum;
+    }
+    __syncthreads();
+    prefix |= sh[0] << shift;
+    mask |= 255u << shift;
+    want -= (int)sh[1];
+    __syncthreads();  // sh and hist are reused
+  }
+  return prefix;
+}
+
+__global__ __launch_bounds__(kSummaryThreads) void summary_f32_kernel(const float* __restrict__ values, int n,
+                                                                      const PercentileArgs pa,
+                                                                      double* __restrict__ mean,
+                                                                      double* __restrict__ out) {
+  __shared__ unsigned hist[256], sh[2];
+  __shared__ double part[kSummaryThreads];
+  if (mean != nullptr) {
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n; i += kSummaryThreads) acc += (double)values[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = kSummaryThreads / 2; s >= 1; s >>= 1) {
+      if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) *mean = part[0] / (double)n;
+  }
+  for (int i = 0; i < pa.nq; ++i) {
+    const double h = (double)(n - 1) * pa.q[i] / 100.0;
+    int lo = (int)h;
+    lo = lo > n - 1 ? n - 1 : lo;
+    const int hi = lo + 1 < n ? lo + 1 : lo;
+    const double xlo = (double)code_value(select_code(values, n, lo, hist, sh));
+    const double xhi = hi == lo ? xlo : (double)code_value(select_code(values, n, hi, hist, sh));
+    if (threadIdx.x == 0) out[i] = xlo + (h - (double)lo) * (xhi - xlo);
+  }
+}
+
 }  // namespace laser
 
 using namespace laser;
+
+extern "C" int laser_summary_f32(const float* values, int32_t n, const double* q, int32_t nq,
+                                 double* mean, double* out, void* hip_stream) {
+  if (n < 1 || nq < 0 || nq > kMaxPercentiles) return LASER_E_RANGE;
+  if (!values || (nq > 0 && (!q || !out))) return LASER_E_NULL;
+  if (nq == 0 && !mean) return LASER_OK;
+  PercentileArgs pa;
+  pa.nq = nq;
+  for (int i = 0; i < kMaxPercentiles; ++i) {
+    pa.q[i] = i < nq ? q[i] : 0.0;
+    if (i < nq && !(q[i] >= 0.0 && q[i] <= 100.0)) return LASER_E_RANGE;
+  }
+  hipLaunchKernelGGL(summary_f32_kernel, dim3(1), dim3(kSummaryThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), values, n, pa, mean, out);
+  return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;
+}
 
 extern "C" int laser_percentiles(const double* values, int32_t n, const double* q, int32_t nq,
                                  double* out, void* hip_stream) {

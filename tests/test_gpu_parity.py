@@ -560,6 +560,25 @@ def test_percentiles_on_device(n):
         B.laser_percentiles(torch.zeros(4, dtype=torch.float64, device="cuda"), [101.0])
 
 
+@pytest.mark.parametrize("n", [1, 2, 63, 1000, 16384, 100001])
+def test_layer_summary_on_device(n):
+    """Mean and percentiles of a layer's per-token statistic: order statistics exact
+    (equal to the oracle's percentiles of the same values, bit for bit), the mean to
+    fp64 rounding.  Negative values, repeated values, both zeros."""
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    rng = np.random.default_rng(n)
+    x = np.round(rng.standard_normal(n) * 3, 1).astype(np.float32)
+    if n > 2:
+        x[0], x[1] = 0.0, -0.0
+    q = [0, 5, 25, 50, 75, 95, 99.9, 100]
+    mean, got = B.laser_summary_f32(torch.from_numpy(x).cuda(), q)
+    ref = oracle.percentiles(x.astype(np.float64), q)
+    assert np.array_equal(np.abs(got.cpu().numpy()), np.abs(ref))      # (-0 and +0 are one value)
+    assert abs(float(mean) - float(x.astype(np.float64).mean())) <= 1e-12 * max(1.0, float(np.abs(x).max()))
+
+
 def test_fp32_gate_ragged():
     u = _util()
     rng = np.random.default_rng(17)
