@@ -238,6 +238,17 @@ def main():
                           buf.workspace, stream)
         lo_k = loads.cpu().numpy().astype(np.float64)
         extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
+        # the load-only baseline (scores ignored: every token takes the load-aware branch
+        # with all experts as candidates) needs c = E, which the kernels carry up to 16
+        if E <= 16:
+            p_lo = B.make_params(k, E, 2.0, 1e-30, dtype=s.dtype)
+            loads.zero_()
+            for layer in range(layers):
+                B.laser_route(hidden[layer], wgate[layer], T, H, E, p_lo, loads_of[layer],
+                              buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
+                              buf.workspace, stream)
+            lo_l = loads.cpu().numpy().astype(np.float64)
+            extras["max_over_mean_load_loadonly"] = float(np.mean(lo_l.max(1) / lo_l.mean(1)))
 
         # the statistics pass (laser_route_stats): cost beside the plain call, and what
         # the synthetic gate scores look like (layer means of per-token values)
