@@ -121,7 +121,7 @@ def main():
     args = ap.parse_args()
 
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus above 1 is not supported", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus above 1 is not supported", file=sys.stderr)
         sys.exit(2)
 
     import torch
