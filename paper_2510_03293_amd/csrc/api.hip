@@ -92,17 +92,22 @@ __global__ void spin_kernel(long long ticks) {
 // kernels' bandwidth is compared with.  The xor keeps the loads alive; the store
 // never happens for real data streams short of a 2^-32 coincidence per thread, and
 // `sink` is a valid device word in any case.
-__global__ __launch_bounds__(256) void plain_read_kernel(const uint4* __restrict__ p, size_t n16,
+typedef unsigned int stream_u4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void plain_read_kernel(const uint4* __restrict__ p16, size_t n16,
                                                          unsigned* __restrict__ sink) {
+  // (non-temporal loads, as the gate kernel uses for the rows it streams)
+  const stream_u4* p = reinterpret_cast<const stream_u4*>(p16);
   const size_t stride = (size_t)gridDim.x * 256;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   unsigned x = 0;
   for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+    const stream_u4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + stride),
+                    c = __builtin_nontemporal_load(p + i + 2 * stride),
+                    d = __builtin_nontemporal_load(p + i + 3 * stride);
     x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
   for (; i < n16; i += stride) {
-    const uint4 a = p[i];
+    const stream_u4 a = __builtin_nontemporal_load(p + i);
     x ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   if (x == 0x9E3779B9u) *sink = x;

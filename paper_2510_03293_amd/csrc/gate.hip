@@ -46,13 +46,16 @@ constexpr int kGateLdsBytes =
 __device__ __forceinline__ u32x4 load_global_16(const unsigned char* p) {
   return *(global_u4_ptr)(p);
 }
+__device__ __forceinline__ u32x4 load_global_16_stream(const unsigned char* p) {
+  return __builtin_nontemporal_load((global_u4_ptr)(p));
+}
 
 // GH / GW: global -> registers, the hidden rows (8 loads) or the W rows (2*EB loads)
 // of one chunk.  The scheduling barriers keep the compiler from sinking the loads
 // down to their first use, which would undo the prefetch.
 #define GATE_GH(RH, KBYTES)                                                      \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_)                               \
-      RH[q_] = load_global_16(hbase + hoff[q_] + (KBYTES));                      \
+      RH[q_] = load_global_16_stream(hbase + hoff[q_] + (KBYTES));                      \
   __builtin_amdgcn_sched_barrier(0);
 #define GATE_GW(RW, KBYTES)                                                      \
   _Pragma("unroll") for (int q_ = 0; q_ < 2 * EB; ++q_)                          \
