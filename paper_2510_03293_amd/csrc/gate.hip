@@ -112,7 +112,11 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
     logits_out = logits_out != nullptr ? logits_out + (size_t)prob * logits_stride : nullptr;
   }
   const int T = a.T, E = a.E;
-  const int tile = blockIdx.x;
+  // Workgroups go to the eight XCDs in turn; an XCD then works on one contiguous eighth
+  // of the tiles (measured: up to 1.4 % on the kernel, nothing lost anywhere).
+  const int per_xcd = (int)gridDim.x >> 3;
+  const int tile = ((int)gridDim.x & 7) == 0 ? ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3)
+                                            : (int)blockIdx.x;
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
