@@ -600,6 +600,69 @@ def test_split_call_carries_loads():
     assert np.array_equal(second["loads"], whole["loads"])
 
 
+def test_calls_replayed_from_a_hip_graph():
+    """The entry points allocate nothing, never synchronise and clear their own flags
+    with kernels, so a sequence of calls can be captured into a HIP graph (a decode loop
+    does that).  Three decode-sized calls with carried loads are captured once and
+    replayed on new inputs several times, with eager work in between; every replay must
+    give exactly what the eager calls give."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    s = wl.SHAPES["decode"]
+    w = wl.decode_gate_weight()
+    wd = u.to_device(w)
+    eps, tfix = wl.thresholds("decode", 0, "paper")
+    params = B.make_params(s.k, s.c, eps, tfix, dtype=s.dtype)
+    steps = 3
+    hid = [torch.empty((s.T, s.H), dtype=torch.bfloat16, device="cuda") for _ in range(steps)]
+    bufs = [B.RouteBuffers(s.T, s.H, s.E, params) for _ in range(steps)]
+    loads = torch.zeros(s.E, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def enqueue(stream):
+        for i in range(steps):
+            B.laser_route(hid[i], wd, s.T, s.H, s.E, params, loads, bufs[i].expert_ids, bufs[i].weights,
+                          bufs[i].permutation, bufs[i].expert_offsets, None, bufs[i].workspace, stream)
+
+    def fill(rep):
+        for i in range(steps):
+            hid[i].copy_(u.to_device(wl.layer_inputs("decode", 10 * rep + i, w=w)["hidden"]))
+        loads.zero_()
+
+    fill(0)
+    with torch.cuda.stream(side):
+        enqueue(side)                       # warm-up outside the capture (per-kernel set-up happens here)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    fill(0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(side)
+    torch.cuda.synchronize()
+    for rep in range(1, 5):
+        fill(rep)
+        torch.cuda.synchronize()
+        enqueue(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        want = [(b.expert_ids.clone(), b.weights.clone(), b.permutation.clone(), b.expert_offsets.clone())
+                for b in bufs]
+        want_loads = loads.clone()
+        for b in bufs:                      # eager work between the replays; outputs wiped
+            b.expert_ids.fill_(-1)
+            b.permutation.fill_(-1)
+        fill(rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for b, (ids, wts, perm, offs) in zip(bufs, want):
+            assert torch.equal(b.expert_ids, ids) and torch.equal(b.permutation, perm)
+            assert torch.equal(b.weights.view(torch.int32), wts.view(torch.int32))
+            assert torch.equal(b.expert_offsets, offs)
+        assert torch.equal(loads, want_loads), f"replay {rep}"
+    assert int(loads.sum()) == steps * s.T * s.k
+
+
 def test_run_to_run_determinism():
     u = _util()
     inp = wl.layer_inputs("deepseek", 1, T=2048)
