@@ -490,14 +490,22 @@ __device__ __forceinline__ void spec_fill(SpecTok<CP>* ring, int seg, int half, 
 // (to every wave) the number of flexible tokens decided; wave 0 leaves the flexible
 // choices so far in `gflex` (lane = expert) and the bits of the unfinished output
 // word in `hist`.  KK = k when known at compile time, else 0.
+// LDS of the window evaluation beside the ring (one copy for all compiled variants).
+struct SpecShared {
+  SpecExp M[64];
+  int lin_tab[64];
+  int sh_done[2], sh_bail[2];  // by segment parity: written before, read after a barrier
+};
+
 template <int CP, int KK, bool GUESS>
-__device__ __forceinline__ int spec_walk(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
-                         int wave, int lane, int lin, int& gflex, unsigned& hist) {
+__device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex_tok, const RouteArgs& a,
+                         const Workspace& ws, int wave, int lane, int lin, int& gflex, unsigned& hist) {
   nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
   SpecTok<CP>* ring = reinterpret_cast<SpecTok<CP>*>(lds);
-  __shared__ SpecExp M[64];
-  __shared__ int lin_tab[64];
-  __shared__ int sh_done[2], sh_bail[2];  // by segment parity: written before, read after a barrier
+  SpecExp* M = sp.M;
+  int* lin_tab = sp.lin_tab;
+  int* sh_done = sp.sh_done;
+  int* sh_bail = sp.sh_bail;
   const int k = KK > 0 ? KK : a.k;
   if (wave == 0) {
     M[lane].mask = 0ull;
@@ -675,6 +683,7 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
   __shared__ int wave_flex[kChainWaves], wave_tok[kChainWaves];
+  __shared__ SpecShared spec_sh;
   // (as a scalar: branches on the wave number are then uniform for the compiler, and
   // values carried around them stay in scalar registers)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -843,8 +852,8 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     // First guesses (GUESS) where tokens rarely compete: many experts per candidate.
     // With few experts every sweep ends at an early conflict and they only cost.
 #define LASER_SPEC_WALK(CP_, KK_)                                                                   \
-  (a.E >= 4 * CP_ ? spec_walk<CP_, KK_, true>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
-                  : spec_walk<CP_, KK_, false>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0))
+  (a.E >= 4 * CP_ ? spec_walk<CP_, KK_, true>(lds, spec_sh, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
+                  : spec_walk<CP_, KK_, false>(lds, spec_sh, nflex_tok, a, ws, wave, lane, lin, gflex, hist0))
     if (a.c <= 4) {
       decided = a.k == 2 ? LASER_SPEC_WALK(4, 2) : LASER_SPEC_WALK(4, 0);
     } else if (a.c <= 8) {
