@@ -600,6 +600,22 @@ def test_split_call_carries_loads():
     assert np.array_equal(second["loads"], whole["loads"])
 
 
+@pytest.mark.parametrize("T", [1, 37, 64])
+@pytest.mark.parametrize("H,E,k,c", [(2048, 64, 6, 8), (4096, 33, 2, 4), (512, 64, 4, 16), (1000, 40, 6, 8)])
+def test_single_tile_calls(T, H, E, k, c):
+    """Calls of at most 64 tokens (one tile; one chain and one finishing workgroup):
+    every regime of the chain -- no flexible token, a few, all of them -- with loads
+    carried over, for each variant of the gate kernel's main loop."""
+    u = _util()
+    rng = np.random.default_rng(T + H + E)
+    loads = rng.integers(0, 40, size=E).astype(np.int32)
+    for eps, tfix in [(1e-6, 1.0), (0.6, 0.3), (2.0, 1e-30)]:
+        hidden, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16, bias=np.linspace(-1.0, 1.0, E))
+        gpu, ref = u.check_route(hidden, w, wl.DTYPE_BF16, k, c, eps, tfix, loads,
+                                 label=f"single tile T{T} H{H} E{E} eps{eps}")
+        loads = ref["loads"].astype(np.int32)
+
+
 def test_calls_replayed_from_a_hip_graph():
     """The entry points allocate nothing, never synchronise and clear their own flags
     with kernels, so a sequence of calls can be captured into a HIP graph (a decode loop
