@@ -881,7 +881,7 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
   const unsigned long long fm = pro.fm;
 
   bool any_flex = false;
-  if (!self) {
+  if (__builtin_expect(!self, 0)) {
     if (!poll_flag(&ws.status[kStatusPhase], 1)) {
       ws.status[kStatusError] = 1;
       return;
@@ -899,7 +899,7 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
   const int f0 = any_flex ? load_published(&ws.flex_tok_base[tile]) : 0;
   {
     int bef;
-    if (self) {
+    if (__builtin_expect(self, 1)) {
       bef = own_offsets[lane] + own_base[lane];
     } else {
       bef = (lane < a.E ? load_published(&expert_offsets[lane]) : 0) +
@@ -913,7 +913,7 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
     fl->before[lane] = bef;
   }
 
-  if (cstar > 0) {
+  if (__builtin_expect(cstar > 0, 0)) {
     const int f = f0 + __builtin_popcountll(fm & lanes_below(lane));
     const unsigned* cw = ws.chain_bits + (size_t)(f >> 5) * 64;
     // (called twice so that each copy knows its address space: LDS or memory)
@@ -957,7 +957,7 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
   // (the masks came from the analysis with the non-flexible tokens in them)
-  if (cstar > 0)
+  if (__builtin_expect(cstar > 0, 0))
     for (int j = 0; j < k; ++j) atomicOr(&fl->mask64[fl->ids[lane][j]], 1ull << lane);
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
@@ -1304,13 +1304,13 @@ __device__ __forceinline__ void tail_role(int block, uint8_t* tail_lds, const Ro
 #pragma unroll
   for (int j = 0; j < kChainWaves - 1; ++j)
     wg_cnt[j] = (small && j < wave && t0 + j < a.ntiles) ? ws.tile_fixed_cnt[(size_t)(t0 + j) * 64 + lane] : 0;
-  if (small) {
+  if (__builtin_expect(small, 1)) {
     unsigned long long fm_mine = 0ull;
     self_prefix(t0, a, ws, sh_before, sh_all, sh_anyflex, fm_mine);
     if (tile < a.ntiles) finish_commit(fl, pro, a.k);
     __syncthreads();
     self = (sh_anyflex[0] | sh_anyflex[1] | sh_anyflex[2] | sh_anyflex[3]) == 0;
-    if (self) {
+    if (__builtin_expect(self, 1)) {
       int before = 0, all = 0;
       for (int w = 0; w < kChainWaves; ++w) {
         before += sh_before[w][lane];
@@ -1333,7 +1333,7 @@ __device__ __forceinline__ void tail_role(int block, uint8_t* tail_lds, const Ro
     }
     __syncthreads();
     // a handful of flexible tokens: resolved here, by every workgroup for itself
-    if (!self && a.ntiles <= kFastMaxTiles) {
+    if (__builtin_expect(!self && a.ntiles <= kFastMaxTiles, 0)) {
       fast_n = finish_fast(block, fs, fm_mine, wg_cnt, sh_before, sh_all, own_base, own_offsets, a, ws, loads_inout,
                            expert_offsets);
       self = fast_n > 0;
