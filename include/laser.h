@@ -24,6 +24,9 @@
  *   - Scores are ordered by logit, equal logits by lower expert index first.
  *     That one order decides top-k membership, trimming to c, the score tie-break
  *     of the load sort, and the order in which a token's k experts are listed.
+ *   - A workspace belongs to one call at a time: calls that share a workspace (or any
+ *     output buffer) must be ordered, e.g. by being enqueued on one stream.  Calls with
+ *     their own workspaces and outputs may run side by side on different streams.
  *   - Inputs must be finite; loads_inout[e] + T must stay below 2^27.
  *   - Limits: 1 <= k <= c <= min(E, 16); E <= 64; bf16 needs H % 8 == 0 and
  *     16-byte aligned hidden / w_gate; fp32 needs H % 4 == 0.
