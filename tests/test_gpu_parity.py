@@ -679,6 +679,38 @@ def test_calls_replayed_from_a_hip_graph():
     assert int(loads.sum()) == steps * s.T * s.k
 
 
+def test_calls_side_by_side_on_two_streams():
+    """Calls with their own workspaces and outputs share nothing: two streams, each
+    running its own sequence of layers at the same time, give what one stream gives."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    T, H, E, k, c = 3000, 512, 64, 6, 8
+    rng = np.random.default_rng(31)
+    params = B.make_params(k, c, 2.0, 1e-30, dtype=wl.DTYPE_BF16)      # every token on the chain
+    prob = []
+    for i in range(4):
+        h, w = wl.make_gate(rng, T, H, E, wl.DTYPE_BF16, bias=np.linspace(-1.0, 1.0, E))
+        prob.append((u.to_device(h), u.to_device(w)))
+
+    def run(streams):
+        bufs = [B.RouteBuffers(T, H, E, params) for _ in prob]
+        loads = [torch.zeros(E, dtype=torch.int32, device="cuda") for _ in prob]
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for i, (hd, wd) in enumerate(prob):
+                st = streams[i % len(streams)]
+                B.laser_route(hd, wd, T, H, E, params, loads[i], bufs[i].expert_ids, bufs[i].weights,
+                              bufs[i].permutation, bufs[i].expert_offsets, None, bufs[i].workspace, st)
+        torch.cuda.synchronize()
+        return [(b.expert_ids.clone(), b.permutation.clone(), l.clone()) for b, l in zip(bufs, loads)]
+
+    one = run([torch.cuda.current_stream()])
+    two = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    for (i1, p1, l1), (i2, p2, l2) in zip(one, two):
+        assert torch.equal(i1, i2) and torch.equal(p1, p2) and torch.equal(l1, l2)
+
+
 def test_run_to_run_determinism():
     u = _util()
     inp = wl.layer_inputs("deepseek", 1, T=2048)
