@@ -454,6 +454,10 @@ def test_batched_call_equals_single_calls(nb, T, H, E, k, c, dtype, eps, tfix):
         single = u.run_route(hs[b], ws_[b], dtype, k, c, eps, tfix, ls[b])
         for key in ("logits", "expert_ids", "weights", "permutation", "expert_offsets", "loads"):
             assert np.array_equal(got[b][key], single[key]), f"{label}: {key} differs from the single call"
+    blind = u.run_route_batched(hs, ws_, dtype, k, c, eps, tfix, ls, want_logits=False)   # no logits buffer
+    for b in range(nb):
+        for key in ("expert_ids", "weights", "permutation", "expert_offsets", "loads"):
+            assert np.array_equal(got[b][key], blind[b][key]), f"problem {b}: {key} differs without a logits buffer"
 
 
 def test_batched_call_random_trimming_and_no_logits():
