@@ -83,3 +83,31 @@ def test_argument_errors_before_any_device_work(B):
 def test_binding_raises_on_error(B):
     with pytest.raises(B.LaserError):
         B._check(-4)
+
+
+def test_header_is_plain_c_and_links(B, tmp_path):
+    """The header compiles as C99 on its own, and a C program that includes it links
+    against the library and calls the host-only entry points (no GPU needed)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_laser.c"
+    src.write_text(
+        '#include "laser.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '  laser_params_t p = {0};\n'
+        '  p.struct_bytes = (uint32_t)sizeof p; p.k = 6; p.c = 8; p.eps_high = 0.4f; p.t_fix = 0.8f;\n'
+        '  p.trim_mode = LASER_TRIM_TOP; p.renormalize = 1; p.dtype = LASER_DTYPE_BF16;\n'
+        '  printf("%zu %s %d\\n", laser_workspace_bytes(16384, 2048, 64, &p), laser_strerror(LASER_E_WORKSPACE),\n'
+        '         laser_route(0, 0, 64, 2048, 64, &p, 0, 0, 0, 0, 0, 0, 0, 0, 0));\n'
+        '  return 0;\n'
+        '}\n')
+    exe = tmp_path / "use_laser"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-llaser_route", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == B.laser_workspace_bytes(16384, 2048, 64, B.make_params(6, 8, 0.4, 0.8))
+    assert out[-1] == "-1"                     # NULL pointers are refused before any device work
