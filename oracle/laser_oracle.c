@@ -7,14 +7,14 @@
  * What it computes (paper: section "The Method", appendix "Pseudo Code",
  * Algorithm 1 "per token, per layer"):
  *   gate projection   z[t,e] = sum_h hidden[t,h] * W[e,h]            (fp64)
- *   scores            s = softmax(z)        ("s_i >= 0, sum_i s_i = 1")
+ *   scores            s = softmax(z)        (non-negative, summing to one)
  *   top-k mass        M_k = s_(1) + ... + s_(k)
  *   expansion rule    M_k >= eps_high  ->  A = top-k, stop
  *   candidate pool    T = { i : s_i >= t_fix * s_(1) }  union  top-k
  *   trimming (TOP)    Cand = the c* = min(c, |T|) highest-scoring members of T
  *   final assignment  sort Cand by (load ascending, score descending); A = first k
  * applied to tokens 0..T-1 in index order, each expert of A getting load += 1
- * before the next token is routed (the paper's "current load" L_e; Algorithm 1
+ * before the next token is routed (the paper's current load L_e; Algorithm 1
  * itself has no update line -- this is the reading taken here), followed by the
  * token-to-expert dispatch tables (per-expert counts, their exclusive prefix
  * sums, and the stable counting-sort permutation of the T*k assignments).
@@ -54,8 +54,8 @@ static double bf16_to_double(uint16_t b) {
 }
 
 /* Gate function: the learned linear map from a token's hidden state to one
- * logit per expert (Introduction: "a lightweight gating network produces a score
- * distribution over experts").  dtype 0 = fp32 inputs, 1 = bf16 bit patterns.
+ * logit per expert (Introduction: the small gating network whose output is the score
+ * distribution over experts).  dtype 0 = fp32 inputs, 1 = bf16 bit patterns.
  * hidden [T,H] row-major, w [E,H] row-major, logits [T,E] fp64. */
 int laser_oracle_gate(const void* hidden, const void* w, int32_t T, int32_t H,
                       int32_t E, int32_t dtype, double* logits) {
@@ -122,8 +122,9 @@ float laser_oracle_tree_sum(const float* v, int32_t n) {
 }
 
 /* Descending order of experts by logit, equal logits by lower index first: the one
- * total order used wherever the paper says "s_(1) >= s_(2) >= ...", "highest
- * scores" or "tiebreak: descending s_e".  Softmax is monotone, so ordering logits
+ * total order used wherever the paper orders scores: the descending order statistics,
+ * the highest-scoring pool members, the score tie-break of the load sort (Method;
+ * Algorithm 1).  Softmax is monotone, so ordering logits
  * orders scores, without merging scores that round to the same value. */
 static void order_desc_f32(const float* z, int32_t E, int32_t* ord) {
   for (int32_t i = 0; i < E; ++i) ord[i] = i;
@@ -145,7 +146,8 @@ static void order_desc_f64(const double* z, int32_t E, int32_t* ord) {
   }
 }
 
-/* "StableSortByLoad(Cand; L)": primary key ascending load, ties by position in the
+/* The stable sort of the working set by load (Algorithm 1, final assignment; Method:
+ * Final assignment): primary key ascending load, ties by position in the
  * score-descending candidate list; returns the first k in `chosen` as positions
  * into cand[], then re-listed in score order (the output lists A by descending
  * score). */
@@ -169,7 +171,7 @@ static void pick_least_loaded(const int32_t* cand, int32_t cstar, int32_t k,
 }
 
 /* Dispatch tables from the final assignment (the paper only says tokens are then
- * routed to experts "via all-to-all"; this is the index structure that move
+ * routed to experts by an all-to-all; this is the index structure that move
  * needs): counts per expert, exclusive prefix sums, and the flat assignment slots
  * t*k+j listed expert by expert, ascending slot order inside an expert. */
 static void build_dispatch(const int32_t* ids, int32_t T, int32_t k, int32_t E,
@@ -288,7 +290,7 @@ void laser_oracle_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint3
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-/* "uniformly sample c indices from the pool (without replacement)" (Algorithm 1,
+/* The uniform sample of c pool members, drawn without replacement (Algorithm 1,
  * mode RANDOM), made reproducible: the pool is the first m positions of the score
  * order; a partial Fisher-Yates shuffle of [0, m) takes, for draw i = 0..c-1, the
  * i-th 32-bit word r_i of the Philox stream with key = seed and counter =
@@ -321,8 +323,8 @@ void laser_oracle_sample_ranks(int32_t m, int32_t c, uint64_t seed, uint32_t str
 /* Algorithm 1 with mode RANDOM: as laser_oracle_route, except that a pool larger
  * than c is trimmed to a uniform sample of c of its members (positions in the score
  * order from laser_oracle_sample_ranks, token index = token_offset + t) instead of
- * its c best.  The sampled candidates are listed in score order, so "tiebreak:
- * descending score" and the output order are as before.  The top-k experts need not
+ * its c best.  The sampled candidates are listed in score order, so the score
+ * tie-break of the load sort and the output order are as before.  The top-k experts need not
  * be in the sample. */
 int laser_oracle_route_random(const float* logits, int32_t T, int32_t E, int32_t k, int32_t c,
                               float eps_high, float t_fix, int32_t renormalize,
