@@ -571,23 +571,32 @@ def test_random_trimming_against_brute_force():
     rng = np.random.default_rng(3)
     sampled_tokens = 0
     top_missing = 0
+    both_branches = [0, 0]
     for trial in range(60):
         E = int(rng.integers(4, 10))
         k = int(rng.integers(1, 4))
         c = int(rng.integers(k, min(E, k + 3) + 1))
         T = 40
         z = wl.random_logits(1000 + trial, T, E, scale=0.4)
-        eps, tfix = 0.95, 0.2
+        eps, tfix = (0.95, 0.2) if trial % 2 else (0.6, 0.5)
+        # tokens whose thresholds are not within rounding: the branch flag and the pool
+        # size then follow from a plain numpy softmax, not from the code under test
+        z = z[_margin_safe(z, k, eps, tfix)]
+        T = len(z)
         L = rng.integers(0, 3, E).astype(np.int64)
         seed, stream, off = 1234 + trial, trial % 3, 10 ** 10 * trial
         ref = oracle.route_random(z, k, c, eps, tfix, L.astype(np.int32), seed, stream, off)
-        m_all = oracle.token_stats(z, k, tfix)["pool_size"]
+        s_all = np.exp(z.astype(np.float64) - z.astype(np.float64).max(1, keepdims=True))
+        s_all /= s_all.sum(1, keepdims=True)
         for t in range(T):
             order = np.argsort(-z[t], kind="stable")
-            if not ref["expanded"][t]:
+            mass = s_all[t, order[:k]].sum()
+            expanded = not mass >= eps
+            both_branches[int(expanded)] += 1
+            if not expanded:
                 A = order[:k].tolist()
             else:
-                m = int(m_all[t])
+                m = max(k, int((s_all[t] >= tfix * s_all[t].max()).sum()))
                 if m > c:
                     ranks = oracle.sample_ranks(m, c, seed, stream, off + t).tolist()
                     sampled_tokens += 1
@@ -600,6 +609,42 @@ def test_random_trimming_against_brute_force():
             L[A] += 1
         assert np.array_equal(ref["loads"], L)
     assert sampled_tokens > 200 and top_missing > 20     # the best expert is not protected
+    assert min(both_branches) > 200
+
+
+def test_random_trimming_threshold_equalities():
+    """The two non-strict comparisons of the expansion rule under RANDOM trimming.
+    (a) Top-k mass exactly at eps_high with a pool larger than c: the token keeps its
+    top-k whatever the seed (a strict test would sample and send it to the idle experts).
+    (b) A score exactly at the cut-off belongs to the pool: with k = c = 1 the pool of two
+    is sampled, and for a seed whose (separately pinned) draw takes position 1 the token
+    goes to the second expert; a strict cut would leave a pool of one and expert 0."""
+    z = np.zeros((1, 4), np.float32)                       # four equal scores of 0.25
+    for seed in range(20):
+        out = oracle.route_random(z, 2, 3, 0.5, 0.5, np.array([7, 7, 0, 0], np.int32), seed)
+        assert out["expert_ids"].tolist() == [[0, 1]] and not out["expanded"][0]
+    zb = np.log(np.array([[1.0, 1.0, 0.5, 0.5]])).astype(np.float32)
+    picks = set()
+    for seed in range(40):
+        pos = int(oracle.sample_ranks(2, 1, seed, 0, 0)[0])
+        out = oracle.route_random(zb, 1, 1, 0.99, 1.0, np.zeros(4, np.int32), seed)
+        assert out["expert_ids"].tolist() == [[pos]], seed
+        picks.add(pos)
+    assert picks == {0, 1}
+
+
+@pytest.mark.parametrize("case", [c for c in _cases() if c["c"] >= c["E"] or
+                                  c["name"] in ("mass_equal_to_threshold", "score_equal_to_cutoff")],
+                         ids=lambda c: c["name"])
+def test_hand_cases_under_random_trimming(case):
+    """Where the pool cannot exceed c nothing is sampled, so the hand-worked results hold
+    for RANDOM trimming as they stand (Algorithm 1: both modes keep a pool of at most c)."""
+    logits = np.log(np.array(case["p"], dtype=np.float64)).astype(np.float32)
+    out = oracle.route_random(logits, case["k"], case["c"], case["eps_high"], case["t_fix"],
+                              np.array(case["loads_in"], np.int32), seed=99)
+    assert out["expert_ids"].tolist() == case["expert_ids"]
+    assert out["loads"].tolist() == case["loads_out"]
+    assert out["expanded"].tolist() == case["expanded"]
 
 
 def test_random_trimming_split_call():
@@ -612,3 +657,39 @@ def test_random_trimming_split_call():
     assert np.array_equal(b["loads"], whole["loads"])
     other = oracle.route_random(z, 2, 4, 2.0, 0.01, L0, seed=6, stream=2, token_offset=1000)
     assert not np.array_equal(other["expert_ids"], whole["expert_ids"])
+
+
+def test_oracle_runs_clean_under_sanitizers(tmp_path):
+    """The oracle compiled with -fsanitize=address,undefined, driven over the hand-worked
+    cases and over shapes at the limits of its arguments (one expert, k = E = 256, no
+    tokens): no out-of-bounds access, no undefined operation, and the hand cases still
+    come out as worked."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    lines = []
+    for c in _cases():
+        p = np.array(c["p"], dtype=np.float64)
+        ids = np.array(c["expert_ids"], dtype=np.int64)
+        lines.append(" ".join(map(str, [c["E"], c["k"], c["c"], c["eps_high"], c["t_fix"], p.shape[0]]
+                                   + list(c["loads_in"]) + [repr(float(x)) for x in p.ravel()]
+                                   + list(ids.ravel()))))
+    cases = tmp_path / "cases.txt"
+    cases.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "oracle_san"
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-o", str(exe), os.path.join(here, "oracle_sanitize_driver.c"),
+           os.path.join(root, "oracle", "laser_oracle.c"), "-lm"]
+    built = subprocess.run(cmd, capture_output=True, text=True)
+    if built.returncode != 0 and "asan" in built.stderr.lower():
+        pytest.skip("no sanitizer runtime for this gcc: " + built.stderr[-200:])
+    assert built.returncode == 0, built.stderr
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    run = subprocess.run([str(exe), str(cases)], capture_output=True, text=True, env=env, timeout=300)
+    assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-4000:]
+    assert run.stdout.strip().endswith("clean")
