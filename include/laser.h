@@ -14,7 +14,8 @@
  *     allocates and owns all buffers, including the workspace.  The library
  *     allocates nothing, frees nothing, never synchronises and never prints:
  *     all work is enqueued on `hip_stream` (a hipStream_t, NULL = default
- *     stream) and the call returns at once.
+ *     stream) and the call returns at once.  The one exception is laser_status(),
+ *     a query that waits for the stream.
  *   - Return value: LASER_OK (0) or a negative LASER_E_* code.  Arguments are
  *     validated on the host before anything is enqueued; on error nothing was
  *     enqueued and no buffer was touched.  laser_strerror() names a code.
@@ -28,8 +29,18 @@
  *     output buffer) must be ordered, e.g. by being enqueued on one stream.  Calls with
  *     their own workspaces and outputs may run side by side on different streams.
  *   - Inputs must be finite; loads_inout[e] + T must stay below 2^27.
- *   - Limits: 1 <= k <= c <= min(E, 16); E <= 64; bf16 needs H % 8 == 0 and
- *     16-byte aligned hidden / w_gate; fp32 needs H % 4 == 0.
+ *   - Limits: 1 <= k <= min(c, 16); c <= E <= 64; bf16 needs H % 8 == 0 and
+ *     16-byte aligned hidden / w_gate; fp32 needs H % 4 == 0.  Trimming sizes
+ *     c <= 16 (the paper evaluates c <= 10) run on the tuned kernels; 16 < c <= E
+ *     (up to the load-only baseline of the paper's evaluation, c = n) is routed
+ *     exactly by general kernels that are not tuned.
+ *   - Completion.  The kernels of a call hand data to one another through the
+ *     workspace; the workgroups that write the dispatch tables wait for the
+ *     workgroup that walks the load-dependent tokens with a bounded number of
+ *     polls (laser_params_t.poll_budget) and, should that bound ever run out, leave
+ *     without writing: the call's outputs are then incomplete.  This is recorded
+ *     in the workspace and reported by laser_status(); it does not happen while
+ *     the GPU makes progress on the call's own kernels.
  */
 #ifndef LASER_H_
 #define LASER_H_
@@ -57,7 +68,15 @@ extern "C" {
 #define LASER_TRIM_RANDOM 1 /* uniform sample of c pool members, see laser_params_t  */
 
 #define LASER_MAX_E 64
-#define LASER_MAX_C 16
+#define LASER_MAX_K 16
+#define LASER_MAX_C 64      /* (c <= E) */
+#define LASER_FAST_C 16     /* trimming sizes up to here run on the tuned kernels */
+
+/* What laser_status() reports about the last call that used a workspace. */
+#define LASER_STATUS_COMPLETE 0
+#define LASER_STATUS_TIMEOUT 1       /* a bounded wait ran out: outputs incomplete      */
+#define LASER_STATUS_INCONSISTENT 2  /* a dispatch slot fell outside the table (inputs  */
+                                     /* overwritten while the call ran): outputs incomplete */
 
 /* Parameters of Algorithm 1 plus the storage type of the gate operands. */
 typedef struct laser_params {
@@ -70,8 +89,8 @@ typedef struct laser_params {
   int32_t trim_mode;     /* LASER_TRIM_*                                            */
   int32_t renormalize;   /* 1: weights sum to 1 over the k chosen; 0: raw scores    */
   int32_t dtype;         /* LASER_DTYPE_* of hidden and w_gate (laser_route only)   */
-  /* LASER_TRIM_RANDOM only (Algorithm 1, mode RANDOM: "uniformly sample c* indices
-   * from the pool, without replacement").  The sample of a token is a function of
+  /* LASER_TRIM_RANDOM only (Algorithm 1, mode RANDOM: the working set is a uniform
+   * sample of the pool, drawn without replacement).  The sample of a token is a function of
    * (seed, stream, token_offset + t) alone: Philox4x32-10 with key = seed and counter
    * = (token index low, high, stream, block); a partial Fisher-Yates shuffle of the
    * pool's positions [0, m) in the score order swaps position i with
@@ -81,7 +100,9 @@ typedef struct laser_params {
   uint64_t seed;         /* generator key                                           */
   uint64_t token_offset; /* caller's index of token 0 of this call (split calls)    */
   uint32_t stream;       /* caller's stream id, e.g. the layer                      */
-  uint32_t reserved;     /* 0                                                       */
+  uint32_t poll_budget;  /* 0: the library sizes its bounded waits from T (millions of */
+                         /* polls); otherwise the number of polls after which a waiting */
+                         /* workgroup gives up (see "Completion" above)                 */
 } laser_params_t;
 
 /* Bytes of device workspace a call with these sizes needs (0 on bad arguments).
@@ -214,38 +235,13 @@ int laser_summary_f32(const float* values, int32_t n, const double* q, int32_t n
 const char* laser_strerror(int code);
 
 /*
- * Stage timing for benchmarks.  While enabled, laser_route brackets its gate
- * kernel with HIP events on the caller's stream (events come from a pool created
- * by laser_profile_enable; at most `max_calls` calls are recorded, later ones
- * are not bracketed).  laser_profile_read synchronises on the recorded events
- * and returns the summed gate-kernel time in milliseconds and the number of
- * launches it covers (both host pointers), then clears the record.
- * laser_profile_enable(0) turns it off and destroys the pool.  Not thread-safe.
+ * Whether the last call that used `workspace` (the start of one problem's workspace; for
+ * problem b of a batched call, workspace + b * laser_workspace_bytes(...)) wrote all of
+ * its outputs: waits for `hip_stream`, then stores LASER_STATUS_* in *status (host
+ * pointer).  The record is cleared by the next call that uses the workspace.  This is
+ * the library's only call that synchronises.
  */
-int laser_profile_enable(int32_t max_calls);
-int laser_profile_read(double* gate_ms_sum, int64_t* gate_launches);
-
-/*
- * What a pair of HIP events adds to the kernel it brackets, in milliseconds (host
- * pointer): the library launches a kernel that spins for a fixed 10 microseconds of
- * the GPU's constant-rate clock between event pairs on `hip_stream`, synchronises,
- * and returns the median of (elapsed - 10 us).  Benchmarks subtract it from the
- * per-launch average of laser_profile_read.  Creates and destroys its own events.
- */
-int laser_profile_event_overhead(void* hip_stream, double* overhead_ms);
-
-/*
- * The box's own ceiling for a streaming read, for benchmarks: a plain kernel (16-byte
- * loads, nothing else) reads `bytes` of `device_buf` (device pointer, 16-byte
- * aligned) in back-to-back launches of `bytes_per_launch` (a multiple of 16; a last
- * partial piece is skipped) on `hip_stream`, bracketed by one HIP event pair; the call
- * synchronises and returns the elapsed milliseconds and the number of launches (host
- * pointers).  `device_sink` is a device word the kernel may write.  Pass a buffer
- * well beyond the 256 MB last-level cache to measure HBM.
- */
-int laser_profile_plain_read(const void* device_buf, size_t bytes, size_t bytes_per_launch,
-                             void* device_sink, void* hip_stream, double* ms_total,
-                             int64_t* launches);
+int laser_status(const void* workspace, void* hip_stream, int32_t* status);
 
 #ifdef __cplusplus
 }

@@ -19,9 +19,17 @@ DTYPE_BF16 = 1
 TRIM_TOP = 0
 TRIM_RANDOM = 1
 
-EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats", "laser_route_from_logits", "laser_imbalance", "laser_percentiles", "laser_summary_f32",
-           "laser_strerror", "laser_profile_enable", "laser_profile_read",
-           "laser_profile_event_overhead", "laser_profile_plain_read")
+# include/laser.h
+EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats",
+           "laser_route_from_logits", "laser_imbalance", "laser_percentiles", "laser_summary_f32",
+           "laser_strerror", "laser_status")
+# include/laser_bench.h
+BENCH_EXPORTS = ("laser_bench_timer_create", "laser_bench_timer_destroy", "laser_bench_route",
+                 "laser_bench_timer_read", "laser_bench_event_overhead", "laser_bench_plain_read")
+
+STATUS_COMPLETE = 0
+STATUS_TIMEOUT = 1
+STATUS_INCONSISTENT = 2
 
 
 class LaserParams(ctypes.Structure):
@@ -37,7 +45,7 @@ class LaserParams(ctypes.Structure):
         ("seed", ctypes.c_uint64),
         ("token_offset", ctypes.c_uint64),
         ("stream", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("poll_budget", ctypes.c_uint32),
     ]
 
 
@@ -74,15 +82,22 @@ def _load() -> ctypes.CDLL:
     lib.laser_route_from_logits.restype = ctypes.c_int
     lib.laser_strerror.argtypes = [ctypes.c_int]
     lib.laser_strerror.restype = ctypes.c_char_p
-    lib.laser_profile_enable.argtypes = [i32]
-    lib.laser_profile_enable.restype = ctypes.c_int
-    lib.laser_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
-    lib.laser_profile_read.restype = ctypes.c_int
-    lib.laser_profile_event_overhead.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
-    lib.laser_profile_event_overhead.restype = ctypes.c_int
-    lib.laser_profile_plain_read.argtypes = [vp, sz, sz, vp, vp, ctypes.POINTER(ctypes.c_double),
-                                             ctypes.POINTER(ctypes.c_int64)]
-    lib.laser_profile_plain_read.restype = ctypes.c_int
+    lib.laser_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.laser_status.restype = ctypes.c_int
+    lib.laser_bench_timer_create.argtypes = [i32, ctypes.POINTER(vp)]
+    lib.laser_bench_timer_create.restype = ctypes.c_int
+    lib.laser_bench_timer_destroy.argtypes = [vp]
+    lib.laser_bench_timer_destroy.restype = None
+    lib.laser_bench_route.argtypes = [vp] + lib.laser_route.argtypes
+    lib.laser_bench_route.restype = ctypes.c_int
+    lib.laser_bench_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                           ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
+    lib.laser_bench_timer_read.restype = ctypes.c_int
+    lib.laser_bench_event_overhead.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.laser_bench_event_overhead.restype = ctypes.c_int
+    lib.laser_bench_plain_read.argtypes = [vp, sz, sz, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int64)]
+    lib.laser_bench_plain_read.restype = ctypes.c_int
     return lib
 
 
@@ -91,9 +106,9 @@ _lib = _load()
 
 def make_params(k: int, c: int, eps_high: float, t_fix: float, dtype: int = DTYPE_BF16,
                 renormalize: bool = True, trim_mode: int = TRIM_TOP, seed: int = 0,
-                stream: int = 0, token_offset: int = 0) -> LaserParams:
+                stream: int = 0, token_offset: int = 0, poll_budget: int = 0) -> LaserParams:
     return LaserParams(ctypes.sizeof(LaserParams), k, c, eps_high, t_fix, trim_mode,
-                       1 if renormalize else 0, dtype, seed, token_offset, stream, 0)
+                       1 if renormalize else 0, dtype, seed, token_offset, stream, poll_budget)
 
 
 def laser_strerror(code: int) -> str:
@@ -195,30 +210,62 @@ def laser_summary_f32(values, q, stream=None):
     return mean, out
 
 
-def laser_profile_enable(max_calls: int) -> None:
-    _check(_lib.laser_profile_enable(max_calls))
+def laser_status(workspace, stream=None) -> int:
+    """STATUS_* of the last call that used `workspace` (waits for the stream)."""
+    st = ctypes.c_int32(-1)
+    _check(_lib.laser_status(_ptr(workspace), _stream_handle(stream), ctypes.byref(st)))
+    return st.value
 
 
-def laser_profile_read() -> tuple[float, int]:
-    ms = ctypes.c_double(0.0)
-    n = ctypes.c_int64(0)
-    _check(_lib.laser_profile_read(ctypes.byref(ms), ctypes.byref(n)))
-    return ms.value, n.value
+class BenchTimer:
+    """Event pool of include/laser_bench.h: times the stages of laser_bench_route calls."""
+
+    def __init__(self, max_calls: int):
+        self.capacity = max_calls
+        self._h = ctypes.c_void_p()
+        _check(_lib.laser_bench_timer_create(max_calls, ctypes.byref(self._h)))
+
+    def route(self, hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+              expert_offsets, logits_out, workspace, stream=None) -> None:
+        _check(_lib.laser_bench_route(self._h, _ptr(hidden), _ptr(w_gate), T, H, E, ctypes.byref(params),
+                                      _ptr(loads_inout), _ptr(expert_ids), _ptr(weights),
+                                      _ptr(permutation), _ptr(expert_offsets), _ptr(logits_out),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream_handle(stream)))
+
+    def read(self):
+        """(first_ms, tail_ms): per timed call, projection + analysis and tail kernel (lists)."""
+        a = (ctypes.c_double * self.capacity)()
+        b = (ctypes.c_double * self.capacity)()
+        n = ctypes.c_int64(0)
+        _check(_lib.laser_bench_timer_read(self._h, a, b, self.capacity, ctypes.byref(n)))
+        return list(a[:n.value]), list(b[:n.value])
+
+    def close(self) -> None:
+        if self._h:
+            _lib.laser_bench_timer_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
-def laser_profile_event_overhead(stream=None) -> float:
+def laser_bench_event_overhead(stream=None) -> float:
     """Milliseconds a HIP event pair adds to the kernel it brackets (measured now)."""
     ms = ctypes.c_double(0.0)
-    _check(_lib.laser_profile_event_overhead(_stream_handle(stream), ctypes.byref(ms)))
+    _check(_lib.laser_bench_event_overhead(_stream_handle(stream), ctypes.byref(ms)))
     return ms.value
 
 
-def laser_profile_plain_read(buf, bytes_per_launch: int, sink, stream=None):
+def laser_bench_plain_read(buf, bytes_per_launch: int, sink, stream=None):
     """(milliseconds, launches) of a plain streaming read of `buf` in pieces."""
     ms = ctypes.c_double(0.0)
     n = ctypes.c_int64(0)
     nbytes = buf.numel() * buf.element_size()
-    _check(_lib.laser_profile_plain_read(
+    _check(_lib.laser_bench_plain_read(
         ctypes.c_void_p(buf.data_ptr()), ctypes.c_size_t(nbytes), ctypes.c_size_t(bytes_per_launch),
         ctypes.c_void_p(sink.data_ptr()), _stream_handle(stream), ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value

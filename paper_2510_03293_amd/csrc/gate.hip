@@ -254,6 +254,7 @@ static hipError_t launch_nmb(const void* hidden, const void* w, int H, const Rou
   const void* fn = reinterpret_cast<const void*>(&gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>);
   const hipError_t e = allow_dynamic_lds(fn, kGateLdsBytes, allowed);
   if (e != hipSuccess) return e;
+  clear_stale_error();
   hipLaunchKernelGGL((gate_analyse_bf16_kernel<EB, NE, NM, STATS, BATCH>), dim3(a.ntiles, a.nbatch), dim3(kGateThreads), kGateLdsBytes, s,
                      static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out, logits_stride);
@@ -275,8 +276,11 @@ template <int EB, int NE>
 static hipError_t launch_one(const void* hidden, const void* w, int H, const RouteArgs& a,
                              const Workspace& ws, int32_t* expert_ids, float* weights,
                              float* logits_out, size_t logits_stride, hipStream_t s) {
-  // (the statistics variant exists for the general loop only)
-  if (wants_stats(a)) return launch_nm<EB, NE, 0, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+  if (wants_stats(a)) {
+    if (H == 2048) return launch_nm<EB, NE, 4, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+    if (H == 4096) return launch_nm<EB, NE, 8, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+    return launch_nm<EB, NE, 0, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
+  }
   if (H == 2048) return launch_nm<EB, NE, 4, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
   if (H == 4096) return launch_nm<EB, NE, 8, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
   return launch_nm<EB, NE, 0, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
@@ -325,6 +329,7 @@ hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, in
   const long long total = (long long)T * E;
   if (total == 0) return hipSuccess;
   const unsigned blocks = (unsigned)((total + 255) / 256);
+  clear_stale_error();
   hipLaunchKernelGGL(gate_f32_kernel, dim3(blocks, nbatch), dim3(256), 0, s, hidden, w, T, H, E, logits,
                      logits_stride);
   return hipGetLastError();

@@ -10,7 +10,9 @@ namespace laser {
 
 constexpr int kTile = 64;        // tokens per tile (one wave-wide bit mask per tile)
 constexpr int kMaxE = 64;        // experts: one lane of a wavefront per expert
-constexpr int kMaxC = 16;        // trimming size limit (candidate ranks fit 4 bits)
+constexpr int kMaxC = 16;        // trimming size the fast kernels carry (candidate ranks fit 4 bits)
+constexpr int kWideC = 64;       // trimming sizes above kMaxC: records of kWideC candidates, general kernels
+constexpr int kMaxK = 16;        // experts per token
 
 // Per-call scalars handed to every kernel by value.
 struct RouteArgs {
@@ -19,6 +21,7 @@ struct RouteArgs {
   int EP;           // experts padded to 8/16/32/64 (8 lanes per token x EP/8 each)
   int k;            // experts per token
   int c;            // trimming size
+  int cw;           // candidates per token record: kMaxC, or kWideC when c > kMaxC ("wide" calls)
   int ntiles;       // ceil(T / kTile)
   int renormalize;  // weights over the chosen k (1) or raw softmax scores (0)
   float eps_high;   // top-k mass threshold
@@ -32,6 +35,7 @@ struct RouteArgs {
   int pool_in_ws;      // 1: nobody asked for st_pool but RANDOM trimming needs the pool sizes:
                        // the kernels write and read them in the workspace (Workspace::pool)
   // batched calls: the kernels run with the problem index in blockIdx.y
+  long long spin_limit;  // polls a finishing wavefront spends on one flag of the chain before it gives up
   int nbatch;          // problems in the call (1: all of the above is the one problem's)
   size_t ws_stride;    // bytes from one problem's workspace to the next
 };
@@ -50,10 +54,11 @@ inline bool wants_stats(const RouteArgs& a) { return a.st_mass || a.st_entropy |
 struct Workspace {
   float* logits;               // [T,E]   gate logits (unless the caller gave a buffer)
   uint8_t* rec_cstar;          // [T]     working-set size of a flexible token, else 0
-  uint8_t* rec_ids;            // [T,16]  experts by descending score
-  float* rec_p;                // [T,16]  their softmax numerators exp(z - z_max)
+  uint8_t* rec_ids;            // [T,cw]  experts by descending score
+  float* rec_p;                // [T,cw]  their softmax numerators exp(z - z_max)
   float* rec_Z;                // [T]     softmax normaliser
   uint16_t* rec_lane;          // [slot,EP] per expert: (fixed-prefix << 4 | rank) or 0xFFFF
+                               //           (wide calls: fixed-prefix << 6 | rank)
   unsigned long long* flexmask;    // [ntiles] bit i: token i of the tile is flexible
   uint8_t* tile_fixed_cnt;     // [ntiles,64] assignments of the tile's non-flexible tokens (<= 64)
   unsigned long long* tile_mask;   // [ntiles,64] per expert: the tile's non-flexible tokens
@@ -71,7 +76,8 @@ struct Workspace {
   int32_t* chain_cum;          // [T/32+2,64] per expert: choices by flexible tokens < 32*w
   int32_t* lin_copy;           // [64] loads before token 0 (0 beyond E)
   int32_t* pool;               // [T] pool sizes, when RANDOM trimming needs them (see pool_in_ws)
-  int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call
+  int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call (the
+                               //     first bytes of the workspace, so that a query needs no sizes)
 };
 
 // Problem b of a batched call.  All problems share the sizes; every array of problem
@@ -116,11 +122,19 @@ __device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size
 
 constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished
 constexpr int kStatusFlexTiles = 1;  // number of tiles that hold flexible tokens
-constexpr int kStatusError = 2;      // a bounded wait in the tail kernel ran out
+constexpr int kStatusError = 2;      // 0, or why the outputs of the call are incomplete (kError*)
+constexpr int kErrorTimeout = 1;        // a bounded wait in the tail kernel ran out (LASER_STATUS_TIMEOUT)
+constexpr int kErrorInconsistent = 2;   // a dispatch slot fell outside the table (LASER_STATUS_INCONSISTENT)
+// Polls of one flag before a finishing wavefront gives up (a poll is a memory round trip
+// plus a short sleep, about a microsecond): a floor for the chain workgroup's start-up
+// plus an allowance per token of the call, far above the chain's cost per token.
+constexpr long long kSpinFloor = 1ll << 22;
+constexpr long long kSpinPerToken = 16;
 constexpr int kStatusSweeps = 3;     // sweeps of the chain's window evaluation (diagnostic)
 
-size_t workspace_bytes(int T, int E, bool need_logits);
-Workspace carve_workspace(void* base, int T, int E, bool need_logits);
+inline int record_width(int c) { return c > kMaxC ? kWideC : kMaxC; }
+size_t workspace_bytes(int T, int E, int cw);
+Workspace carve_workspace(void* base, int T, int E, int cw);
 
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
 
@@ -141,6 +155,10 @@ inline hipError_t allow_dynamic_lds(const void* fn, int bytes, LdsAttr& rec) {
   return e;
 }
 
+// A launcher reports the status of its own launch: an error that an earlier HIP call of
+// the caller left behind is cleared first, not mistaken for a failed launch.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+
 // Launchers (enqueue only; return the HIP error of the launch).
 // gate projection fused with the per-token analysis (logits_out may be NULL;
 // logits_stride: floats from one problem's logits to the next)
@@ -153,11 +171,11 @@ hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, in
 // (logits_stride: floats from one problem's logits to the next)
 hipError_t launch_analyse(const float* logits, size_t logits_stride, const RouteArgs& a, const Workspace& ws,
                           int32_t* expert_ids, float* weights, hipStream_t s);
-// per-token analysis with RANDOM trimming, from logits [T,E]: the whole analysis
-// (problem b draws with stream id rnd.stream + b) ...
-hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,
-                                 const Workspace& ws, const RandomArgs& rnd, int32_t* expert_ids,
-                                 float* weights, hipStream_t s);
+// the whole per-token analysis from logits [T,E] by the general kernel: either trimming
+// mode (sample: RANDOM; problem b draws with stream id rnd.stream + b), any record width ...
+hipError_t launch_analyse_general(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                  const Workspace& ws, bool sample, const RandomArgs& rnd,
+                                  int32_t* expert_ids, float* weights, hipStream_t s);
 // ... or, behind the deterministic analysis run with pool sizes (c > k only), a second
 // look at the tokens whose pool exceeds c: their records are rewritten for the sample
 hipError_t launch_random_resample(const float* logits, size_t logits_stride, const RouteArgs& a,
@@ -166,4 +184,25 @@ hipError_t launch_tail(const RouteArgs& a, const Workspace& ws, int32_t* loads_i
                        int32_t* expert_offsets, int32_t* expert_ids, float* weights,
                        int32_t* permutation, hipStream_t s);
 
+
+// ---- host side shared by the C ABI files ------------------------------------------
+
+// Events of the benchmark timer (laser_bench.h): three per timed call.
+struct BenchTimer {
+  hipEvent_t* ev;
+  int capacity;  // calls
+  int used;      // calls recorded
+};
+
+}  // namespace laser
+
+struct laser_params;
+namespace laser {
+// The routing call behind laser_route, laser_route_batched and laser_route_stats
+// (timer: NULL, or where laser_bench_route records its events).
+int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int32_t H, int32_t E,
+               const laser_params* params, int32_t* loads_inout, int32_t* expert_ids, float* weights,
+               int32_t* permutation, int32_t* expert_offsets, float* logits_out, float* topk_mass,
+               float* entropy, int32_t* pool_size, void* workspace, size_t workspace_bytes_given,
+               void* hip_stream, BenchTimer* timer);
 }  // namespace laser

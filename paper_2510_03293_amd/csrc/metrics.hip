@@ -219,6 +219,7 @@ extern "C" int laser_summary_f32(const float* values, int32_t n, const double* q
     pa.q[i] = i < nq ? q[i] : 0.0;
     if (i < nq && !(q[i] >= 0.0 && q[i] <= 100.0)) return LASER_E_RANGE;
   }
+  (void)hipGetLastError();  // (an earlier call's error is not this launch's)
   hipLaunchKernelGGL(summary_f32_kernel, dim3(1), dim3(kSummaryThreads), 0,
                      static_cast<hipStream_t>(hip_stream), values, n, pa, mean, out);
   return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;
@@ -236,6 +237,7 @@ extern "C" int laser_percentiles(const double* values, int32_t n, const double* 
     pa.q[i] = i < nq ? q[i] : 0.0;
     if (i < nq && !(q[i] >= 0.0 && q[i] <= 100.0)) return LASER_E_RANGE;
   }
+  (void)hipGetLastError();  // (an earlier call's error is not this launch's)
   hipLaunchKernelGGL(percentile_kernel, dim3(1), dim3(kMetricThreads), 0, static_cast<hipStream_t>(hip_stream),
                      values, n, pa, out);
   return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;
@@ -251,10 +253,12 @@ extern "C" int laser_imbalance(const int32_t* counts, int32_t L, int32_t E, cons
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (L > 0) {
     const size_t lds = placement ? (size_t)G * sizeof(double) : 0;
+    (void)hipGetLastError();  // (an earlier call's error is not this launch's)
     hipLaunchKernelGGL(imbalance_layers_kernel, dim3(L), dim3(kMetricThreads), lds, s, counts, E,
                        placement, G, I, MV, I_gpu);
     if (hipGetLastError() != hipSuccess) return LASER_E_LAUNCH;
   }
+  (void)hipGetLastError();  // (an earlier call's error is not this launch's)
   hipLaunchKernelGGL(imbalance_aggregate_kernel, dim3(1), dim3(64), 0, s, I, placement ? I_gpu : nullptr,
                      layer_weights, L, agg);
   return hipGetLastError() == hipSuccess ? LASER_OK : LASER_E_LAUNCH;

@@ -13,11 +13,14 @@
 // the score order swaps position i with i + floor(r_i * (m - i) / 2^32) for
 // i = 0..c-1; the first c positions, in ascending order, are the candidates.
 //
-// Two kernels.  analyse_random_kernel is the whole analysis in this mode: one workgroup
-// per tile of 64 tokens, lane = token, per-token arrays in LDS, order statistics by
-// counting (E^2 compares per token, shared by four waves), everything after that one
-// wavefront's work; written for clarity, and used where c == k (a sampled token is then
-// not load-dependent, but its experts are the sample).  Where c > k the deterministic
+// Two kernels.  analyse_general_kernel is the whole analysis in either trimming mode:
+// one workgroup per tile of 64 tokens, lane = token, per-token arrays in LDS, order
+// statistics by counting (E^2 compares per token, shared by four waves), everything
+// after that one wavefront's work; written for clarity.  It is used for RANDOM trimming
+// where c == k (a sampled token is then not load-dependent, but its experts are the
+// sample), and in both modes for trimming sizes above the 16 candidates that the fast
+// analysis carries ("wide" calls: up to 64 candidates per token, e.g. the load-only
+// baseline of the paper's evaluation, c = n).  Where 16 >= c > k the deterministic
 // analysis already gives everything but the candidates of the tokens it trimmed, and
 // random_resample_kernel only redoes those.
 #include "analyse.h"
@@ -50,7 +53,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 constexpr int kRandomWaves = 4;  // the counting pass is shared by 4 waves, the rest is wave 0's
 
-__global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const float* __restrict__ logits,
+// SAMPLE: trimming mode RANDOM (otherwise the c best of the pool are kept).
+template <bool SAMPLE>
+__global__ __launch_bounds__(64 * kRandomWaves) void analyse_general_kernel(const float* __restrict__ logits,
                                                             size_t logits_stride, const RouteArgs a0,
                                                             const Workspace ws0, const RandomArgs rnd0,
                                                             int32_t* __restrict__ expert_ids,
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
   const int cstar = mass_ok ? k : (c < m ? c : m);
 
   // ---- candidates: positions in the score order, ascending ----------------------
-  if (!mass_ok && m > c) {
+  if (SAMPLE && !mass_ok && m > c) {
     for (int i = 0; i < m; ++i) arr[i] = (uint8_t)i;
     const unsigned long long g = rnd.token_offset + (unsigned long long)t;
     uint32_t wv[4] = {0u, 0u, 0u, 0u};
@@ -193,9 +198,11 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
   if (flex) {
     const int slot = tile * kTile + __builtin_popcountll(fm & lanes_below(lane));
     const unsigned long long below = lanes_below(lane);
+    const int cw = a.cw;
+    const bool wide = cw > kMaxC;  // (the wide chain reads the per-expert rows only)
     // ranks beyond the working set point the chain at a lane that holds no candidate
     int padlane = E;
-    if (E == 64) {
+    if (E == 64 && !wide) {
       unsigned used = 0;
       for (int j = 0; j < cstar; ++j) {
         const int e = ord[arr[j]];
@@ -205,15 +212,17 @@ __global__ __launch_bounds__(64 * kRandomWaves) void analyse_random_kernel(const
     }
     uint16_t* row = ws.rec_lane + (size_t)slot * a.EP;
     for (int e = 0; e < a.EP; ++e) row[e] = (uint16_t)0xFFFF;
-    for (int j = 0; j < kMaxC; ++j) {
+    for (int j = 0; j < cw; ++j) {
       const bool in = j < cstar;
       const int e = in ? (int)ord[arr[j]] : 0;
       const int pref = in ? __builtin_popcountll(maskl[e] & below) : 0xFF;
-      ws.rec_ids[(size_t)t * 16 + j] = (uint8_t)e;
-      ws.rec_p[(size_t)t * 16 + j] = in ? p[e] : 0.0f;
-      ws.rec_cids[(size_t)slot * 16 + j] = (uint8_t)(in ? e : padlane);
-      ws.rec_pref[(size_t)slot * 16 + j] = (uint8_t)pref;
-      if (in) row[e] = (uint16_t)((pref << 4) | j);
+      ws.rec_ids[(size_t)t * cw + j] = (uint8_t)e;
+      ws.rec_p[(size_t)t * cw + j] = in ? p[e] : 0.0f;
+      if (!wide) {
+        ws.rec_cids[(size_t)slot * 16 + j] = (uint8_t)(in ? e : padlane);
+        ws.rec_pref[(size_t)slot * 16 + j] = (uint8_t)pref;
+      }
+      if (in) row[e] = (uint16_t)(wide ? ((pref << 6) | j) : ((pref << 4) | j));
     }
   }
 }
@@ -335,17 +344,23 @@ __global__ __launch_bounds__(64 * kRandomWaves) void random_resample_kernel(cons
 hipError_t launch_random_resample(const float* logits, size_t logits_stride, const RouteArgs& a,
                                   const Workspace& ws, const RandomArgs& rnd, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
+  clear_stale_error();
   hipLaunchKernelGGL(random_resample_kernel, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s, logits,
                      logits_stride, a, ws, rnd);
   return hipGetLastError();
 }
 
-hipError_t launch_analyse_random(const float* logits, size_t logits_stride, const RouteArgs& a,
-                                 const Workspace& ws, const RandomArgs& rnd, int32_t* expert_ids,
-                                 float* weights, hipStream_t s) {
+hipError_t launch_analyse_general(const float* logits, size_t logits_stride, const RouteArgs& a,
+                                  const Workspace& ws, bool sample, const RandomArgs& rnd,
+                                  int32_t* expert_ids, float* weights, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(analyse_random_kernel, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s, logits,
-                     logits_stride, a, ws, rnd, expert_ids, weights);
+  clear_stale_error();
+  if (sample)
+    hipLaunchKernelGGL(analyse_general_kernel<true>, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s,
+                       logits, logits_stride, a, ws, rnd, expert_ids, weights);
+  else
+    hipLaunchKernelGGL(analyse_general_kernel<false>, dim3(a.ntiles, a.nbatch), dim3(64 * kRandomWaves), 0, s,
+                       logits, logits_stride, a, ws, rnd, expert_ids, weights);
   return hipGetLastError();
 }
 

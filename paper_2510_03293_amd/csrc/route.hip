@@ -79,6 +79,7 @@ hipError_t launch_analyse(const float* logits, size_t logits_stride, const Route
   if (a.ntiles == 0) return hipSuccess;
   const dim3 grid(a.ntiles, a.nbatch), block(512);
   const bool st = wants_stats(a);
+  clear_stale_error();
 #define LASER_LAUNCH_ANALYSE(NE_)                                                                  \
   if (st)                                                                                          \
     hipLaunchKernelGGL((analyse_kernel<NE_, true>), grid, block, 0, s, logits, logits_stride, a,   \
@@ -128,6 +129,7 @@ static hipError_t launch_tail_b(const RouteArgs& a, const Workspace& ws, int32_t
       allow_dynamic_lds(reinterpret_cast<const void*>(&tail_kernel<BATCH>), kChainLdsBytes, allowed);
   if (e != hipSuccess) return e;
   const int grid = 1 + (a.ntiles + kChainWaves - 1) / kChainWaves;
+  clear_stale_error();
   hipLaunchKernelGGL(tail_kernel<BATCH>, dim3(grid, a.nbatch), dim3(kTailThreads), kChainLdsBytes, s, a, ws,
                      loads_inout, expert_offsets, expert_ids, weights, permutation);
   return hipGetLastError();

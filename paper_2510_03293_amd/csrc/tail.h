@@ -49,20 +49,20 @@ namespace laser {
 // The waits are bounded polls of flags that the analysis kernel of the same call
 // cleared; workgroup 0 has the lowest index, is dispatched first and never waits,
 // so the polls end.  A poll that runs out sets ws.status[kStatusError] and the wave
-// leaves without writing.
+// leaves without writing; the caller learns of it through laser_status().
 
 constexpr int kChainWaves = 4;
 constexpr int kTailThreads = kChainWaves * 64;
 constexpr int kChainBatch = 3;  // flexible tiles per LDS batch
-constexpr int kSpinLimit = 1 << 22;
 constexpr int kSelfPrefixTiles = 1024;  // up to here finishing workgroups sum the counts themselves
 // (see "a handful of flexible tokens" below)
 constexpr int kFastMaxTiles = 256;
 constexpr int kFastTiles = 4;
 constexpr int kFastTokens = 8;
 
-__device__ __forceinline__ bool fast_path_applies(int ntiles, int nflex_tiles, int nflex_tok) {
-  return ntiles <= kFastMaxTiles && nflex_tiles > 0 && nflex_tiles <= kFastTiles &&
+// (not for wide calls: the shortcut reads the 16-candidate records)
+__device__ __forceinline__ bool fast_path_applies(int ntiles, int nflex_tiles, int nflex_tok, int cw) {
+  return cw == kMaxC && ntiles <= kFastMaxTiles && nflex_tiles > 0 && nflex_tiles <= kFastTiles &&
          nflex_tok <= kFastTokens;
 }
 
@@ -87,8 +87,8 @@ __device__ __forceinline__ unsigned load_published(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ bool poll_flag(const int* flag, int want) {
-  for (int it = 0; it < kSpinLimit; ++it) {
+__device__ __forceinline__ bool poll_flag(const int* flag, int want, long long limit) {
+  for (long long it = 0; it < limit; ++it) {
     const int seen = __builtin_amdgcn_readfirstlane(
         __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     if (seen >= want) return true;
@@ -163,10 +163,42 @@ __device__ __forceinline__ bool chain_step(unsigned key, bool cand, const uint4 
   return cand && smaller < k;
 }
 
+// Wave-wide minimum as a scalar: two exchanges inside the quads, the half-row and row
+// mirrors (every lane of a 16-lane row then holds the row's minimum), one lane of each
+// row read out.
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v) {
+  constexpr int kRowMirror = 0x140;
+  v = min(v, (unsigned)dpp_int<kQuadXor1>((int)v));
+  v = min(v, (unsigned)dpp_int<kQuadXor2>((int)v));
+  v = min(v, (unsigned)dpp_int<kRowHalfMirror>((int)v));
+  v = min(v, (unsigned)dpp_int<kRowMirror>((int)v));
+  const unsigned r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+  const unsigned r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+  return min(min(r0, r1), min(r2, r3));
+}
+
+// One flexible token of a wide call (up to 64 candidates), lane = expert: the k
+// candidates with the smallest (load, rank), found in k rounds -- the least load among
+// the remaining candidates, then the least rank among those that have it.  Any loads
+// below 2^32 - 1; not tuned (the trimming sizes the paper evaluates are at most 10).
+__device__ __forceinline__ bool chain_step_wide(unsigned load, unsigned rank, bool cand, int k) {
+  bool remaining = cand, chosen = false;
+  for (int r = 0; r < k; ++r) {
+    const unsigned lmin = wave_min_u32(remaining ? load : 0xFFFFFFFFu);
+    const bool tie = remaining && load == lmin;
+    const unsigned rmin = wave_min_u32(tie ? rank : 0xFFFFFFFFu);
+    const bool pick = tie && rank == rmin;
+    chosen = chosen || pick;
+    remaining = remaining && !pick;
+  }
+  return chosen;
+}
+
 // Sequential walk (wave 0, lane = expert) over the flexible tiles from flexible tile
 // `ft0`, record `r_start` of that tile, which is flexible token `f0` of the call;
 // `hist0` holds the bits of output word f0/32 that are decided already.  The output
 // (chain_bits, chain_cum) is indexed by the flexible token's number within the call.
+// CP = 0: a wide call (records of up to 64 candidates, per-expert rows only).
 template <int CP>
 __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start, int f0,
                                            unsigned hist0, int nflex_tiles, const RouteArgs& a, const Workspace& ws,
@@ -214,8 +246,13 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start
               ids_next = cidp[r + 1];
             }
             const bool cand = lane_ok && rec != 0xFFFFu;
-            const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
-            const bool chosen = chain_step<CP>(key, cand, ids, k);
+            bool chosen;
+            if constexpr (CP == 0) {
+              chosen = chain_step_wide((unsigned)lsum + (rec >> 6), rec & 63u, cand, k);
+            } else {
+              const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
+              chosen = chain_step<CP>(key, cand, ids, k);
+            }
             lsum += chosen ? 1 : 0;
             hist |= (chosen ? 1u : 0u) << sh;
           }
@@ -604,6 +641,9 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   const int lane = threadIdx.x & 63;
   const int ntiles = a.ntiles;
 
+  // (a call without tokens has no analysis kernel that would have cleared the status
+  // words, and no finishing workgroup that polls them)
+  if (ntiles == 0 && threadIdx.x < 4) ws.status[threadIdx.x] = 0;
   // Everything the workgroup reads first is requested before anything is consumed:
   // the counters, the first super-batch of byte counts, the flexible-tile masks.
   int lin = 0;
@@ -659,7 +699,7 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   }
   // a handful of flexible tokens: the finishing workgroups resolve them themselves and
   // write the totals; nothing to do here
-  if (fast_path_applies(ntiles, nflex_tiles, nflex_tok)) return;
+  if (fast_path_applies(ntiles, nflex_tiles, nflex_tok, a.cw)) return;
   // Without flexible tokens, small problems are finished without tile_base (the
   // finishing workgroups sum the byte counts themselves): only the totals are needed.
   const bool need_tile_base = nflex_tiles > 0 || ntiles > kSelfPrefixTiles;
@@ -701,7 +741,8 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
 
   nflex_tiles = __builtin_amdgcn_readfirstlane(nflex_tiles);
   nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
-  const bool use_spec = nflex_tok >= kSpecMinTokens;
+  const bool wide = a.cw > kMaxC;
+  const bool use_spec = nflex_tok >= kSpecMinTokens && !wide;
   // order of the flexible tiles, and for every tile the number of flexible tokens before it
   for (int g = ga; g < gb && nflex_tiles > 0; ++g) {
     const int tile = g * 64 + lane;
@@ -785,7 +826,9 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
       ft0 = ws.flex_ord[slot >> 6];
       r0 = slot & 63;
     }
-    if (a.c <= 4)
+    if (wide)
+      chain_walk<0>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
+    else if (a.c <= 4)
       chain_walk<4>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
     else if (a.c <= 8)
       chain_walk<8>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
@@ -882,13 +925,13 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
 
   bool any_flex = false;
   if (__builtin_expect(!self, 0)) {
-    if (!poll_flag(&ws.status[kStatusPhase], 1)) {
-      ws.status[kStatusError] = 1;
+    if (!poll_flag(&ws.status[kStatusPhase], 1, a.spin_limit)) {
+      ws.status[kStatusError] = kErrorTimeout;
       return;
     }
     any_flex = load_published(&ws.status[kStatusFlexTiles]) > 0;
-    if (any_flex && !poll_flag(&ws.status[kStatusPhase], 2)) {
-      ws.status[kStatusError] = 1;
+    if (any_flex && !poll_flag(&ws.status[kStatusPhase], 2, a.spin_limit)) {
+      ws.status[kStatusError] = kErrorTimeout;
       return;
     }
   }
@@ -945,11 +988,11 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
       for (int i = 0; i < fast_n; ++i) n = fast->tok[i] == t ? i : n;
       write_row(fast->rids[n], fast->p[n], fast->Z[n], fast->emask[n]);
     } else {
-      const uint8_t* ids = ws.rec_ids + (size_t)t * 16;
+      const uint8_t* ids = ws.rec_ids + (size_t)t * a.cw;
       unsigned long long chosen = 0ull;
       for (int j = 0; j < cstar; ++j)
         chosen |= (unsigned long long)((load_published(&cw[ids[j]]) >> (f & 31)) & 1u) << ids[j];
-      write_row(ids, ws.rec_p + (size_t)t * 16, a.renormalize ? 0.0f : ws.rec_Z[t], chosen);
+      write_row(ids, ws.rec_p + (size_t)t * a.cw, a.renormalize ? 0.0f : ws.rec_Z[t], chosen);
     }
   }
   // LDS traffic of one wavefront is processed in order; the fences only stop the
@@ -968,7 +1011,10 @@ __device__ __forceinline__ void finish_tile(FinishLds* fl, int tile, const Finis
       const int pos = fl->before[e] + __builtin_popcountll(fl->mask64[e] & below);
       // (pos is a slot number by construction; the check turns any inconsistency of
       // the inputs into a missing entry instead of a stray store)
-      if ((unsigned)pos < (unsigned)(a.T * k)) permutation[pos] = t * k + j;
+      if ((unsigned)pos < (unsigned)(a.T * k))
+        permutation[pos] = t * k + j;
+      else
+        ws.status[kStatusError] = kErrorInconsistent;
     }
   }
 }
@@ -1103,7 +1149,7 @@ __device__ __forceinline__ int finish_fast(int block, FastShared& fs, unsigned l
       ntok += __builtin_popcountll(fmask[f]);
     }
   }
-  if (!fast_path_applies(ntiles, nft, ntok)) return 0;
+  if (!fast_path_applies(ntiles, nft, ntok, a.cw)) return 0;
 
   // ---- lane n < ntok: the n-th flexible token of the call ---------------------------
   int my_tok = 0, my_slot = 0, my_f = 0;

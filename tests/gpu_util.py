@@ -84,6 +84,8 @@ def check_random_from_logits(logits, k, c, eps_high, t_fix, loads_in, seed, stre
 
 
 def _collect(buf, loads, logits):
+    # every kernel of the call has reported completion (no bounded wait ran out)
+    assert B.laser_status(buf.workspace) == B.STATUS_COMPLETE
     out = {
         "expert_ids": buf.expert_ids.cpu().numpy(),
         "weights": buf.weights.cpu().numpy(),
@@ -158,6 +160,8 @@ def run_route_batched(hiddens, w_gates, dtype, k, c, eps_high, t_fix, loads_in, 
     logits = torch.full((nb, T, E), -1.0, dtype=torch.float32, device="cuda") if want_logits else None
     B.laser_route_batched(hd, wd, nb, T, H, E, params, loads, ids, wts, perm, offs, logits, ws)
     torch.cuda.synchronize()
+    for b in range(nb):
+        assert B.laser_status(ws[b * one:]) == B.STATUS_COMPLETE
     out = []
     for b in range(nb):
         d = {"expert_ids": ids[b].cpu().numpy(), "weights": wts[b].cpu().numpy(),

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "laser.h")
+BENCH_HEADER = os.path.join(ROOT, "include", "laser_bench.h")
 
 
 @pytest.fixture(scope="module")
@@ -18,18 +19,25 @@ def B():
     return binding
 
 
-def _declared_functions():
-    text = open(HEADER).read()
+def _declared_functions(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(laser_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(B):
-    names = _declared_functions()
-    assert set(names) == set(B.EXPORTS)
     lib = ctypes.CDLL(B.LIB_PATH)
-    for n in names:
-        assert hasattr(lib, n), n
+    for header, listed in ((HEADER, B.EXPORTS), (BENCH_HEADER, B.BENCH_EXPORTS)):
+        names = _declared_functions(header)
+        assert set(names) == set(listed), header
+        for n in names:
+            assert hasattr(lib, n), n
+
+
+def test_product_header_holds_no_benchmark_helpers(B):
+    """Calls that create events, synchronise for timing or launch probe kernels live in
+    laser_bench.h; laser.h declares the routing path only."""
+    assert not [n for n in _declared_functions(HEADER) if "bench" in n or "profile" in n]
 
 
 def test_strerror_and_struct_size(B):
@@ -46,6 +54,15 @@ def test_workspace_query(B):
     assert B.laser_workspace_bytes(0, 2048, 64, p) > 0
     assert B.laser_workspace_bytes(-1, 2048, 64, p) == 0
     assert B.laser_workspace_bytes(64, 2048, 65, p) == 0          # E above the limit
+    wide = B.make_params(6, 64, 0.4, 0.8)                          # records of 64 candidates
+    assert B.laser_workspace_bytes(16384, 2048, 64, wide) > big
+    assert B.laser_workspace_bytes(16384, 2048, 64, B.make_params(6, 16, 0.4, 0.8)) == big
+
+
+def test_status_query_rejects_null(B):
+    st = ctypes.c_int32(0)
+    assert B._lib.laser_status(None, None, ctypes.byref(st)) == -1
+    assert B._lib.laser_status(ctypes.c_void_p(0x1000), None, None) == -1
 
 
 def test_argument_errors_before_any_device_work(B):
@@ -67,7 +84,8 @@ def test_argument_errors_before_any_device_work(B):
     assert route(B.make_params(**{**ok, "t_fix": 0.0})) == -2
     assert route(B.make_params(**ok), T=-1) == -2
     assert route(B.make_params(k=6, c=8, eps_high=.4, t_fix=.8), E=65) == -5
-    assert route(B.make_params(k=2, c=17, eps_high=.4, t_fix=.8), E=64) == -5   # c > 16
+    assert route(B.make_params(k=17, c=17, eps_high=.4, t_fix=.8), E=64) == -5  # k > 16
+    assert route(B.make_params(k=2, c=64, eps_high=.4, t_fix=.8), E=64, wsz=1024) == -4  # (c up to E is valid)
     assert route(B.make_params(**ok, trim_mode=2)) == -2            # neither TOP nor RANDOM
     assert route(B.make_params(**ok), H=2044) == -3                 # bf16 rows need H % 8 == 0
     assert route(B.make_params(**ok), hidden=ctypes.c_void_p(0x1008)) == -3
@@ -95,6 +113,7 @@ def test_header_is_plain_c_and_links(B, tmp_path):
     src = tmp_path / "use_laser.c"
     src.write_text(
         '#include "laser.h"\n'
+        '#include "laser_bench.h"\n'
         '#include <stdio.h>\n'
         'int main(void) {\n'
         '  laser_params_t p = {0};\n'
