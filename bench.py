@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the gate kernel from rocprofv3 counters (two --pmc runs,
 # FETCH_SIZE then WRITE_SIZE, KiB per dispatch, each scaled by what the same counter
 # read for a plain 256 MiB device copy in the same run; summary under profiles/).
-# Valid only for the kernel sources they were taken on: the record carries their hash
-# and `traffic` is reported as null once the sources differ.
+# A constant taken from those runs, not measured by this program; valid only for the
+# kernel sources it was taken on: the record carries their hash and `traffic` is
+# reported as null once the sources differ.
 PMC_TRAFFIC = {
     "sources_sha256_16": "3587a7c9a1f4825a",
     "workload": "deepseek",
@@ -58,6 +59,152 @@ def algorithmic_bytes(T, H, E, k, sz):
     # expert ids and weights of every token whose choice does not depend on loads
     gate = T * H * sz + E * H * sz + T * k * 8
     return whole, gate
+
+
+def max_over_mean(loads_2d) -> float:
+    lo = loads_2d.cpu().numpy().astype(np.float64)
+    return float(np.mean(lo.max(1) / lo.mean(1)))
+
+
+class Workload:
+    """One benchmark configuration resident on the GPU: `layers` layers of inputs."""
+
+    def __init__(self, name, preset, layers=0):
+        import torch
+        from paper_2510_03293_amd import binding as B
+        from synth import workloads as wl
+        self.name, self.preset = name, preset
+        s = wl.SHAPES[name]
+        self.s = s
+        self.layers = layers or s.layers
+        self.sz = 2 if s.dtype == wl.DTYPE_BF16 else 4
+        self.hidden, self.wgate, self.params, self.host = [], [], [], []
+        for layer in range(self.layers):
+            inp = wl.layer_inputs(name, layer)
+            if layer == 0:
+                self.host.append(inp)          # kept for the oracle check of layer 0
+            self.hidden.append(torch.from_numpy(inp["hidden"].view(np.int16)).view(torch.bfloat16).cuda())
+            self.wgate.append(torch.from_numpy(inp["w_gate"].view(np.int16)).view(torch.bfloat16).cuda())
+            eps, tfix = wl.thresholds(name, layer, preset)
+            self.params.append(B.make_params(s.k, s.c, eps, tfix, dtype=s.dtype))
+        self.loads = torch.zeros((self.layers, s.E), dtype=torch.int32, device="cuda")
+        self.loads_of = [self.loads[layer] for layer in range(self.layers)]
+        self.buf = B.RouteBuffers(s.T, s.H, s.E, self.params[0])
+        self.stream = torch.cuda.current_stream()
+
+    def step(self, params=None, route=None, nlayers=None):
+        from paper_2510_03293_amd import binding as B
+        s, buf = self.s, self.buf
+        route = route or B.laser_route
+        self.loads.zero_()
+        for layer in range(nlayers or self.layers):
+            p = params if params is not None else self.params[layer]
+            route(self.hidden[layer], self.wgate[layer], s.T, s.H, s.E, p, self.loads_of[layer],
+                  buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
+                  buf.workspace, self.stream)
+
+    def measure(self, steps, warmup, event_overhead_s):
+        """Wall clock over `steps` steps (the headline), then the same steps with every
+        call's launches bracketed by HIP events: how the time divides between the fused
+        projection/analysis kernel and the tail kernel."""
+        import torch
+        from paper_2510_03293_amd import binding as B
+        s = self.s
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        imbalance = max_over_mean(self.loads)
+        us_per_layer = wall * 1e6 / (steps * self.layers)
+
+        timer = B.BenchTimer(self.layers * steps)
+        for _ in range(steps):
+            self.step(route=timer.route)
+        torch.cuda.synchronize()
+        first_ms, tail_ms = timer.read()
+        timer.close()
+        ov_us = event_overhead_s * 1e6
+        first_us = np.array(first_ms) * 1e3 - ov_us     # an event pair adds a fixed cost to what it brackets
+        tail_us = np.array(tail_ms) * 1e3 - ov_us
+        # The events give the split; the wall clock gives the total.  The kernel's
+        # duration is its share of the wall time per layer, so that the two kernels
+        # add up to the path exactly and every gap between launches is charged.
+        share = float(first_us.mean() / (first_us.mean() + tail_us.mean()))
+        whole_bytes, gate_bytes = algorithmic_bytes(s.T, s.H, s.E, s.k, self.sz)
+        return {
+            "wall_s": wall, "us_per_layer": us_per_layer, "max_over_mean_load": imbalance,
+            "gate_us": us_per_layer * share, "tail_us": us_per_layer * (1.0 - share),
+            "gate_us_events": float(first_us.mean()), "tail_us_events": float(tail_us.mean()),
+            "median_us_per_layer_events": float(np.median(first_us + tail_us)),
+            "timed_calls": int(first_us.size),
+            "whole_bytes": whole_bytes, "gate_bytes": gate_bytes,
+            "hbm_frac": whole_bytes / (us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "gate_hbm_frac": gate_bytes / (us_per_layer * share * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        }
+
+    def topk_imbalance(self):
+        """Plain top-k on the same inputs (c = k: every token keeps its k best)."""
+        import torch
+        from paper_2510_03293_amd import binding as B
+        s = self.s
+        self.step(params=B.make_params(s.k, s.k, 0.5, 0.5, dtype=s.dtype))
+        torch.cuda.synchronize()
+        return max_over_mean(self.loads)
+
+    def load_only_imbalance(self, nlayers):
+        """The load-only baseline (scores ignored: every token takes the load-aware branch
+        with all E experts as candidates), a few layers: the floor of the metric."""
+        import torch
+        from paper_2510_03293_amd import binding as B
+        s = self.s
+        p = B.make_params(s.k, s.E, 2.0, 1e-30, dtype=s.dtype)
+        wide = B.RouteBuffers(s.T, s.H, s.E, p)
+        keep, self.buf = self.buf, wide
+        try:
+            self.step(params=p, nlayers=nlayers)
+            torch.cuda.synchronize()
+            assert B.laser_status(wide.workspace) == B.STATUS_COMPLETE
+            return max_over_mean(self.loads[:nlayers])
+        finally:
+            self.buf = keep
+
+    def check_layer0(self):
+        """The timed call (no logits buffer) on layer 0 against the same call with a logits
+        buffer, bit for bit, and that one against the CPU oracle fed with the GPU's
+        logits.  Raises if anything differs."""
+        import torch
+        import oracle
+        from paper_2510_03293_amd import binding as B
+        s, inp = self.s, self.host[0]
+        outs = []
+        for want_logits in (False, True):
+            loads = torch.zeros(s.E, dtype=torch.int32, device="cuda")
+            buf = B.route(self.hidden[0], self.wgate[0], self.params[0], loads, want_logits=want_logits)
+            torch.cuda.synchronize()
+            assert B.laser_status(buf.workspace) == B.STATUS_COMPLETE
+            outs.append((buf, loads))
+        (b0, l0), (b1, l1) = outs
+        for name in ("expert_ids", "permutation", "expert_offsets"):
+            assert torch.equal(getattr(b0, name), getattr(b1, name)), f"no-logits call differs: {name}"
+        assert torch.equal(b0.weights.view(torch.int32), b1.weights.view(torch.int32)), "no-logits call differs: weights"
+        assert torch.equal(l0, l1), "no-logits call differs: loads"
+        z = b1.logits.cpu().numpy()
+        p = self.params[0]
+        ref = oracle.route(z, s.k, s.c, p.eps_high, p.t_fix, inp["loads_in"])
+        assert np.array_equal(b1.expert_ids.cpu().numpy(), ref["expert_ids"]), "expert_ids differ from the oracle"
+        assert np.array_equal(b1.permutation.cpu().numpy(), ref["permutation"]), "permutation differs from the oracle"
+        assert np.array_equal(b1.expert_offsets.cpu().numpy(), ref["expert_offsets"]), "offsets differ from the oracle"
+        assert np.array_equal(l1.cpu().numpy(), ref["loads"]), "loads differ from the oracle"
+        assert np.abs(b1.weights.cpu().numpy() - ref["weights"]).max() <= 2e-3, "weights off"
+        rows = np.arange(0, s.T, max(1, s.T // 256))
+        zz = oracle.gate(inp["hidden"][rows], inp["w_gate"], s.dtype)
+        assert np.abs(z[rows] - zz).max() <= 2e-3, "logits off"
+        return {"expanded_fraction": float(ref["expanded"].mean()),
+                "load_dependent_fraction": float((ref["cstar"] > s.k).mean())}
 
 
 def cpu_baseline(name, preset, budget_s):
@@ -102,6 +249,106 @@ def cpu_baseline(name, preset, budget_s):
     }, float(np.mean(expanded)), float(np.mean(flexible))
 
 
+def side_workload(name, preset, layers, steps, event_overhead_s, check):
+    """A second configuration, fewer layers and steps: where the time goes when a
+    material share of the tokens is load-dependent."""
+    import torch
+    w = Workload(name, preset, layers)
+    m = w.measure(steps, 2, event_overhead_s)
+    out = {
+        "workload": f"{name}-shaped gate: T={w.s.T} H={w.s.H} E={w.s.E} k={w.s.k} c={w.s.c}, {w.layers} layers, "
+                    f"preset '{preset}'",
+        "us_per_layer": m["us_per_layer"], "gate_us": m["gate_us"], "tail_us": m["tail_us"],
+        "hbm_frac": m["hbm_frac"], "gate_hbm_frac": m["gate_hbm_frac"],
+        "tokens_per_s": w.s.T / (m["us_per_layer"] * 1e-6),
+        "max_over_mean_load": m["max_over_mean_load"],
+        "max_over_mean_load_topk": w.topk_imbalance(),
+        "max_over_mean_load_loadonly": w.load_only_imbalance(min(w.layers, 1)),
+    }
+    if check:
+        out.update(w.check_layer0())
+        out["parity_checked"] = True
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
+def decode_figures(preset, extras):
+    """Decode-shaped calls (64 tokens per call, loads carried over 512 steps): eager
+    calls, the same 512 steps replayed from one HIP graph, and 16 problems per call."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    from synth import workloads as wl
+    sd = wl.SHAPES["decode"]
+    stream = torch.cuda.current_stream()
+    wdec = wl.decode_gate_weight()
+    wdec_d = torch.from_numpy(wdec.view(np.int16)).view(torch.bfloat16).cuda()
+    hdec = [torch.from_numpy(wl.layer_inputs("decode", i, w=wdec)["hidden"].view(np.int16))
+            .view(torch.bfloat16).cuda() for i in range(16)]
+    eps_d, tfix_d = wl.thresholds("decode", 0, preset)
+    p_dec = B.make_params(sd.k, sd.c, eps_d, tfix_d, dtype=sd.dtype)
+    bufd = B.RouteBuffers(sd.T, sd.H, sd.E, p_dec)
+    ld = torch.zeros(sd.E, dtype=torch.int32, device="cuda")
+
+    def decode_steps(n, s=None):
+        for i in range(n):
+            B.laser_route(hdec[i % len(hdec)], wdec_d, sd.T, sd.H, sd.E, p_dec, ld, bufd.expert_ids,
+                          bufd.weights, bufd.permutation, bufd.expert_offsets, None,
+                          bufd.workspace, s)
+    decode_steps(32, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    decode_steps(sd.layers, stream)
+    torch.cuda.synchronize()
+    extras["decode_us_per_call"] = (time.perf_counter() - t0) * 1e6 / sd.layers
+    extras["decode_tokens_per_call"] = sd.T
+
+    # the 512 steps as one HIP graph (a call only enqueues kernels, so it can be captured)
+    ld.zero_()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        decode_steps(sd.layers)          # (on the capture stream: torch's current stream)
+    ld.zero_()
+    g.replay()
+    torch.cuda.synchronize()
+    after_one = ld.clone()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        g.replay()
+    torch.cuda.synchronize()
+    extras["decode_us_per_step_graph"] = (time.perf_counter() - t0) * 1e6 / (reps * sd.layers)
+    ld.zero_()
+    decode_steps(sd.layers, stream)
+    torch.cuda.synchronize()
+    extras["decode_graph_equals_eager"] = bool(torch.equal(ld, after_one))
+    del g
+
+    nbd = len(hdec)
+    hb = torch.stack(hdec)
+    wb = wdec_d.unsqueeze(0).repeat(nbd, 1, 1).contiguous()
+    lb = torch.zeros((nbd, sd.E), dtype=torch.int32, device="cuda")
+    one = B.laser_workspace_bytes(sd.T, sd.H, sd.E, p_dec)
+    wsb = torch.empty(nbd * one, dtype=torch.uint8, device="cuda")
+    idb = torch.empty((nbd, sd.T, sd.k), dtype=torch.int32, device="cuda")
+    wtb = torch.empty((nbd, sd.T, sd.k), dtype=torch.float32, device="cuda")
+    pmb = torch.empty((nbd, sd.T * sd.k), dtype=torch.int32, device="cuda")
+    ofb = torch.empty((nbd, sd.E + 1), dtype=torch.int32, device="cuda")
+
+    def decode_batched(n):
+        for _ in range(n):
+            B.laser_route_batched(hb, wb, nbd, sd.T, sd.H, sd.E, p_dec, lb, idb, wtb, pmb, ofb, None,
+                                  wsb, stream)
+    decode_batched(8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    decode_batched(64)
+    torch.cuda.synchronize()
+    extras["batched_decode_us_per_problem"] = (time.perf_counter() - t0) * 1e6 / (64 * nbd)
+    extras["batched_decode_problems_per_call"] = nbd
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -116,6 +363,8 @@ def main():
                     help="skip the extra full-duty chain measurement (keeps kernel traces to the timed workload)")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context figures (plain read, top-k, rerun, decode calls)")
+    ap.add_argument("--no-side-workloads", action="store_true",
+                    help="skip the Mixtral- and prefill-shaped side measurements")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -130,55 +379,19 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    s = wl.SHAPES[args.workload]
-    layers = args.layers or s.layers
-    T, H, E, k, c = s.T, s.H, s.E, s.k, s.c
-    sz = 2 if s.dtype == wl.DTYPE_BF16 else 4
+    stream = torch.cuda.current_stream()
 
     # ---- inputs, resident in HBM before anything is timed --------------------
-    hidden, wgate, params = [], [], []
-    for layer in range(layers):
-        inp = wl.layer_inputs(args.workload, layer)
-        hidden.append(torch.from_numpy(inp["hidden"].view(np.int16)).view(torch.bfloat16).cuda())
-        wgate.append(torch.from_numpy(inp["w_gate"].view(np.int16)).view(torch.bfloat16).cuda())
-        eps, tfix = wl.thresholds(args.workload, layer, args.preset)
-        params.append(B.make_params(k, c, eps, tfix, dtype=s.dtype))
-    loads = torch.zeros((layers, E), dtype=torch.int32, device="cuda")
-    buf = B.RouteBuffers(T, H, E, params[0])
-    stream = torch.cuda.current_stream()
-    loads_of = [loads[layer] for layer in range(layers)]
+    w = Workload(args.workload, args.preset, args.layers)
+    s, layers = w.s, w.layers
+    T, H, E, k, c = s.T, s.H, s.E, s.k, s.c
+    event_overhead_s = B.laser_bench_event_overhead(stream) * 1e-3
+    m = w.measure(args.steps, args.warmup, event_overhead_s)
+    ms_per_step = m["wall_s"] * 1e3 / args.steps
+    tokens_per_s = T * layers * args.steps / m["wall_s"]
 
-    def step():
-        loads.zero_()
-        for layer in range(layers):
-            B.laser_route(hidden[layer], wgate[layer], T, H, E, params[layer], loads_of[layer],
-                          buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                          buf.workspace, stream)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    tokens_per_s = T * layers * args.steps / wall
-
-    # ---- the gate kernel alone, HIP events on the launch stream ---------------
-    B.laser_profile_enable(layers * args.steps)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    gate_ms, gate_launches = B.laser_profile_read()
-    B.laser_profile_enable(0)
-    # an event pair adds a fixed cost to whatever it brackets; it is measured on the
-    # spot with a kernel of known duration and taken off the per-launch average
-    event_overhead_s = B.laser_profile_event_overhead(stream) * 1e-3
-    whole_bytes, gate_bytes = algorithmic_bytes(T, H, E, k, sz)
-    gate_avg_s = gate_ms * 1e-3 / max(gate_launches, 1) - event_overhead_s
-    achieved = gate_bytes / gate_avg_s / 1e9
+    # the timed call's outputs, checked (a mismatch fails the run)
+    parity = w.check_layer0()
 
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -186,33 +399,22 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    lo = loads.cpu().numpy().astype(np.float64)
-    imbalance = float(np.mean(lo.max(1) / lo.mean(1)))
-
     # ---- the load-ordered chain at full duty: every token takes the load-aware
     # branch with c candidates (preset "stress"), a few layers, reported separately
     # because it is bound by the dependency through the counters, not by any roofline
     eps_s, tfix_s = wl.thresholds(args.workload, 0, "stress")
     p_stress = B.make_params(k, c, eps_s, tfix_s, dtype=s.dtype)
     n_stress = min(layers, 3)
-
-    def stress_pass():
-        loads.zero_()
-        for layer in range(n_stress):
-            B.laser_route(hidden[layer], wgate[layer], T, H, E, p_stress, loads_of[layer],
-                          buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                          buf.workspace, stream)
     stress = None
     if not args.no_chain_stress:
-        stress_pass()
+        w.step(params=p_stress, nlayers=n_stress)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        stress_pass()
+        w.step(params=p_stress, nlayers=n_stress)
         torch.cuda.synchronize()
         stress_us = (time.perf_counter() - t0) * 1e6 / n_stress
-        lo_s = loads[:n_stress].cpu().numpy().astype(np.float64)
         stress = {"us_per_layer": stress_us, "ns_per_load_dependent_token": stress_us * 1e3 / T,
-                  "max_over_mean_load": float(np.mean(lo_s.max(1) / lo_s.mean(1))),
+                  "max_over_mean_load": max_over_mean(w.loads[:n_stress]),
                   "note": "every token load-dependent (eps_high=2, t_fix=1e-30): chain-bound"}
 
     # ---- context figures (none of them enters `value`) --------------------------
@@ -220,35 +422,18 @@ def main():
     if not args.no_context:
         # the box's own ceiling: a plain kernel reads the same number of bytes per launch
         # as the gate kernel reads activations, from one buffer far beyond the cache
-        flat = torch.cat([h.view(torch.uint8).reshape(-1) for h in hidden])
+        flat = torch.cat([h.view(torch.uint8).reshape(-1) for h in w.hidden])
         sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-        B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
-        read_ms, read_n = B.laser_profile_plain_read(flat, T * H * sz, sink, stream)
+        B.laser_bench_plain_read(flat, T * H * w.sz, sink, stream)
+        read_ms, read_n = B.laser_bench_plain_read(flat, T * H * w.sz, sink, stream)
         read_s = (read_ms * 1e-3 - event_overhead_s) / max(read_n, 1)
-        extras["plain_read"] = {"bytes_per_launch": T * H * sz, "us_per_launch": read_s * 1e6,
-                                "GBps": T * H * sz / read_s / 1e9, "launches": read_n}
+        extras["plain_read"] = {"bytes_per_launch": T * H * w.sz, "us_per_launch": read_s * 1e6,
+                                "GBps": T * H * w.sz / read_s / 1e9, "launches": read_n,
+                                "frac_of_peak": T * H * w.sz / read_s / 1e9 / HBM_PEAK_GBS}
         del flat
 
-        # plain top-k on the same inputs (c = k: every token keeps its k best)
-        p_topk = B.make_params(k, k, 0.5, 0.5, dtype=s.dtype)
-        loads.zero_()
-        for layer in range(layers):
-            B.laser_route(hidden[layer], wgate[layer], T, H, E, p_topk, loads_of[layer],
-                          buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                          buf.workspace, stream)
-        lo_k = loads.cpu().numpy().astype(np.float64)
-        extras["max_over_mean_load_topk"] = float(np.mean(lo_k.max(1) / lo_k.mean(1)))
-        # the load-only baseline (scores ignored: every token takes the load-aware branch
-        # with all experts as candidates) needs c = E, which the kernels carry up to 16
-        if E <= 16:
-            p_lo = B.make_params(k, E, 2.0, 1e-30, dtype=s.dtype)
-            loads.zero_()
-            for layer in range(layers):
-                B.laser_route(hidden[layer], wgate[layer], T, H, E, p_lo, loads_of[layer],
-                              buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                              buf.workspace, stream)
-            lo_l = loads.cpu().numpy().astype(np.float64)
-            extras["max_over_mean_load_loadonly"] = float(np.mean(lo_l.max(1) / lo_l.mean(1)))
+        extras["max_over_mean_load_topk"] = w.topk_imbalance()
+        extras["max_over_mean_load_loadonly"] = w.load_only_imbalance(min(layers, 2))
 
         # the statistics pass (laser_route_stats): cost beside the plain call, and what
         # the synthetic gate scores look like (layer means of per-token values)
@@ -256,17 +441,13 @@ def main():
         st_ent = torch.empty(T, dtype=torch.float32, device="cuda")
         st_pool = torch.empty(T, dtype=torch.int32, device="cuda")
 
-        def stats_pass():
-            loads.zero_()
-            for layer in range(layers):
-                B.laser_route_stats(hidden[layer], wgate[layer], T, H, E, params[layer],
-                                    loads_of[layer], buf.expert_ids, buf.weights, buf.permutation,
-                                    buf.expert_offsets, None, st_mass, st_ent, st_pool,
-                                    buf.workspace, stream)
-        stats_pass()
+        def stats_route(hidden, wgate, T_, H_, E_, p, loads, ids, wts, perm, offs, logits, ws, stream_):
+            B.laser_route_stats(hidden, wgate, T_, H_, E_, p, loads, ids, wts, perm, offs, logits,
+                                st_mass, st_ent, st_pool, ws, stream_)
+        w.step(route=stats_route)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        stats_pass()
+        w.step(route=stats_route)
         torch.cuda.synchronize()
         us_stats = (time.perf_counter() - t0) * 1e6 / layers
         # the layer summaries the thresholds are chosen from, by the library's own kernel
@@ -293,11 +474,11 @@ def main():
                                         seed=20251003, stream=layer))
 
         def random_pass():
-            loads.zero_()
+            w.loads.zero_()
             for layer in range(n_rand):
-                B.laser_route(hidden[layer], wgate[layer], T, H, E, p_rand[layer], loads_of[layer],
-                              buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
-                              buf.workspace, stream)
+                B.laser_route(w.hidden[layer], w.wgate[layer], T, H, E, p_rand[layer], w.loads_of[layer],
+                              w.buf.expert_ids, w.buf.weights, w.buf.permutation, w.buf.expert_offsets, None,
+                              w.buf.workspace, stream)
         random_pass()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -308,85 +489,39 @@ def main():
 
         # the same figure from the device-side metrics (counts = loads after a step
         # that started from zero loads)
-        step()
-        im = B.laser_imbalance(loads)
+        w.step()
+        im = B.laser_imbalance(w.loads)
         torch.cuda.synchronize()
         extras["device_I_agg"] = float(im["agg"][0])
         extras["device_max_violation_mean"] = float(im["MV"].mean())
+        loads_seq = w.loads.clone()
 
         # run-to-run determinism: one layer twice into separate buffers, every output bit
-        buf2 = B.RouteBuffers(T, H, E, params[0])
+        buf2 = B.RouteBuffers(T, H, E, w.params[0])
         l1 = torch.zeros(E, dtype=torch.int32, device="cuda")
         l2 = torch.zeros_like(l1)
-        for bb, ll in ((buf, l1), (buf2, l2)):
-            B.laser_route(hidden[0], wgate[0], T, H, E, p_stress, ll, bb.expert_ids, bb.weights,
+        for bb, ll in ((w.buf, l1), (buf2, l2)):
+            B.laser_route(w.hidden[0], w.wgate[0], T, H, E, p_stress, ll, bb.expert_ids, bb.weights,
                           bb.permutation, bb.expert_offsets, None, bb.workspace, stream)
         torch.cuda.synchronize()
         extras["bit_identical_rerun"] = bool(
-            torch.equal(buf.expert_ids, buf2.expert_ids) and torch.equal(buf.permutation, buf2.permutation)
-            and torch.equal(buf.weights.view(torch.int32), buf2.weights.view(torch.int32))
-            and torch.equal(buf.expert_offsets, buf2.expert_offsets) and torch.equal(l1, l2))
+            torch.equal(w.buf.expert_ids, buf2.expert_ids) and torch.equal(w.buf.permutation, buf2.permutation)
+            and torch.equal(w.buf.weights.view(torch.int32), buf2.weights.view(torch.int32))
+            and torch.equal(w.buf.expert_offsets, buf2.expert_offsets) and torch.equal(l1, l2))
         del buf2
 
-        # decode-shaped calls (64 tokens per call, loads carried): launch-latency-bound
-        sd = wl.SHAPES["decode"]
-        wdec = wl.decode_gate_weight()
-        wdec_d = torch.from_numpy(wdec.view(np.int16)).view(torch.bfloat16).cuda()
-        hdec = [torch.from_numpy(wl.layer_inputs("decode", i, w=wdec)["hidden"].view(np.int16))
-                .view(torch.bfloat16).cuda() for i in range(16)]
-        eps_d, tfix_d = wl.thresholds("decode", 0, args.preset)
-        p_dec = B.make_params(sd.k, sd.c, eps_d, tfix_d, dtype=sd.dtype)
-        bufd = B.RouteBuffers(sd.T, sd.H, sd.E, p_dec)
-        ld = torch.zeros(sd.E, dtype=torch.int32, device="cuda")
+        decode_figures(args.preset, extras)
 
-        def decode_steps(n):
-            for i in range(n):
-                B.laser_route(hdec[i % len(hdec)], wdec_d, sd.T, sd.H, sd.E, p_dec, ld, bufd.expert_ids,
-                              bufd.weights, bufd.permutation, bufd.expert_offsets, None,
-                              bufd.workspace, stream)
-        decode_steps(32)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        decode_steps(512)
-        torch.cuda.synchronize()
-        extras["decode_us_per_call"] = (time.perf_counter() - t0) * 1e6 / 512
-        extras["decode_tokens_per_call"] = sd.T
-
-        # the batched entry point: independent problems in one call.  (a) 16 decode-sized
-        # problems; (b) all layers of the timed workload at once -- possible only where
+        # all layers of the timed workload in one batched call -- possible only where
         # their inputs exist together (micro-batches in flight at different layers), so
         # it is context, never the headline
-        nbd = len(hdec)
-        hb = torch.stack(hdec)
-        wb = wdec_d.unsqueeze(0).repeat(nbd, 1, 1).contiguous()
-        lb = torch.zeros((nbd, sd.E), dtype=torch.int32, device="cuda")
-        one = B.laser_workspace_bytes(sd.T, sd.H, sd.E, p_dec)
-        wsb = torch.empty(nbd * one, dtype=torch.uint8, device="cuda")
-        idb = torch.empty((nbd, sd.T, sd.k), dtype=torch.int32, device="cuda")
-        wtb = torch.empty((nbd, sd.T, sd.k), dtype=torch.float32, device="cuda")
-        pmb = torch.empty((nbd, sd.T * sd.k), dtype=torch.int32, device="cuda")
-        ofb = torch.empty((nbd, sd.E + 1), dtype=torch.int32, device="cuda")
-
-        def decode_batched(n):
-            for _ in range(n):
-                B.laser_route_batched(hb, wb, nbd, sd.T, sd.H, sd.E, p_dec, lb, idb, wtb, pmb, ofb, None,
-                                      wsb, stream)
-        decode_batched(8)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        decode_batched(64)
-        torch.cuda.synchronize()
-        extras["batched_decode_us_per_problem"] = (time.perf_counter() - t0) * 1e6 / (64 * nbd)
-        extras["batched_decode_problems_per_call"] = nbd
-        del hb, wb, wsb
-
-        same = all(p_.eps_high == params[0].eps_high and p_.t_fix == params[0].t_fix for p_ in params)
+        same = all(p_.eps_high == w.params[0].eps_high and p_.t_fix == w.params[0].t_fix for p_ in w.params)
         free_b, _ = torch.cuda.mem_get_info()
-        need = layers * (T * H * sz + B.laser_workspace_bytes(T, H, E, params[0]) + T * k * 12)
+        need = layers * (T * H * w.sz + B.laser_workspace_bytes(T, H, E, w.params[0]) + T * k * 12)
         if same and need < free_b // 2:
-            hall = torch.stack(hidden)
-            wall_ = torch.stack(wgate)
-            one = B.laser_workspace_bytes(T, H, E, params[0])
+            hall = torch.stack(w.hidden)
+            wall_ = torch.stack(w.wgate)
+            one = B.laser_workspace_bytes(T, H, E, w.params[0])
             wsa = torch.empty(layers * one, dtype=torch.uint8, device="cuda")
             ida = torch.empty((layers, T, k), dtype=torch.int32, device="cuda")
             wta = torch.empty((layers, T, k), dtype=torch.float32, device="cuda")
@@ -397,7 +532,7 @@ def main():
             def all_layers(n):
                 for _ in range(n):
                     la.zero_()
-                    B.laser_route_batched(hall, wall_, layers, T, H, E, params[0], la, ida, wta, pma, ofa,
+                    B.laser_route_batched(hall, wall_, layers, T, H, E, w.params[0], la, ida, wta, pma, ofa,
                                           None, wsa, stream)
             all_layers(2)
             torch.cuda.synchronize()
@@ -405,9 +540,11 @@ def main():
             all_layers(10)
             torch.cuda.synchronize()
             extras["batched_all_layers_us_per_layer"] = (time.perf_counter() - t0) * 1e6 / (10 * layers)
-            extras["batched_all_layers_equal_sequential"] = bool(torch.equal(la, loads))
+            extras["batched_all_layers_equal_sequential"] = bool(torch.equal(la, loads_seq))
             del hall, wall_, wsa
 
+    gate_bytes, whole_bytes = m["gate_bytes"], m["whole_bytes"]
+    traffic = measured_traffic_bytes(args.workload)
     out = {
         "metric": "routed tokens/sec + % HBM roofline (fused gate+route+dispatch); max/mean load",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -418,23 +555,50 @@ def main():
                         f"{layers} layers per step, thresholds preset '{args.preset}'",
             "tokens_per_layer": T, "layers": layers, "preset": args.preset,
         },
+        # the dominant kernel (fused projection + per-token analysis)
         "roofline": {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(args.workload),
-            "kernel": "gate_analyse_bf16_kernel", "avg_launch_us": gate_avg_s * 1e6,
+            "bound": "hbm", "achieved": gate_bytes / (m["gate_us"] * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": m["gate_hbm_frac"], "traffic": traffic,
+            "traffic_source": ("constant from the rocprofv3 --pmc summary under profiles/ (not measured by "
+                               "this run); null when the kernel sources have changed since"),
+            "kernel": "gate_analyse_bf16_kernel", "avg_launch_us": m["gate_us"],
+            "avg_launch_us_how": "share of the wall time per layer, split by HIP events around the launches",
+            "avg_launch_us_events": m["gate_us_events"],
             "algorithmic_bytes_per_launch": gate_bytes,
             "event_pair_overhead_us": event_overhead_s * 1e6,
-            "other_kernels_us_per_layer": ms_per_step * 1e3 / layers - gate_avg_s * 1e6,
+            "tail_kernel_us": m["tail_us"],
+            "whole_path_frac": m["hbm_frac"],
+            "target_frac": 0.60,
         },
         "whole_path": {
-            "us_per_layer": ms_per_step * 1e3 / layers,
+            "us_per_layer": m["us_per_layer"],
+            "median_us_per_layer_events": m["median_us_per_layer_events"],
+            "timed_calls_for_median": m["timed_calls"],
             "algorithmic_bytes_per_layer": whole_bytes,
-            "hbm_frac": whole_bytes / (ms_per_step * 1e-3 / layers) / 1e9 / HBM_PEAK_GBS,
+            "hbm_frac": m["hbm_frac"],
         },
-        "max_over_mean_load": imbalance,
+        "parity_checked": True,
+        "expanded_fraction_layer0": parity["expanded_fraction"],
+        "load_dependent_fraction_layer0": parity["load_dependent_fraction"],
+        "max_over_mean_load": m["max_over_mean_load"],
         "chain_stress": stress,
         "context": extras,
     }
+    if "plain_read" in extras:
+        pr = extras["plain_read"]["us_per_launch"]
+        out["roofline"]["frac_of_plain_read"] = pr / m["gate_us"]
+        out["whole_path"]["frac_of_plain_read"] = pr / m["us_per_layer"]
+
+    # ---- other configurations, where tokens are load-dependent -------------------
+    if not args.no_side_workloads:
+        del w
+        torch.cuda.empty_cache()
+        side = {}
+        for name, nl, st in (("mixtral", 4, 10), ("prefill", 1, 10)):
+            if name != args.workload:
+                side[name] = side_workload(name, "paper", nl, st, event_overhead_s, check=(name == "mixtral"))
+        out["workloads"] = side
+
     if not args.no_cpu_baseline:
         base, expanded, flexible = cpu_baseline(args.workload, args.preset, args.cpu_seconds)
         out["cpu_baseline"] = base
