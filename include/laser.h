@@ -243,6 +243,23 @@ const char* laser_strerror(int code);
  */
 int laser_status(const void* workspace, void* hip_stream, int32_t* status);
 
+/*
+ * laser_route for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is an array inside the library (one per GPU, held until the
+ * process ends) of laser_static_workspace_bytes() bytes; a call whose
+ * laser_workspace_bytes(T, H, E, params) exceeds that returns LASER_E_WORKSPACE.  The
+ * call allocates nothing and otherwise behaves as laser_route.  All such calls on one
+ * GPU share the array: they must be ordered (one stream, or events), calls that overlap
+ * race.  laser_status_static() is laser_status() for the current device's array.
+ */
+size_t laser_static_workspace_bytes(void);
+int laser_route_static(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                       const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                       float* weights, int32_t* permutation, int32_t* expert_offsets,
+                       float* logits_out, void* hip_stream);
+int laser_status_static(void* hip_stream, int32_t* status);
+
 #ifdef __cplusplus
 }
 #endif

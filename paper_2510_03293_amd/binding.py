@@ -22,7 +22,8 @@ TRIM_RANDOM = 1
 # include/laser.h
 EXPORTS = ("laser_workspace_bytes", "laser_route", "laser_route_batched", "laser_route_stats",
            "laser_route_from_logits", "laser_imbalance", "laser_percentiles", "laser_summary_f32",
-           "laser_strerror", "laser_status")
+           "laser_strerror", "laser_status", "laser_static_workspace_bytes", "laser_route_static",
+           "laser_status_static")
 # include/laser_bench.h
 BENCH_EXPORTS = ("laser_bench_timer_create", "laser_bench_timer_destroy", "laser_bench_route",
                  "laser_bench_timer_read", "laser_bench_event_overhead", "laser_bench_plain_read")
@@ -84,6 +85,12 @@ def _load() -> ctypes.CDLL:
     lib.laser_strerror.restype = ctypes.c_char_p
     lib.laser_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.laser_status.restype = ctypes.c_int
+    lib.laser_static_workspace_bytes.argtypes = []
+    lib.laser_static_workspace_bytes.restype = sz
+    lib.laser_route_static.argtypes = [vp, vp, i32, i32, i32, pp, vp, vp, vp, vp, vp, vp, vp]
+    lib.laser_route_static.restype = ctypes.c_int
+    lib.laser_status_static.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.laser_status_static.restype = ctypes.c_int
     lib.laser_bench_timer_create.argtypes = [i32, ctypes.POINTER(vp)]
     lib.laser_bench_timer_create.restype = ctypes.c_int
     lib.laser_bench_timer_destroy.argtypes = [vp]
@@ -214,6 +221,24 @@ def laser_status(workspace, stream=None) -> int:
     """STATUS_* of the last call that used `workspace` (waits for the stream)."""
     st = ctypes.c_int32(-1)
     _check(_lib.laser_status(_ptr(workspace), _stream_handle(stream), ctypes.byref(st)))
+    return st.value
+
+
+def laser_static_workspace_bytes() -> int:
+    return int(_lib.laser_static_workspace_bytes())
+
+
+def laser_route_static(hidden, w_gate, T, H, E, params, loads_inout, expert_ids, weights,
+                       permutation, expert_offsets, logits_out, stream=None) -> None:
+    """laser_route on the library's own per-GPU workspace (nothing is allocated)."""
+    _check(_lib.laser_route_static(_ptr(hidden), _ptr(w_gate), T, H, E, ctypes.byref(params),
+                                   _ptr(loads_inout), _ptr(expert_ids), _ptr(weights), _ptr(permutation),
+                                   _ptr(expert_offsets), _ptr(logits_out), _stream_handle(stream)))
+
+
+def laser_status_static(stream=None) -> int:
+    st = ctypes.c_int32(-1)
+    _check(_lib.laser_status_static(_stream_handle(stream), ctypes.byref(st)))
     return st.value
 
 

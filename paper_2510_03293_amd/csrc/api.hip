@@ -215,11 +215,58 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   return LASER_OK;
 }
 
+// ---- the workspace of laser_route_static ------------------------------------------
+// One array per GPU, part of the library's code object: it exists from the moment the
+// library is loaded on a device until the process ends.  In host code the array's name
+// is only a handle for the runtime's symbol lookup, not a device address; the address
+// on each device is looked up once (with that device current) and kept.
+constexpr size_t kStaticBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+struct StaticWorkspace {
+  void* ptr[kMaxDevices] = {};
+};
+static StaticWorkspace g_static;
+
+// The current device's copy of the array, or NULL if the lookup failed.
+static void* static_workspace() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  if (g_static.ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_static.ptr[dev] = p;
+  }
+  return g_static.ptr[dev];
+}
+
 }  // namespace laser
 
 using namespace laser;
 
 extern "C" {
+
+size_t laser_static_workspace_bytes(void) { return kStaticBytes; }
+
+int laser_route_static(const void* hidden, const void* w_gate, int32_t T, int32_t H, int32_t E,
+                       const laser_params_t* params, int32_t* loads_inout, int32_t* expert_ids,
+                       float* weights, int32_t* permutation, int32_t* expert_offsets,
+                       float* logits_out, void* hip_stream) {
+  const int rc = check_params(T, E, params);
+  if (rc != LASER_OK) return rc;
+  if (workspace_bytes(T, E, record_width(params->c)) > kStaticBytes) return LASER_E_WORKSPACE;
+  void* ws = static_workspace();
+  if (!ws) return LASER_E_LAUNCH;
+  return route_impl(hidden, w_gate, 1, T, H, E, params, loads_inout, expert_ids, weights, permutation,
+                    expert_offsets, logits_out, nullptr, nullptr, nullptr, ws, kStaticBytes, hip_stream,
+                    nullptr);
+}
+
+int laser_status_static(void* hip_stream, int32_t* status) {
+  void* ws = static_workspace();
+  if (!ws) return LASER_E_LAUNCH;
+  return laser_status(ws, hip_stream, status);
+}
 
 size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params_t* params) {
   if (check_params(T, E, params) != LASER_OK || H < 0) return 0;
