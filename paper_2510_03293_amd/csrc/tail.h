@@ -628,6 +628,342 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
   return decided;
 }
 
+// ---- window of 128 tokens, two consumer wavefronts -----------------------------------
+//
+// Where tokens rarely compete (many experts behind each candidate: the variants with
+// first guesses) a sweep usually retires most of its window, so a wider window decides
+// more tokens for the same chain of dependent steps.  Waves 0 and 1 each hold 64 of the
+// 128 window positions (position = flexible token number mod 128; wave = position / 64,
+// lane = position mod 64) and evaluate them exactly as above; an expert's tentative
+// choices are a 128-bit mask, of which each consumer wave writes only its own half.
+// A sweep has two workgroup barriers that settle LDS traffic only: after the
+// evaluation both waves publish which of their lanes changed, so that every wave finds
+// the same first changed token; after the retirement (each consumer wave, lane =
+// expert, retires its own half of the masks) the next evaluation may read.  Waves 2
+// and 3 take part in the barriers and in between stage the per-token data into an LDS
+// ring of 512 tokens: each stages 64 tokens per sweep, with the three dependent loads of
+// a token (its slot, its record, the counters of its candidates) spread over three
+// sweeps so that none of them is waited for.  Decided bits go to a small ring of output
+// words in LDS; wave 3 writes out the words that are complete.
+constexpr int kRing2 = 512;         // tokens in the LDS ring
+constexpr int kSpecOutWords = 16;   // output staging ring, words of 32 tokens
+
+// Only LDS traffic has to be settled at these barriers; loads from memory that are in
+// flight (the producers' pipeline) stay in flight across them.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+struct __align__(16) SpecExp2 {
+  unsigned long long mask[2];  // window positions 0..63 / 64..127 that tentatively chose the expert
+  int G;                       // final flexible choices of the expert so far
+  int pad[3];
+};
+struct SpecShared2 {
+  SpecExp2 M[64];
+  unsigned obits[kSpecOutWords][64];  // per expert: chosen bits of 32 flexible tokens, not yet written out
+  unsigned long long bal[2][2];       // [sweep parity][consumer wave]: lanes whose choice changed
+  int staged[2][2];                   // [sweep parity][producer wave]: tokens below this number are in the ring
+  int pub_done[2], pub_flags[2];      // [sweep parity] written by wave 0 before the second barrier
+  int lin_tab[64];
+};
+constexpr int kShared2Offset = kRing2 * (int)sizeof(SpecTok<16>);
+static_assert(kShared2Offset + (int)sizeof(SpecShared2) <= kChainLdsBytes, "ring and state must fit the chain LDS");
+
+// The positions before x of the 128-position ring, as two 64-bit halves.
+__device__ __forceinline__ void below128(int x, unsigned long long& lo, unsigned long long& hi) {
+  lo = x >= 64 ? ~0ull : (1ull << x) - 1ull;
+  hi = x > 64 ? (x >= 128 ? ~0ull : (1ull << (x - 64)) - 1ull) : 0ull;
+}
+
+// Runs the window evaluation from flexible token 0 (see spec_walk for the contract).
+template <int CP, int KK>
+__device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const RouteArgs& a, const Workspace& ws,
+                                          int wave, int lane, int lin, int& gflex, unsigned& hist) {
+  nflex_tok = __builtin_amdgcn_readfirstlane(nflex_tok);
+  SpecTok<CP>* ring = reinterpret_cast<SpecTok<CP>*>(lds);
+  SpecShared2& S = *reinterpret_cast<SpecShared2*>(lds + kShared2Offset);
+  SpecExp2* M = S.M;
+  const int k = KK > 0 ? KK : a.k;
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    M[tid].mask[0] = M[tid].mask[1] = 0ull;
+    M[tid].G = 0;
+    S.lin_tab[tid] = lin;
+  }
+  for (int i = tid; i < kSpecOutWords * 64; i += kTailThreads) (&S.obits[0][0])[i] = 0u;
+  if (tid < 4) (&S.bal[0][0])[tid] = 0ull;
+  if (tid < 4) (&S.staged[0][0])[tid] = 0;
+  if (tid < 2) {
+    S.pub_done[tid] = 0;
+    S.pub_flags[tid] = 2;  // (bit 0: give up, bit 1: first guesses in use)
+  }
+  __syncthreads();
+
+  const bool consumer = wave < 2;
+  const int pw = wave & 1;  // consumer: which half of the window; producer: which half of a batch
+  const unsigned long long lane_bit = 1ull << lane, lb = lanes_below(lane);
+
+  // ---- consumer state ------------------------------------------------------------------
+  int ex[CP];       // candidate experts by rank
+  unsigned b[CP];   // their counters without flexible choices
+#pragma unroll
+  for (int j = 0; j < CP; ++j) {
+    ex[j] = 0;
+    b[j] = kSpecInvalid;
+  }
+  unsigned sel = 0;
+  int cur_f = -1;  // token whose data this lane holds
+
+  // ---- producer state: batch n of a producer is the tokens 128 n + 64 pw + lane ----------
+  // in flight: the slot of batch nb + 2, slot and record of batch nb + 1, and for batch
+  // nb the record (arrived) whose candidates' counters are fetched in the sweep it is staged
+  int nb = 0;
+  int slot0 = 0, slot1 = 0, slot2 = 0;
+  uint4 ids1 = make_uint4(0, 0, 0, 0), pref1 = ids1, ids2 = ids1, pref2 = ids1;
+  auto tok = [&](int n) { return 128 * n + 64 * pw + lane; };
+  if (!consumer) {
+    slot2 = tok(0) < nflex_tok ? ws.flex_slot[tok(0)] : 0;
+    slot1 = tok(1) < nflex_tok ? ws.flex_slot[tok(1)] : 0;
+    slot0 = tok(2) < nflex_tok ? ws.flex_slot[tok(2)] : 0;
+    ids2 = reinterpret_cast<const uint4*>(ws.rec_cids)[slot2];
+    pref2 = reinterpret_cast<const uint4*>(ws.rec_pref)[slot2];
+    ids1 = reinterpret_cast<const uint4*>(ws.rec_cids)[slot1];
+    pref1 = reinterpret_cast<const uint4*>(ws.rec_pref)[slot1];
+  }
+
+  int done = 0, avail = 0;  // tokens decided, tokens in the ring (both uniform, the same in every wave)
+  int sweeps = 0, done_mark = 0, total_sweeps = 0;
+  bool bail = false, guess_on = true;
+  int wout = 0, gflushed = 0;  // wave 3, lane = expert: output words written, their bits so far
+
+  for (;;) {
+    const int par = total_sweeps & 1;
+    const int head = done & 127;
+    if (consumer) {
+      // ---- this lane's token of the window [done, done + 128) -----------------------------
+      const int pos = 64 * pw + lane;
+      const int f_lane = done + ((pos - head) & 127);
+      const bool enters = f_lane < avail && cur_f != f_lane;
+      if (enters) {
+        const SpecTok<CP>* src = &ring[f_lane & (kRing2 - 1)];
+        const uint4 ids = src->ids;
+        const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
+        sel = 0;
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+          ex[j] = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+          b[j] = src->b[j];  // (bit 31, the guess, drops out of the key's shift below)
+        }
+        if (guess_on) {
+#pragma unroll
+          for (int j = 0; j < CP; ++j) sel |= (b[j] >> 31) << j;  // the producer's first guess
+        }
+        cur_f = f_lane;
+      }
+      const bool valid = cur_f == f_lane;
+      if (!valid) sel = 0;
+      if (guess_on && __builtin_amdgcn_ballot_w64(enters) != 0ull) {
+        // the guesses join the masks before this wave counts (the lane's bit is clear:
+        // the token that held the lane took its bits along when it retired)
+        if (enters) {
+#pragma unroll
+          for (int j = 0; j < CP; ++j)
+            if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+      }
+      // the window positions before this one: from the head up to pos, cyclically
+      unsigned long long bh0, bh1;
+      below128(head, bh0, bh1);
+      const unsigned long long bp0 = pw ? ~0ull : lb, bp1 = pw ? lb : 0ull;
+      const bool ge = pos >= head;
+      const unsigned long long e0 = ge ? (bp0 & ~bh0) : (bp0 | ~bh0);
+      const unsigned long long e1 = ge ? (bp1 & ~bh1) : (bp1 | ~bh1);
+      unsigned key[CP];
+#pragma unroll
+      for (int j = 0; j < CP; ++j) {
+        const uint4 m = *reinterpret_cast<const uint4*>(&M[ex[j]]);  // the two halves of the mask
+        const unsigned g = (unsigned)M[ex[j]].G;
+        const unsigned cnt = (unsigned)(__builtin_popcount(m.x & (unsigned)e0) + __builtin_popcount(m.y & (unsigned)(e0 >> 32)) +
+                                        __builtin_popcount(m.z & (unsigned)e1) + __builtin_popcount(m.w & (unsigned)(e1 >> 32)));
+        key[j] = ((b[j] + g + cnt) << 4) | (unsigned)j;
+      }
+      unsigned newsel = smallest_k_slots<CP, KK>(key, k);
+      newsel = valid ? newsel : 0u;
+      const unsigned diff = sel ^ newsel;
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(diff != 0u);
+      if (bal != 0ull) {
+        // flip this lane's bit in the masks of the experts whose choice changed
+#pragma unroll
+        for (int j = 0; j < CP; ++j)
+          if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
+      }
+      sel = newsel;
+      if (lane == 0) S.bal[par][pw] = bal;
+    } else {
+      // ---- producer: stage batch nb if the ring has room for it ----------------------------
+      // (the ring holds the tokens [done, done + kRing2); `done` is at most one sweep old)
+      if (128 * nb + 128 <= done + kRing2 && 128 * nb < nflex_tok) {
+        const int f = tok(nb);
+        const bool live = f < nflex_tok;
+        const unsigned idw[4] = {ids2.x, ids2.y, ids2.z, ids2.w};
+        const unsigned pfw[4] = {pref2.x, pref2.y, pref2.z, pref2.w};
+        const int tile = slot2 >> 6;
+        int base[CP];
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+          const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+          base[j] = ws.tile_base[(size_t)tile * 64 + e] + S.lin_tab[e];
+        }
+        // the loads of the batches behind it: asked for now, used one and two sweeps on
+        const uint4 ids_n = reinterpret_cast<const uint4*>(ws.rec_cids)[slot0];
+        const uint4 pref_n = reinterpret_cast<const uint4*>(ws.rec_pref)[slot0];
+        const int slot_n = tok(nb + 3) < nflex_tok ? ws.flex_slot[tok(nb + 3)] : 0;
+        unsigned bj[CP], key[CP];
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+          const unsigned pf = (pfw[j >> 2] >> (8 * (j & 3))) & 255u;
+          const int e = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+          bj[j] = pf == 0xFFu ? kSpecInvalid : (unsigned)base[j] + pf;
+          // (the guess also counts the flexible choices that are final by now: a few
+          // hundred tokens stale when this token enters the window, better than none)
+          key[j] = ((bj[j] + (unsigned)M[e].G) << 4) | (unsigned)j;
+        }
+        const unsigned guess = smallest_k_slots<CP, KK>(key, k);
+        if (live) {
+          SpecTok<CP>* dst = &ring[f & (kRing2 - 1)];
+          dst->ids = ids2;
+#pragma unroll
+          for (int j = 0; j < CP; ++j) dst->b[j] = bj[j] | (((guess >> j) & 1u) << 31);
+        }
+        slot2 = slot1;
+        ids2 = ids1;
+        pref2 = pref1;
+        slot1 = slot0;
+        ids1 = ids_n;
+        pref1 = pref_n;
+        slot0 = slot_n;
+        ++nb;
+      }
+      // (by sweep parity: a producer that is already in the next sweep must not change what
+      // a consumer still reads after the second barrier of this one)
+      if (lane == 0) S.staged[par][pw] = 128 * nb;
+    }
+    lds_barrier();
+
+    if (consumer) {
+      // ---- tokens up to the first changed one are final ------------------------------------
+      unsigned long long c0 = S.bal[par][0], c1 = S.bal[par][1];
+      c0 = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c0 >> 32)) << 32) |
+           (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c0);
+      c1 = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c1 >> 32)) << 32) |
+           (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c1);
+      if (head >= 64) {
+        const unsigned long long t = c0;
+        c0 = c1;
+        c1 = t;
+      }
+      const int sh = head & 63;
+      const unsigned long long r0 = sh ? (c0 >> sh) | (c1 << (64 - sh)) : c0;
+      const unsigned long long r1 = sh ? (c1 >> sh) | (c0 << (64 - sh)) : c1;
+      const int q = r0 ? __builtin_ctzll(r0) : r1 ? 64 + __builtin_ctzll(r1) : 128;
+      const int fin = min(min(q + 1, 128), avail - done);
+      // ---- lane = expert: this wave's half of the window positions head .. head + fin - 1
+      if (fin > 0) {
+        unsigned long long lo0, hi0, lo1, hi1;
+        below128(head, lo0, hi0);
+        const int end = head + fin;  // (up to 255: the range may wrap)
+        below128(end > 128 ? 128 : end, lo1, hi1);
+        unsigned long long ret0 = lo1 & ~lo0, ret1 = hi1 & ~hi0;  // head .. min(end, 128) - 1
+        if (end > 128) {
+          unsigned long long wl, wh;
+          below128(end - 128, wl, wh);
+          ret0 |= wl;
+          ret1 |= wh;
+        }
+        const unsigned long long mine = pw ? ret1 : ret0;
+        const unsigned long long mk = M[lane].mask[pw];
+        const unsigned long long fb = mk & mine;
+        // (unconditional: lanes without retiring bits add nothing)
+        atomicAdd(&M[lane].G, __builtin_popcountll(fb));
+        M[lane].mask[pw] = mk & ~mine;
+        // a quarter of the mask (32 positions) is bit-aligned with the output word of its
+        // tokens; only the quarter of the head can hold tokens of two words (the positions
+        // below the head belong to tokens four words on)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int qi = 2 * pw + h;              // quarter of the ring
+          const unsigned qb = (unsigned)(fb >> (32 * h));
+          const int cut = (head >> 5) == qi ? (head & 31) : 0;
+          const int first = (done + ((32 * qi + cut - head) & 127)) >> 5;  // word of the positions >= cut
+          const unsigned below_cut = (1u << cut) - 1u;
+          atomicOr(&S.obits[first & (kSpecOutWords - 1)][lane], qb & ~below_cut);
+          if (cut != 0) atomicOr(&S.obits[(first + 4) & (kSpecOutWords - 1)][lane], qb & below_cut);
+        }
+      }
+      if (wave == 0) {
+        int d = done + fin;
+        bool gv = bail, gg = guess_on;
+        int sw = sweeps + 1, dm = done_mark;
+        if (sw == kSpecCheckSweeps) {
+          // give up only if both the last run of sweeps and the average so far are
+          // below break-even: the switch is one-way
+          if (d - dm < spec_min_progress(CP) && d * kSpecCheckSweeps < spec_min_progress(CP) * (total_sweeps + 1) &&
+              nflex_tok - d > 2 * kSpecSeg && avail - done >= 128)
+            gv = true;
+          gg = d - dm >= kSpecGuessProgress;
+        }
+        if (lane == 0) {
+          S.pub_done[par] = d;
+          S.pub_flags[par] = (gv ? 1 : 0) | (gg ? 2 : 0);
+        }
+      }
+    }
+    lds_barrier();
+
+    // ---- every wave takes over the books ------------------------------------------------
+    done = __builtin_amdgcn_readfirstlane(S.pub_done[par]);
+    const int flags = __builtin_amdgcn_readfirstlane(S.pub_flags[par]);
+    bail = (flags & 1) != 0;
+    avail = min(nflex_tok, min(__builtin_amdgcn_readfirstlane(S.staged[par][0]),
+                               __builtin_amdgcn_readfirstlane(S.staged[par][1])));
+    ++total_sweeps;
+    if (++sweeps == kSpecCheckSweeps) {
+      guess_on = (flags & 2) != 0;
+      sweeps = 0;
+      done_mark = done;
+    }
+    // ---- output words that are complete (wave 3, lane = expert) ---------------------------
+    if (wave == kChainWaves - 1) {
+      while (32 * (wout + 1) <= done) {
+        unsigned* slot = &S.obits[wout & (kSpecOutWords - 1)][lane];
+        const unsigned word = *slot;
+        *slot = 0u;
+        gflushed += __builtin_popcount(word);
+        ws.chain_bits[(size_t)wout * 64 + lane] = word;
+        ws.chain_cum[(size_t)(wout + 1) * 64 + lane] = gflushed;
+        ++wout;
+      }
+    }
+    // (every sweep with tokens in the ring retires at least one, and the ring refills
+    // within two sweeps; the cap only keeps a mistake from turning into an endless loop:
+    // the sequential walk then takes over, and the result is still exact)
+    if (total_sweeps > nflex_tok + (nflex_tok >> 5) + 64) bail = true;
+    if (done >= nflex_tok || bail) break;
+  }
+  const int decided = done;
+  if (wave == 0) {
+    gflex = M[lane].G;
+    hist = S.obits[(decided >> 5) & (kSpecOutWords - 1)][lane];  // the decided % 32 bits of the unfinished word
+    if (decided == nflex_tok && (decided & 31) != 0) ws.chain_bits[(size_t)(decided >> 5) * 64 + lane] = hist;
+    if (lane == 0) ws.status[kStatusSweeps] = total_sweeps;
+  }
+  __syncthreads();  // the ring is dead: the sequential walk may reuse the LDS
+  return decided;
+}
+
 __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
                                 int32_t* __restrict__ loads_inout,
                                 int32_t* __restrict__ expert_offsets) {
@@ -764,14 +1100,11 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     }
     if (f) ws.flex_list[ord] = tile;
     if (use_spec) {
-      // slot (tile * 64 + rank among the tile's flexible tokens) of every flexible token
+      // slot (tile * 64 + rank among the tile's flexible tokens) of every flexible token:
+      // every lane lists its own tile's
       const int mybase = tokbefore + incl - np;
-      for (unsigned long long rem = bal; rem != 0ull; rem &= rem - 1ull) {
-        const int src = __builtin_ctzll(rem);
-        const int fbase = __builtin_amdgcn_readlane(mybase, src);
-        const int n_src = __builtin_amdgcn_readlane(np, src);
-        if (lane < n_src) ws.flex_slot[fbase + lane] = ((g * 64 + src) << 6) + lane;
-      }
+      for (int i = 0; __builtin_amdgcn_ballot_w64(i < np) != 0ull; ++i)
+        if (i < np) ws.flex_slot[mybase + i] = (tile << 6) + i;
     }
     fbefore += __builtin_popcountll(bal);
     tokbefore += __shfl(incl, 63, 64);
@@ -806,8 +1139,10 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   if (use_spec) {
     // First guesses (GUESS) where tokens rarely compete: many experts per candidate.
     // With few experts every sweep ends at an early conflict and they only cost.
+    // (with few experts every sweep ends at an early conflict and the guesses only cost:
+    // one consumer wave, a window of 64)
 #define LASER_SPEC_WALK(CP_, KK_)                                                                   \
-  (a.E >= 4 * CP_ ? spec_walk<CP_, KK_, true>(lds, spec_sh, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
+  (a.E >= 4 * CP_ ? spec_walk2<CP_, KK_>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
                   : spec_walk<CP_, KK_, false>(lds, spec_sh, nflex_tok, a, ws, wave, lane, lin, gflex, hist0))
     if (a.c <= 4) {
       decided = a.k == 2 ? LASER_SPEC_WALK(4, 2) : LASER_SPEC_WALK(4, 0);

@@ -78,15 +78,18 @@ def test_route_from_logits(T, E, k, c, eps, tfix, kind, renorm):
                         label=f"T{T} E{E} k{k} c{c} {kind}")
 
 
-# The chain decides flexible tokens 64 at a time where that pays (a window advancing
-# over them, data staged in segments of 192 through a ring of 576) and one by one
-# otherwise, switching over at an arbitrary token.  Every token here is flexible
+# The chain decides flexible tokens a window at a time where that pays and one by one
+# otherwise, switching over at an arbitrary token.  Two window evaluations exist: 64
+# tokens in one wavefront, data staged in segments of 192 through a ring of 576; and
+# (many experts per candidate) 128 tokens in two wavefronts, data staged in batches of
+# 128 through a ring of 512, output words of 32 tokens.  Every token here is flexible
 # (eps_high = 2, tiny t_fix), so T is the number of flexible tokens.
-WINDOW_SIZES = [191, 192, 193, 255, 256, 257, 383, 384, 385, 511, 513, 575, 576, 577, 1025, 2000]
+WINDOW_SIZES = [191, 192, 193, 255, 256, 257, 287, 288, 289, 383, 384, 385, 511, 512, 513, 575, 576, 577,
+                639, 640, 641, 1023, 1024, 1025, 1151, 1153, 2000, 4097]
 
 
 @pytest.mark.parametrize("T", WINDOW_SIZES)
-@pytest.mark.parametrize("E,k,c", [(64, 6, 8), (8, 2, 4), (40, 3, 16)])
+@pytest.mark.parametrize("E,k,c", [(64, 6, 8), (8, 2, 4), (40, 3, 16), (64, 2, 4), (33, 5, 8), (64, 9, 16)])
 def test_window_chain_sizes(T, E, k, c):
     u = _util()
     rng = np.random.default_rng(T * 7 + E)
@@ -123,6 +126,26 @@ def test_window_chain_gives_way_to_sequential(E, k, c, T1, T2):
     logits = np.concatenate([a, np.repeat(row, T2, axis=0)], axis=0)
     loads_in = rng.integers(0, 50, size=E).astype(np.int32)
     u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"handover E{E} c{c} {T1}+{T2}")
+
+
+@pytest.mark.parametrize("scale,loads_hi", [(3.0, 1), (1.0, 50), (0.3, 1000), (0.02, 3)])
+@pytest.mark.parametrize("E,k,c", [(64, 6, 8), (64, 2, 4), (64, 4, 16)])
+def test_wide_window_regimes(E, k, c, scale, loads_hi):
+    """The 128-token window from windows that retire whole (peaked scores, unrelated
+    candidate sets) down to neighbours that all compete (flat scores: it gives up and the
+    sequential walk finishes), flexible tokens dense and sparse inside their tiles."""
+    u = _util()
+    T = 6000
+    rng = np.random.default_rng(int(scale * 100) + E + c)
+    z = wl.random_logits(17 + c, T, E, kind="normal", scale=scale)
+    loads_in = rng.integers(0, loads_hi, size=E).astype(np.int32)
+    gpu, ref = u.check_from_logits(z, k, c, 2.0, 1e-30, loads_in, label=f"wide window dense s{scale} c{c}")
+    peaked = wl.random_logits(5, T, E, kind="normal", scale=4.0)
+    pick = rng.random(T) < 0.15
+    flat = wl.random_logits(6, T, E, kind="normal", scale=min(scale, 0.2))
+    mixed = np.where(pick[:, None], flat, peaked).astype(np.float32)
+    gpu, ref = u.check_from_logits(mixed, k, c, 0.6, 0.5, loads_in, label=f"wide window sparse s{scale} c{c}")
+    assert int((ref["cstar"] > k).sum()) > 256
 
 
 def test_window_chain_long_run():
