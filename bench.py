@@ -31,10 +31,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # kernel sources it was taken on: the record carries their hash and `traffic` is
 # reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "3587a7c9a1f4825a",
+    "sources_sha256_16": "a1cd1fd9f2dbb0b3",
     "workload": "deepseek",
-    "fetch_kib": 33904.92, "fetch_scale": 1.9997,
-    "write_kib": 994.33, "write_scale": 1.0,
+    "fetch_kib": 33902.35, "fetch_scale": 1.9997,
+    "write_kib": 1024.23, "write_scale": 1.0,
 }
 GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
 
