@@ -87,6 +87,13 @@ __device__ __forceinline__ unsigned load_published(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Orders this wavefront's LDS traffic (another lane's write before this lane's read)
+// without waiting for anything in flight to memory: a fence at workgroup scope would
+// also wait for the chain's output stores.
+__device__ __forceinline__ void lds_wave_fence() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
 __device__ __forceinline__ bool poll_flag(const int* flag, int want, long long limit) {
   for (long long it = 0; it < limit; ++it) {
     const int seen = __builtin_amdgcn_readfirstlane(
@@ -535,7 +542,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
             for (int j = 0; j < CP; ++j)
               if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
           }
-          __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+          lds_wave_fence();
           __builtin_amdgcn_wave_barrier();
         }
         const unsigned long long hb = lanes_below(head);
@@ -564,7 +571,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
         const int q = rot ? __builtin_ctzll(rot) : 64;
         // (without guesses more than 32 is rare: a token needs a sweep to get a choice)
         const int fin = min(min(q + 1, avail - done), GUESS ? 64 : 32);
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        lds_wave_fence();
         __builtin_amdgcn_wave_barrier();
         {  // lane = expert
           unsigned long long mk = M[lane].mask;
@@ -593,7 +600,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
           M[lane].mask = mk;
           M[lane].G = G;
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        lds_wave_fence();
         __builtin_amdgcn_wave_barrier();
         done += fin;
         ++total_sweeps;
@@ -771,7 +778,7 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
           for (int j = 0; j < CP; ++j)
             if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        lds_wave_fence();
         __builtin_amdgcn_wave_barrier();
       }
       // the window positions before this one: from the head up to pos, cyclically
