@@ -98,7 +98,7 @@ class Workload:
         route = route or B.laser_route
         self.loads.zero_()
         for layer in range(nlayers or self.layers):
-            p = params if params is not None else self.params[layer]
+            p = self.params[layer] if params is None else (params[layer] if isinstance(params, list) else params)
             route(self.hidden[layer], self.wgate[layer], s.T, s.H, s.E, p, self.loads_of[layer],
                   buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, None,
                   buf.workspace, self.stream)
@@ -265,6 +265,22 @@ def side_workload(name, preset, layers, steps, event_overhead_s, check):
         "max_over_mean_load_topk": w.topk_imbalance(),
         "max_over_mean_load_loadonly": w.load_only_imbalance(min(w.layers, 1)),
     }
+    # Batches of 64 K tokens and more are pipelined (the walk over a segment's
+    # load-dependent tokens runs inside the projection kernel while later segments
+    # stream): the same call with the pipeline switched off, for comparison.
+    from paper_2510_03293_amd import binding as B
+    from synth import workloads as wl
+    out["pipelined"] = bool(w.s.T >= 65280)
+    if out["pipelined"]:
+        off = [B.make_params(w.s.k, w.s.c, *wl.thresholds(name, layer, preset), dtype=w.s.dtype,
+                             pipeline_tiles=1) for layer in range(w.layers)]
+        w.step(params=off)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.step(params=off)
+        torch.cuda.synchronize()
+        out["us_per_layer_not_pipelined"] = (time.perf_counter() - t0) * 1e6 / (steps * w.layers)
     if check:
         out.update(w.check_layer0())
         out["parity_checked"] = True

@@ -103,6 +103,15 @@ typedef struct laser_params {
   uint32_t poll_budget;  /* 0: the library sizes its bounded waits from T (millions of */
                          /* polls); otherwise the number of polls after which a waiting */
                          /* workgroup gives up (see "Completion" above)                 */
+  uint32_t pipeline_tiles; /* Large bf16 calls of laser_route are pipelined: the walk over */
+                         /* the load-dependent tokens of a segment of the batch (Algorithm */
+                         /* 1 orders the tokens, so it needs nothing of later tokens) runs */
+                         /* while the projection of the later segments still streams.      */
+                         /* 0: the library decides (segments of about 32 K tokens for      */
+                         /* batches of 64 K tokens or more); 1: never; n >= 2: segments of */
+                         /* n tiles of 64 tokens whenever the batch has more tiles.  The   */
+                         /* results do not depend on it.                                   */
+  uint32_t reserved;     /* 0                                                           */
 } laser_params_t;
 
 /* Bytes of device workspace a call with these sizes needs (0 on bad arguments).

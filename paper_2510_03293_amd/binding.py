@@ -47,6 +47,8 @@ class LaserParams(ctypes.Structure):
         ("token_offset", ctypes.c_uint64),
         ("stream", ctypes.c_uint32),
         ("poll_budget", ctypes.c_uint32),
+        ("pipeline_tiles", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -113,9 +115,11 @@ _lib = _load()
 
 def make_params(k: int, c: int, eps_high: float, t_fix: float, dtype: int = DTYPE_BF16,
                 renormalize: bool = True, trim_mode: int = TRIM_TOP, seed: int = 0,
-                stream: int = 0, token_offset: int = 0, poll_budget: int = 0) -> LaserParams:
+                stream: int = 0, token_offset: int = 0, poll_budget: int = 0,
+                pipeline_tiles: int = 0) -> LaserParams:
     return LaserParams(ctypes.sizeof(LaserParams), k, c, eps_high, t_fix, trim_mode,
-                       1 if renormalize else 0, dtype, seed, token_offset, stream, poll_budget)
+                       1 if renormalize else 0, dtype, seed, token_offset, stream, poll_budget,
+                       pipeline_tiles, 0)
 
 
 def laser_strerror(code: int) -> str:

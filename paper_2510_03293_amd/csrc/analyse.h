@@ -54,6 +54,18 @@ __device__ __forceinline__ float exp_fixed(float x) {
   return __int_as_float(__float_as_int(q) + ((int)n << 23));
 }
 
+// A store of something the chain workgroup of a pipelined call reads while the kernel
+// that writes it is still running (PUB): written through to where every compute unit of
+// the device sees it, so that the writer's own "stores done" count covers it.  Otherwise
+// a plain store.
+template <bool PUB, typename P>
+__device__ __forceinline__ void store_for_chain(P* p, P v) {
+  if (PUB)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+
 __device__ __forceinline__ unsigned long long lanes_below(int i) {
   return (1ull << i) - 1ull;  // i in [0, 63]
 }
@@ -196,13 +208,17 @@ __device__ __forceinline__ int group_sum(int x, int q) {
 // the summed logits.  CT (8 or 16) bounds the trimming size c.  STATS: also write the
 // per-token statistics asked for in `a` (top-k mass, entropy, pool size; plain fp32,
 // not part of any decision).  Must be called by all 512 threads of the workgroup.
-template <int NE, int NP, int CT, bool STATS>
+template <int NE, int NP, int CT, bool STATS, bool PUB>
 __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned long long* mask64,
                                 unsigned long long* flex_lds, int tile, const RouteArgs a,
                                 const Workspace ws, int32_t* __restrict__ expert_ids,
                                 float* __restrict__ weights, float* __restrict__ logits_out) {
   constexpr int NS = CT / 8;  // ranks 8*s + q are handled by lane q ("slots")
-  const int tid = threadIdx.x;
+  int tid = threadIdx.x;
+  // (PUB: called from a loop over tiles.  Everything derived from the thread index is
+  // then computed anew for every tile: held in registers across the loop it would crowd
+  // out the loads that are in flight around this call)
+  if (PUB) asm volatile("" : "+v"(tid));
   const int itok = tid >> 3;
   const int q = tid & 7;
   const int t = tile * kTile + itok;
@@ -213,11 +229,12 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   if (tid == 0) *flex_lds = 0ull;
   // the tail kernel of this call polls these words; they are cleared here, one
   // kernel earlier on the same stream
-  if (tile == 0 && tid < 4) ws.status[tid] = 0;
+  // (PUB: a kernel before this one has done it, and copied the counters)
+  if (!PUB && tile == 0 && tid < 4) ws.status[tid] = 0;
   // Tile 0 keeps a copy of the counters before token 0 for the tail kernel (which
   // overwrites them in place).  Loaded here, stored at the very end: the wait for the
   // load then costs nothing.
-  const bool lin_copier = tile == 0 && tid < 64;
+  const bool lin_copier = !PUB && tile == 0 && tid < 64;
   const int lin_before = (lin_copier && tid < a.E) ? a.loads_in[tid] : 0;
 
   constexpr int G = NE < 4 ? NE : 4;      // consecutive experts per run
@@ -257,7 +274,9 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
     for (int i = 0; i < NE; ++i)
       if (live && owned(i) < a.E) logits_out[(size_t)t * a.E + owned(i)] = z[i];
   }
-  __syncthreads();  // masks zeroed before anyone ORs into them
+  // masks zeroed before anyone ORs into them  (PUB: the next tile's loads are in flight
+  // around this call and must stay so; the barriers order LDS traffic only)
+  if (PUB) lds_barrier(); else __syncthreads();
 
   // ---- the CT best of the token, sorted, in every lane of its group -----------
   sort_descending<NE>(K);
@@ -362,7 +381,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
       if (8 * s + q < k) atomicOr(&mask64[my_e[s]], 1ull << itok);
   }
   if (flex && q == 0) atomicOr(flex_lds, 1ull << itok);
-  __syncthreads();
+  if (PUB) lds_barrier(); else __syncthreads();
   // (global stores only after the barrier: a barrier waits for the stores before it)
   if (live && !flex) {
     const float denom = a.renormalize ? sk : zsum;
@@ -381,11 +400,11 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
   }
 
   if (tid < 64) {
-    ws.tile_fixed_cnt[(size_t)tile * 64 + tid] = (uint8_t)__builtin_popcountll(mask64[tid]);
+    store_for_chain<PUB>(&ws.tile_fixed_cnt[(size_t)tile * 64 + tid], (uint8_t)__builtin_popcountll(mask64[tid]));
     ws.tile_mask[(size_t)tile * 64 + tid] = mask64[tid];
   }
   const unsigned long long fm = *flex_lds;
-  if (tid == 0) ws.flexmask[tile] = fm;
+  if (tid == 0) store_for_chain<PUB>(&ws.flexmask[tile], fm);
 
   // ---- records of the flexible tokens (rare or chain-bound: not tuned) ----------
   if (__builtin_amdgcn_ballot_w64(flex) != 0ull) {
@@ -428,8 +447,8 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
         }
         reinterpret_cast<unsigned*>(ws.rec_ids)[(size_t)t * 4 + q] = idw;
         reinterpret_cast<float4*>(ws.rec_p)[(size_t)t * 4 + q] = make_float4(pv[0], pv[1], pv[2], pv[3]);
-        reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q] = cidw;
-        reinterpret_cast<unsigned*>(ws.rec_pref)[(size_t)slot * 4 + q] = prefw;
+        store_for_chain<PUB>(&reinterpret_cast<unsigned*>(ws.rec_cids)[(size_t)slot * 4 + q], cidw);
+        store_for_chain<PUB>(&reinterpret_cast<unsigned*>(ws.rec_pref)[(size_t)slot * 4 + q], prefw);
       }
       // per owned expert: rank in the working set and the number of earlier fixed
       // tokens of this tile assigned to it; row in expert order
@@ -443,7 +462,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
         for (int j = 0; j < CT; ++j)
           if (j < cstar && top_e[j] == e) rank = j;
         const int fw = __builtin_popcountll(mask64[e] & below);
-        row[e] = rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF;
+        store_for_chain<PUB>(&row[e], rank >= 0 ? (uint16_t)((fw << 4) | rank) : (uint16_t)0xFFFF);
       }
     }
   }
@@ -451,7 +470,7 @@ __device__ void analyse_tile_ct(const float* __restrict__ lz, int zs, unsigned l
 }
 
 // NE = padded experts / 8 (1, 2, 4 or 8).
-template <int NE, int NP, bool STATS = false>
+template <int NE, int NP, bool STATS = false, bool PUB = false>
 __device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int zs,
                                              unsigned long long* mask64, unsigned long long* flex_lds,
                                              int tile, const RouteArgs a, const Workspace ws,
@@ -459,9 +478,9 @@ __device__ __forceinline__ void analyse_tile(const float* __restrict__ lz, int z
                                              float* __restrict__ weights,
                                              float* __restrict__ logits_out) {
   if (a.c <= 8)
-    analyse_tile_ct<NE, NP, 8, STATS>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
+    analyse_tile_ct<NE, NP, 8, STATS, PUB>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
   else
-    analyse_tile_ct<NE, NP, 16, STATS>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
+    analyse_tile_ct<NE, NP, 16, STATS, PUB>(lz, zs, mask64, flex_lds, tile, a, ws, expert_ids, weights, logits_out);
 }
 
 }  // namespace laser

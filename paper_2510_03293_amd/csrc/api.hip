@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t status, logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
-      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, total;
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, seg, total;
 };
 
 // cw: candidates per token record (record_width(c)).  The status words come first, so
@@ -37,7 +37,9 @@ static Layout layout(int T, int E, int cw) {
   L.fixed_cnt = off;  off += align_up(ntiles * 64);
   L.tile_mask = off;  off += align_up(ntiles * 64 * 8);
   L.base = off;       off += align_up(ntiles * 64 * 4);
-  const size_t words = (size_t)T / 32 + 2;
+  // (a pipelined call numbers the flexible tokens of every segment from a multiple of 32:
+  // up to 32 numbers, one word, are skipped per segment, of which there are fewer than ntiles)
+  const size_t words = (size_t)T / 32 + 2 + ntiles;
   L.chain_bits = off; off += align_up(words * 64 * 4);
   L.chain_cum = off;  off += align_up(words * 64 * 4);
   L.rec_cids = off;   off += align_up(slots * 16);
@@ -45,9 +47,10 @@ static Layout layout(int T, int E, int cw) {
   L.flex_list = off;  off += align_up(ntiles * 4);
   L.flex_ord = off;   off += align_up(ntiles * 4);
   L.flex_tok_base = off; off += align_up((ntiles + 1) * 4);
-  L.flex_slot = off;  off += align_up((size_t)T * 4);
+  L.flex_slot = off;  off += align_up(((size_t)T + 32 * ntiles) * 4);
   L.lin_copy = off;   off += align_up(64 * 4);
   L.pool = off;       off += align_up((size_t)T * 4);
+  L.seg = off;        off += align_up((kSegDone + ntiles) * 4);
   L.total = off + 256;
   return L;
 }
@@ -79,6 +82,7 @@ Workspace carve_workspace(void* base, int T, int E, int cw) {
   w.lin_copy = reinterpret_cast<int32_t*>(b + L.lin_copy);
   w.pool = reinterpret_cast<int32_t*>(b + L.pool);
   w.status = reinterpret_cast<int32_t*>(b + L.status);
+  w.seg = reinterpret_cast<int32_t*>(b + L.seg);
   return w;
 }
 
@@ -115,6 +119,8 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.spin_limit = p->poll_budget != 0 ? (long long)p->poll_budget : kSpinFloor + kSpinPerToken * (long long)T;
   a.nbatch = 1;
   a.ws_stride = 0;
+  a.seg_tiles = 0;
+  a.nseg = 0;
   return a;
 }
 
@@ -124,6 +130,17 @@ static RandomArgs make_random(const laser_params_t* p) {
   r.token_offset = p->token_offset;
   r.stream = p->stream;
   return r;
+}
+
+// Tiles per segment of a pipelined call (0: the call is not pipelined), from
+// laser_params_t.pipeline_tiles.  Left to itself the library pipelines batches of at least
+// four rounds of the persistent grid (one workgroup per compute unit but one) in segments
+// of two rounds: a segment is complete when its last round is, so whole rounds it is.
+static int segment_tiles(int ntiles, uint32_t wanted) {
+  if (wanted == 1) return 0;
+  if (wanted >= 2) return (uint32_t)ntiles > wanted ? (int)wanted : 0;
+  const int round = pipeline_workgroups();
+  return ntiles >= 4 * round ? 2 * round : 0;
 }
 
 // The fast analysis kernels carry at most kMaxC candidates per token.  A wide call runs
@@ -180,6 +197,12 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   const bool resample = random && params->c > params->k && !wide;
   const bool general = wide || (random && !resample);
   if (resample && !a.st_pool) a.pool_in_ws = 1;
+  // Pipelined: one problem through the fused bf16 kernel, nothing between it and the tail
+  // kernel, no statistics (the kernel variants with statistics are not built for it).
+  if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample && !wants_stats(a)) {
+    a.seg_tiles = segment_tiles(a.ntiles, params->pipeline_tiles);
+    a.nseg = a.seg_tiles > 0 ? (a.ntiles + a.seg_tiles - 1) / a.seg_tiles : 0;
+  }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given
   const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);
   float* logits;

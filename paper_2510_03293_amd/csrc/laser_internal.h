@@ -38,6 +38,11 @@ struct RouteArgs {
   long long spin_limit;  // polls a finishing wavefront spends on one flag of the chain before it gives up
   int nbatch;          // problems in the call (1: all of the above is the one problem's)
   size_t ws_stride;    // bytes from one problem's workspace to the next
+  // pipelined calls (large single problems through the fused bf16 kernel): the tiles are cut
+  // into segments of seg_tiles tiles, and the chain over a segment runs, inside the gate
+  // kernel, as soon as the segment's tiles have been analysed (see Workspace::seg)
+  int seg_tiles;       // tiles per segment; 0: the call is not pipelined
+  int nseg;            // segments (ceil(ntiles / seg_tiles)); 0 when not pipelined
 };
 // Trimming mode RANDOM: what makes the sample reproducible.
 struct RandomArgs {
@@ -78,6 +83,8 @@ struct Workspace {
   int32_t* pool;               // [T] pool sizes, when RANDOM trimming needs them (see pool_in_ws)
   int32_t* status;             // [4] see kStatus*: cleared by the analysis kernel of a call (the
                                //     first bytes of the workspace, so that a query needs no sizes)
+  int32_t* seg;                // [kSegDone + ntiles] pipelined calls only, see kSeg*: how far the
+                               //     chain has come, and per tile how much of its analysis is written
 };
 
 // Problem b of a batched call.  All problems share the sizes; every array of problem
@@ -117,6 +124,7 @@ __device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size
   w.lin_copy = shifted(w0.lin_copy, bytes);
   w.pool = shifted(w0.pool, bytes);
   w.status = shifted(w0.status, bytes);
+  w.seg = shifted(w0.seg, bytes);
   return w;
 }
 
@@ -132,11 +140,24 @@ constexpr long long kSpinFloor = 1ll << 22;
 constexpr long long kSpinPerToken = 16;
 constexpr int kStatusSweeps = 3;     // sweeps of the chain's window evaluation (diagnostic)
 
+// Workspace::seg of a pipelined call.  Cleared by a small kernel before the gate kernel.
+constexpr int kSegNext = 0;     // segments the chain has finished
+constexpr int kSegFlexBase = 1; // number the next segment's first flexible token gets (a multiple of 32)
+constexpr int kSegOrdBase = 2;  // tiles with flexible tokens in the finished segments
+constexpr int kSegCarry = 4;    // [64] per expert: assignments in the finished segments
+constexpr int kSegDone = 128;   // [ntiles] wavefronts of the tile's analysis workgroup that have written their records
+
 inline int record_width(int c) { return c > kMaxC ? kWideC : kMaxC; }
 size_t workspace_bytes(int T, int E, int cw);
 Workspace carve_workspace(void* base, int T, int E, int cw);
 
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }
+
+// A workgroup barrier at which only LDS traffic has to be settled: loads from memory that
+// are in flight stay in flight across it (__syncthreads() waits for them as well).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 // Large dynamic LDS must be allowed per kernel and per device before the first launch.
 // `done` is the kernel's own record of the devices it has been allowed on.
@@ -153,6 +174,21 @@ inline hipError_t allow_dynamic_lds(const void* fn, int bytes, LdsAttr& rec) {
   e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess && known) rec.done[dev] = true;
   return e;
+}
+
+// Analysis workgroups of the persistent gate kernel of pipelined calls: one per compute
+// unit of the current device but the one the chain workgroup occupies (255 if the device
+// cannot be asked).  Cached per device.
+inline int pipeline_workgroups() {
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 255;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 2) n = 256;
+    cached[dev] = n - 1;
+  }
+  return cached[dev];
 }
 
 // A launcher reports the status of its own launch: an error that an earlier HIP call of

@@ -94,6 +94,14 @@ __device__ __forceinline__ void lds_wave_fence() {
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
+// (every lane its own word)
+__device__ __forceinline__ bool poll_word(const int* word, int want, long long limit) {
+  for (long long it = 0; it < limit; ++it) {
+    if (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want) return true;
+    __builtin_amdgcn_s_sleep(4);
+  }
+  return false;
+}
 __device__ __forceinline__ bool poll_flag(const int* flag, int want, long long limit) {
   for (long long it = 0; it < limit; ++it) {
     const int seen = __builtin_amdgcn_readfirstlane(
@@ -655,11 +663,6 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
 constexpr int kRing2 = 512;         // tokens in the LDS ring
 constexpr int kSpecOutWords = 16;   // output staging ring, words of 32 tokens
 
-// Only LDS traffic has to be settled at these barriers; loads from memory that are in
-// flight (the producers' pipeline) stay in flight across them.
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 struct __align__(16) SpecExp2 {
   unsigned long long mask[2];  // window positions 0..63 / 64..127 that tentatively chose the expert
@@ -800,14 +803,21 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
       unsigned newsel = smallest_k_slots<CP, KK>(key, k);
       newsel = valid ? newsel : 0u;
       const unsigned diff = sel ^ newsel;
-      const unsigned long long bal = __builtin_amdgcn_ballot_w64(diff != 0u);
-      if (bal != 0ull) {
+      const unsigned long long changed = __builtin_amdgcn_ballot_w64(diff != 0u);
+      if (changed != 0ull) {
         // flip this lane's bit in the masks of the experts whose choice changed
 #pragma unroll
         for (int j = 0; j < CP; ++j)
           if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
       }
       sel = newsel;
+      // A token that entered in this sweep counts as changed even if its first guess held:
+      // its guess joined the masks while the other consumer wave may already have been
+      // counting, so a later token (also new: the new ones are the last of the window) may
+      // or may not have seen it.  Nothing behind the first new token is final before the
+      // next sweep; the first new token itself is, like any first changed one, because
+      // everything before it stood still.
+      const unsigned long long bal = changed | __builtin_amdgcn_ballot_w64(enters);
       if (lane == 0) S.bal[par][pw] = bal;
     } else {
       // ---- producer: stage batch nb if the ring has room for it ----------------------------
@@ -971,9 +981,20 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
   return decided;
 }
 
+// One segment of a pipelined call, as chain_workgroup sees it: `a` and `ws` are then the
+// segment's own view (tile 0 = the segment's first tile, flexible token 0 = its first
+// flexible token), and what the earlier segments did comes in through here.
+struct ChainSeg {
+  bool on;        // false: the whole call in one go (everything below unused)
+  int carry0;     // lane = expert: assignments in the earlier segments
+  int fbase;      // number of the segment's first flexible token in the call's numbering
+  int* out;       // LDS, 66 words: [lane] assignments up to the segment's end, [64] its tiles
+                  // with flexible tokens, [65] its flexible tokens
+};
+
 __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
                                 int32_t* __restrict__ loads_inout,
-                                int32_t* __restrict__ expert_offsets) {
+                                int32_t* __restrict__ expert_offsets, const ChainSeg seg) {
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
   __shared__ int wave_flex[kChainWaves], wave_tok[kChainWaves];
@@ -986,7 +1007,7 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
 
   // (a call without tokens has no analysis kernel that would have cleared the status
   // words, and no finishing workgroup that polls them)
-  if (ntiles == 0 && threadIdx.x < 4) ws.status[threadIdx.x] = 0;
+  if (!seg.on && ntiles == 0 && threadIdx.x < 4) ws.status[threadIdx.x] = 0;
   // Everything the workgroup reads first is requested before anything is consumed:
   // the counters, the first super-batch of byte counts, the flexible-tile masks.
   int lin = 0;
@@ -1042,15 +1063,17 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   }
   // a handful of flexible tokens: the finishing workgroups resolve them themselves and
   // write the totals; nothing to do here
-  if (fast_path_applies(ntiles, nflex_tiles, nflex_tok, a.cw)) return;
+  // (never in a pipelined call: the finishing workgroups judge by the whole call's sizes)
+  if (!seg.on && fast_path_applies(ntiles, nflex_tiles, nflex_tok, a.cw)) return;
   // Without flexible tokens, small problems are finished without tile_base (the
   // finishing workgroups sum the byte counts themselves): only the totals are needed.
-  const bool need_tile_base = nflex_tiles > 0 || ntiles > kSelfPrefixTiles;
+  // (A segment cannot know what the later segments hold.)
+  const bool need_tile_base = seg.on || nflex_tiles > 0 || ntiles > kSelfPrefixTiles;
 
   // ---- prefix over tiles of the fixed tokens' counts -------------------------
   // The byte counts are staged through LDS in super-batches with wide loads; wave
   // w then scans a contiguous run of tiles for its lane's expert.
-  int carry = 0;  // fixed assignments in earlier super-batches (lane's expert)
+  int carry = seg.on ? seg.carry0 : 0;  // assignments before this super-batch (lane's expert)
   for (int sb0 = 0; sb0 < ntiles; sb0 += kChainStageTiles) {
     const int nt = min(kChainStageTiles, ntiles - sb0);
     for (int i0 = threadIdx.x; i0 < nt * 4; i0 += kTailThreads * 8) {
@@ -1087,7 +1110,8 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   const bool wide = a.cw > kMaxC;
   const bool use_spec = nflex_tok >= kSpecMinTokens && !wide;
   // order of the flexible tiles, and for every tile the number of flexible tokens before it
-  for (int g = ga; g < gb && nflex_tiles > 0; ++g) {
+  const int fbase = seg.on ? seg.fbase : 0;
+  for (int g = ga; g < gb && (nflex_tiles > 0 || seg.on); ++g) {
     const int tile = g * 64 + lane;
     const unsigned long long fm = g == ga ? first_fm : (tile < ntiles ? ws.flexmask[tile] : 0ull);
     const bool f = fm != 0ull;
@@ -1102,8 +1126,8 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     }
     if (tile < ntiles) {
       ws.flex_ord[tile] = ord;
-      ws.flex_tok_base[tile] = tokbefore + incl - np;
-      if (tile == ntiles - 1) ws.flex_tok_base[ntiles] = tokbefore + incl;
+      ws.flex_tok_base[tile] = fbase + tokbefore + incl - np;  // (read by the finishing pass only)
+      if (tile == ntiles - 1 && !seg.on) ws.flex_tok_base[ntiles] = tokbefore + incl;
     }
     if (f) ws.flex_list[ord] = tile;
     if (use_spec) {
@@ -1132,15 +1156,31 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     if (lane == a.E - 1) expert_offsets[a.E] = incl;
   };
 
-  if (nflex_tiles == 0 && wave == 0) write_totals();  // already final
-  __syncthreads();  // tile_base, flex_list, flex_ord (and the totals) written by every wave
-  if (threadIdx.x == 0) {
-    ws.status[kStatusFlexTiles] = nflex_tiles;
-    __hip_atomic_store(&ws.status[kStatusPhase], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  // A segment hands its results to the caller instead of publishing anything.
+  auto segment_result = [&]() {  // wave 0
+    seg.out[lane] = total_fixed + gflex;
+    if (lane == 0) {
+      seg.out[64] = nflex_tiles;
+      seg.out[65] = nflex_tok;
+    }
+  };
+  if (wave == 0 && (nflex_tiles > 0 || seg.on)) ws.chain_cum[lane] = 0;  // nothing chosen before flexible token 0
+  if (seg.on) {
+    if (nflex_tiles == 0) {
+      if (wave == 0) segment_result();
+      return;
+    }
+    __syncthreads();  // tile_base, flex_list, flex_ord, flex_slot written by every wave
+  } else {
+    if (nflex_tiles == 0 && wave == 0) write_totals();  // already final
+    __syncthreads();  // tile_base, flex_list, flex_ord (and the totals) written by every wave
+    if (threadIdx.x == 0) {
+      ws.status[kStatusFlexTiles] = nflex_tiles;
+      __hip_atomic_store(&ws.status[kStatusPhase], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (nflex_tiles == 0) return;
   }
-  if (nflex_tiles == 0) return;
 
-  if (wave == 0) ws.chain_cum[lane] = 0;  // nothing chosen before flexible token 0
   int decided = 0;
   unsigned hist0 = 0;
   if (use_spec) {
@@ -1177,10 +1217,160 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
     else
       chain_walk<16>(buf, ft0, r0, decided, hist0, nflex_tiles, a, ws, wave, lane, lin, gflex);
   }
+  if (seg.on) {
+    if (wave == 0) segment_result();
+    return;
+  }
   if (wave == 0) write_totals();
   __syncthreads();
   if (threadIdx.x == 0)
     __hip_atomic_store(&ws.status[kStatusPhase], 2, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- pipelined calls: the chain segment by segment ---------------------------------
+//
+// Algorithm 1 orders the tokens of a batch, so the chain over tiles [0, n) needs nothing
+// of the tiles behind them.  A large call is therefore cut into segments of a.seg_tiles
+// tiles; the chain over a segment starts as soon as the gate kernel has analysed the
+// segment's tiles, inside that kernel (workgroup 0 of its grid), while the other
+// workgroups go on streaming the later tiles.  Every analysis workgroup counts itself into
+// its segment's word of ws.seg when its records are written (release); the chain workgroup
+// waits for a segment to be complete (acquire), bounded: if it ever gives up, or simply
+// has not come to the last segment when the gate kernel's tiles are done, the tail
+// kernel's chain workgroup takes over where it stopped, behind the kernel boundary.
+// What is carried from segment to segment (ws.seg) is small: per expert the assignments
+// so far, and where the numbering of flexible tokens and tiles goes on.  A segment's
+// flexible tokens are numbered from a multiple of 32 (words of chain_bits / chain_cum
+// are not shared between segments), chain_cum restarts at 0 in every segment, and
+// tile_base carries the earlier segments' choices -- the finishing pass reads all of it
+// exactly as in a call that is not pipelined.
+
+// The chain numbers the tiles, the flexible tokens and the tiles with flexible tokens of a
+// segment from 0.  `v` becomes the view of the arrays in which those are dtiles tiles,
+// dflex flexible tokens (a multiple of 32) and dord flexible tiles further on than in `v`.
+// (Advanced in place from segment to segment: one set of pointers in scalar registers.)
+__device__ __forceinline__ void advance_view(Workspace& v, const RouteArgs& a, int dtiles, int dflex, int dord) {
+  const size_t tok = (size_t)dtiles * kTile;  // tokens and record slots
+  v.rec_cstar += tok;
+  v.rec_ids += tok * a.cw;
+  v.rec_p += tok * a.cw;
+  v.rec_Z += tok;
+  v.rec_lane += tok * a.EP;
+  v.flexmask += dtiles;
+  v.tile_fixed_cnt += (size_t)dtiles * 64;
+  v.tile_mask += (size_t)dtiles * 64;
+  v.tile_base += (size_t)dtiles * 64;
+  v.rec_cids += tok * 16;
+  v.rec_pref += tok * 16;
+  v.flex_list += dord;
+  v.flex_ord += dtiles;
+  v.flex_tok_base += dtiles;
+  v.flex_slot += dflex;
+  v.chain_bits += (size_t)(dflex >> 5) * 64;
+  v.chain_cum += (size_t)(dflex >> 5) * 64;
+}
+
+// Polls of a segment's counter before the chain workgroup inside the gate kernel leaves
+// the rest to the tail kernel (a poll is a memory round trip plus a short sleep).
+constexpr long long kSegPollLimit = 1ll << 20;
+// Every wavefront of an analysis workgroup counts itself into its tile's segment.
+constexpr int kGateSignals = 8;
+
+// The chain of a call, by the chain workgroup (kTailThreads threads) of the gate kernel
+// (IN_GATE: as far as the analysed tiles allow, nothing is published) or of the tail
+// kernel (the rest, then the totals and the flags the finishing workgroups wait for).
+template <bool IN_GATE>
+__device__ __forceinline__ void chain_segments(uint8_t* lds, const RouteArgs& a, const Workspace& ws,
+                                               int32_t* __restrict__ loads_inout,
+                                               int32_t* __restrict__ expert_offsets) {
+  ChainSeg sg;
+  sg.on = a.nseg > 0;  // (not pipelined: one round over the whole call, which publishes for itself)
+  sg.carry0 = 0;
+  sg.fbase = 0;
+  __shared__ int seg_out[66];
+  __shared__ int seg_ready;
+  sg.out = seg_out;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int32_t* const status = ws.status;
+  int32_t* const segw = ws.seg;
+  int j = 0, fbase = 0, ordbase = 0, carry = 0;
+  RouteArgs av = a;
+  Workspace wv = ws;
+  if (sg.on) {
+    // (written by the kernel before this one: the clearing kernel, or the gate kernel)
+    j = __builtin_amdgcn_readfirstlane(segw[kSegNext]);
+    fbase = __builtin_amdgcn_readfirstlane(segw[kSegFlexBase]);
+    ordbase = __builtin_amdgcn_readfirstlane(segw[kSegOrdBase]);
+    carry = segw[kSegCarry + lane];
+    advance_view(wv, a, j * a.seg_tiles, fbase, ordbase);
+  }
+  const int rounds = sg.on ? a.nseg : 1;
+  for (; j < rounds; ++j) {
+    if (sg.on) {
+      const int tile0 = j * a.seg_tiles;
+      const int nt = min(a.seg_tiles, a.ntiles - tile0);
+      if (IN_GATE) {
+        // every thread waits for some of the segment's tiles (all of their wavefronts
+        // counted in), then the workgroup agrees on whether all of them are there
+        if (threadIdx.x == 0) seg_ready = 1;
+        __syncthreads();
+        bool mine = true;
+        for (int i = threadIdx.x; i < nt && mine; i += kTailThreads)
+          mine = poll_word(&segw[kSegDone + tile0 + i], kGateSignals, kSegPollLimit);
+        if (!mine) seg_ready = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __syncthreads();
+        const bool ready = seg_ready != 0;
+        __syncthreads();  // (seg_ready is written again in the next round)
+        if (!ready) break;
+      }
+      av.ntiles = nt;
+      av.T = min(a.T - tile0 * kTile, nt * kTile);
+      sg.carry0 = carry;
+      sg.fbase = fbase;
+    }
+    chain_workgroup(lds, av, wv, loads_inout, expert_offsets, sg);
+    if (!sg.on) return;
+    __syncthreads();  // seg_out written (wave 0); the chain's LDS is free again
+    carry = seg_out[lane];
+    // (as scalars: the next segment's view is then computed in scalar registers)
+    const int dord = __builtin_amdgcn_readfirstlane(seg_out[64]);
+    const int dflex = (__builtin_amdgcn_readfirstlane(seg_out[65]) + 32) & ~31;
+    advance_view(wv, a, av.ntiles, dflex, dord);
+    ordbase += dord;
+    fbase += dflex;
+    __syncthreads();  // (seg_out is written again in the next round)
+  }
+  if (IN_GATE) {
+    // for the tail kernel, behind the kernel boundary
+    if (wave == 0) segw[kSegCarry + lane] = carry;
+    if (threadIdx.x == 0) {
+      segw[kSegNext] = j;
+      segw[kSegFlexBase] = fbase;
+      segw[kSegOrdBase] = ordbase;
+    }
+    return;
+  }
+  // the totals, and the flags of the finishing workgroups
+  if (wave == 0) {
+    const int lin = lane < a.E ? loads_inout[lane] : 0;
+    const int cnt = lane < a.E ? carry : 0;
+    if (lane < a.E) loads_inout[lane] = lin + cnt;
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane < a.E) expert_offsets[lane] = incl - cnt;
+    if (lane == a.E - 1) expert_offsets[a.E] = incl;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    status[kStatusFlexTiles] = ordbase;
+    __hip_atomic_store(&status[kStatusPhase], 2, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // ---- a handful of flexible tokens: every finishing workgroup resolves them itself ----
@@ -1664,7 +1854,7 @@ __device__ __forceinline__ void tail_role(int block, uint8_t* tail_lds, const Ro
                                           int32_t* __restrict__ expert_ids, float* __restrict__ weights,
                                           int32_t* __restrict__ permutation) {
   if (block == 0) {
-    chain_workgroup(tail_lds, a, ws, loads_inout, expert_offsets);
+    chain_segments<false>(tail_lds, a, ws, loads_inout, expert_offsets);
     return;
   }
   __shared__ int sh_before[kChainWaves][64], sh_all[kChainWaves][64];
@@ -1721,7 +1911,8 @@ __device__ __forceinline__ void tail_role(int block, uint8_t* tail_lds, const Ro
     }
     __syncthreads();
     // a handful of flexible tokens: resolved here, by every workgroup for itself
-    if (__builtin_expect(!self && a.ntiles <= kFastMaxTiles, 0)) {
+    // (not in a pipelined call: there the chain workgroup walks every flexible token)
+    if (__builtin_expect(!self && a.ntiles <= kFastMaxTiles && a.nseg == 0, 0)) {
       fast_n = finish_fast(block, fs, fm_mine, wg_cnt, sh_before, sh_all, own_base, own_offsets, a, ws, loads_inout,
                            expert_offsets);
       self = fast_n > 0;

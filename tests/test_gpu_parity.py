@@ -163,6 +163,24 @@ def test_window_chain_long_run():
     assert int((ref["cstar"] > k).sum()) > 2000
 
 
+@pytest.mark.parametrize("E,k,c", [(33, 5, 8), (64, 6, 8), (64, 2, 4), (16, 2, 4), (64, 9, 16)])
+def test_window_whose_first_guesses_hold(E, k, c):
+    """Counters far apart at the start: nearly every first guess of the window evaluation
+    is right, so whole windows retire in the sweep in which their tokens entered -- except
+    where two candidates are close, and there a token must have seen the choices of all
+    tokens before it, also of those that entered in the same sweep in the other half of
+    the window.  Many seeds, several windows each."""
+    u = _util()
+    for seed in range(24):
+        rng = np.random.default_rng(1000 * E + seed)
+        T = int(rng.choice([300, 641, 1151, 2500]))
+        logits = wl.random_logits(seed + E, T, E, kind="normal", scale=0.3)
+        # a few groups of experts with nearly equal counters, the groups far apart
+        groups = rng.integers(0, 6, size=E)
+        loads_in = (groups * 400 + rng.integers(0, 3, size=E)).astype(np.int32)
+        u.check_from_logits(logits, k, c, 2.0, 1e-30, loads_in, label=f"guesses hold E{E} seed{seed}")
+
+
 def _random_case(seed):
     rng = np.random.default_rng(seed)
     E = int(rng.choice([2, 3, 5, 8, 8, 8, 16, 24, 33, 48, 64, 64, 64]))
