@@ -662,6 +662,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
 // words in LDS; wave 3 writes out the words that are complete.
 constexpr int kRing2 = 512;         // tokens in the LDS ring
 constexpr int kSpecOutWords = 16;   // output staging ring, words of 32 tokens
+constexpr int kSpecMeetPolls = 1 << 14;  // looks of one consumer wave for the other one, per sweep
 
 
 struct __align__(16) SpecExp2 {
@@ -672,6 +673,7 @@ struct __align__(16) SpecExp2 {
 struct SpecShared2 {
   SpecExp2 M[64];
   unsigned obits[kSpecOutWords][64];  // per expert: chosen bits of 32 flexible tokens, not yet written out
+  int met[2];                         // consumer wave: sweeps in which its new tokens' guesses are in the masks
   unsigned long long bal[2][2];       // [sweep parity][consumer wave]: lanes whose choice changed
   int staged[2][2];                   // [sweep parity][producer wave]: tokens below this number are in the ring
   int pub_done[2], pub_flags[2];      // [sweep parity] written by wave 0 before the second barrier
@@ -703,6 +705,7 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
   }
   for (int i = tid; i < kSpecOutWords * 64; i += kTailThreads) (&S.obits[0][0])[i] = 0u;
   if (tid < 4) (&S.bal[0][0])[tid] = 0ull;
+  if (tid < 2) S.met[tid] = 0;
   if (tid < 4) (&S.staged[0][0])[tid] = 0;
   if (tid < 2) {
     S.pub_done[tid] = 0;
@@ -773,9 +776,13 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
       }
       const bool valid = cur_f == f_lane;
       if (!valid) sel = 0;
-      if (guess_on && __builtin_amdgcn_ballot_w64(enters) != 0ull) {
-        // the guesses join the masks before this wave counts (the lane's bit is clear:
-        // the token that held the lane took its bits along when it retired)
+      bool met = true;
+      if (guess_on) {
+        // The guesses join the masks before anybody counts (the lane's bit is clear: the
+        // token that held the lane took its bits along when it retired).  "Anybody" is
+        // both consumer waves: a new token in the other half of the window counts this
+        // half's new guesses too.  The two waves meet here through a pair of sweep numbers
+        // in LDS (the producers are busy staging and take no part).
         if (enters) {
 #pragma unroll
           for (int j = 0; j < CP; ++j)
@@ -783,6 +790,12 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
         }
         lds_wave_fence();
         __builtin_amdgcn_wave_barrier();
+        if (lane == 0) S.met[pw] = total_sweeps + 1;
+        met = false;
+        for (int it = 0; it < kSpecMeetPolls && !met; ++it) {
+          lds_wave_fence();
+          met = __builtin_amdgcn_readfirstlane(*(volatile int*)&S.met[pw ^ 1]) > total_sweeps;
+        }
       }
       // the window positions before this one: from the head up to pos, cyclically
       unsigned long long bh0, bh1;
@@ -803,21 +816,18 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
       unsigned newsel = smallest_k_slots<CP, KK>(key, k);
       newsel = valid ? newsel : 0u;
       const unsigned diff = sel ^ newsel;
-      const unsigned long long changed = __builtin_amdgcn_ballot_w64(diff != 0u);
-      if (changed != 0ull) {
+      unsigned long long bal = __builtin_amdgcn_ballot_w64(diff != 0u);
+      if (bal != 0ull) {
         // flip this lane's bit in the masks of the experts whose choice changed
 #pragma unroll
         for (int j = 0; j < CP; ++j)
           if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
       }
       sel = newsel;
-      // A token that entered in this sweep counts as changed even if its first guess held:
-      // its guess joined the masks while the other consumer wave may already have been
-      // counting, so a later token (also new: the new ones are the last of the window) may
-      // or may not have seen it.  Nothing behind the first new token is final before the
-      // next sweep; the first new token itself is, like any first changed one, because
-      // everything before it stood still.
-      const unsigned long long bal = changed | __builtin_amdgcn_ballot_w64(enters);
+      // (should the other wave not have shown up in time, which does not happen while both
+      // run: this sweep's new tokens may have missed guesses, so none of them is final yet
+      // but the first -- it counts as changed)
+      if (!met) bal |= __builtin_amdgcn_ballot_w64(enters);
       if (lane == 0) S.bal[par][pw] = bal;
     } else {
       // ---- producer: stage batch nb if the ring has room for it ----------------------------
