@@ -120,6 +120,7 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.nbatch = 1;
   a.ws_stride = 0;
   a.seg_tiles = 0;
+  a.seg_first = 0;
   a.nseg = 0;
   return a;
 }
@@ -132,15 +133,24 @@ static RandomArgs make_random(const laser_params_t* p) {
   return r;
 }
 
-// Tiles per segment of a pipelined call (0: the call is not pipelined), from
+// The segments of a pipelined call (a.seg_tiles == 0: the call is not pipelined), from
 // laser_params_t.pipeline_tiles.  Left to itself the library pipelines batches of at least
-// four rounds of the persistent grid (one workgroup per compute unit but one) in segments
-// of two rounds: a segment is complete when its last round is, so whole rounds it is.
-static int segment_tiles(int ntiles, uint32_t wanted) {
-  if (wanted == 1) return 0;
-  if (wanted >= 2) return (uint32_t)ntiles > wanted ? (int)wanted : 0;
-  const int round = pipeline_workgroups();
-  return ntiles >= 4 * round ? 2 * round : 0;
+// four rounds of the persistent grid (one workgroup per compute unit but one): a first
+// segment of one round, so that the chain starts early, then segments of two rounds -- a
+// segment is complete when its last round is, so whole rounds it is.
+static void choose_segments(RouteArgs& a, uint32_t wanted) {
+  a.seg_tiles = a.seg_first = a.nseg = 0;
+  if (wanted == 1) return;
+  if (wanted >= 2) {
+    if ((uint32_t)a.ntiles <= wanted) return;
+    a.seg_tiles = a.seg_first = (int)wanted;
+  } else {
+    const int round = pipeline_workgroups();
+    if (a.ntiles < 4 * round) return;
+    a.seg_first = round;
+    a.seg_tiles = 2 * round;
+  }
+  a.nseg = 1 + (a.ntiles - a.seg_first + a.seg_tiles - 1) / a.seg_tiles;
 }
 
 // The fast analysis kernels carry at most kMaxC candidates per token.  A wide call runs
@@ -200,8 +210,7 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   // Pipelined: one problem through the fused bf16 kernel, nothing between it and the tail
   // kernel, no statistics (the kernel variants with statistics are not built for it).
   if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample && !wants_stats(a)) {
-    a.seg_tiles = segment_tiles(a.ntiles, params->pipeline_tiles);
-    a.nseg = a.seg_tiles > 0 ? (a.ntiles + a.seg_tiles - 1) / a.seg_tiles : 0;
+    choose_segments(a, params->pipeline_tiles);
   }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given
   const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);

@@ -42,8 +42,13 @@ struct RouteArgs {
   // into segments of seg_tiles tiles, and the chain over a segment runs, inside the gate
   // kernel, as soon as the segment's tiles have been analysed (see Workspace::seg)
   int seg_tiles;       // tiles per segment; 0: the call is not pipelined
-  int nseg;            // segments (ceil(ntiles / seg_tiles)); 0 when not pipelined
+  int seg_first;       // tiles of segment 0 (a short one lets the chain start early)
+  int nseg;            // segments: 1 + ceil((ntiles - seg_first) / seg_tiles); 0 when not pipelined
 };
+// First tile of segment j of a pipelined call (j <= nseg; segment nseg starts at ntiles or beyond).
+__host__ __device__ inline int segment_start(const RouteArgs& a, int j) {
+  return j == 0 ? 0 : a.seg_first + (j - 1) * a.seg_tiles;
+}
 // Trimming mode RANDOM: what makes the sample reproducible.
 struct RandomArgs {
   unsigned long long seed;          // generator key

@@ -1313,13 +1313,13 @@ __device__ __forceinline__ void chain_segments(uint8_t* lds, const RouteArgs& a,
     fbase = __builtin_amdgcn_readfirstlane(segw[kSegFlexBase]);
     ordbase = __builtin_amdgcn_readfirstlane(segw[kSegOrdBase]);
     carry = segw[kSegCarry + lane];
-    advance_view(wv, a, j * a.seg_tiles, fbase, ordbase);
+    advance_view(wv, a, min(segment_start(a, j), a.ntiles), fbase, ordbase);
   }
   const int rounds = sg.on ? a.nseg : 1;
   for (; j < rounds; ++j) {
     if (sg.on) {
-      const int tile0 = j * a.seg_tiles;
-      const int nt = min(a.seg_tiles, a.ntiles - tile0);
+      const int tile0 = segment_start(a, j);
+      const int nt = min(segment_start(a, j + 1), a.ntiles) - tile0;
       if (IN_GATE) {
         // every thread waits for some of the segment's tiles (all of their wavefronts
         // counted in), then the workgroup agrees on whether all of them are there
