@@ -69,7 +69,7 @@ def max_over_mean(loads_2d) -> float:
 class Workload:
     """One benchmark configuration resident on the GPU: `layers` layers of inputs."""
 
-    def __init__(self, name, preset, layers=0):
+    def __init__(self, name, preset, layers=0, pipeline_tiles=0):
         import torch
         from paper_2510_03293_amd import binding as B
         from synth import workloads as wl
@@ -86,7 +86,7 @@ class Workload:
             self.hidden.append(torch.from_numpy(inp["hidden"].view(np.int16)).view(torch.bfloat16).cuda())
             self.wgate.append(torch.from_numpy(inp["w_gate"].view(np.int16)).view(torch.bfloat16).cuda())
             eps, tfix = wl.thresholds(name, layer, preset)
-            self.params.append(B.make_params(s.k, s.c, eps, tfix, dtype=s.dtype))
+            self.params.append(B.make_params(s.k, s.c, eps, tfix, dtype=s.dtype, pipeline_tiles=pipeline_tiles))
         self.loads = torch.zeros((self.layers, s.E), dtype=torch.int32, device="cuda")
         self.loads_of = [self.loads[layer] for layer in range(self.layers)]
         self.buf = B.RouteBuffers(s.T, s.H, s.E, self.params[0])
@@ -281,6 +281,16 @@ def side_workload(name, preset, layers, steps, event_overhead_s, check):
             w.step(params=off)
         torch.cuda.synchronize()
         out["us_per_layer_not_pipelined"] = (time.perf_counter() - t0) * 1e6 / (steps * w.layers)
+        # (the buffers hold the last layer's outputs: the same from both kinds of call)
+        one_piece = [t.clone() for t in (w.buf.expert_ids, w.buf.permutation, w.buf.expert_offsets, w.loads,
+                                         w.buf.weights.view(torch.int32))]
+        w.step()
+        torch.cuda.synchronize()
+        pipelined = (w.buf.expert_ids, w.buf.permutation, w.buf.expert_offsets, w.loads,
+                     w.buf.weights.view(torch.int32))
+        if not all(torch.equal(x, y) for x, y in zip(one_piece, pipelined)):
+            raise SystemExit(f"{name}: the pipelined call differs from the call in one piece")
+        out["pipelined_equals_not_pipelined"] = True
     if check:
         out.update(w.check_layer0())
         out["parity_checked"] = True
@@ -381,6 +391,8 @@ def main():
                     help="skip the context figures (plain read, top-k, rerun, decode calls)")
     ap.add_argument("--no-side-workloads", action="store_true",
                     help="skip the Mixtral- and prefill-shaped side measurements")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="route large batches in one piece (laser_params_t.pipeline_tiles = 1)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -398,7 +410,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     # ---- inputs, resident in HBM before anything is timed --------------------
-    w = Workload(args.workload, args.preset, args.layers)
+    w = Workload(args.workload, args.preset, args.layers, pipeline_tiles=1 if args.no_pipeline else 0)
     s, layers = w.s, w.layers
     T, H, E, k, c = s.T, s.H, s.E, s.k, s.c
     event_overhead_s = B.laser_bench_event_overhead(stream) * 1e-3
@@ -612,7 +624,7 @@ def main():
         side = {}
         for name, nl, st in (("mixtral", 4, 10), ("prefill", 1, 10)):
             if name != args.workload:
-                side[name] = side_workload(name, "paper", nl, st, event_overhead_s, check=(name == "mixtral"))
+                side[name] = side_workload(name, "paper", nl, st, event_overhead_s, check=True)
         out["workloads"] = side
 
     if not args.no_cpu_baseline:
