@@ -265,12 +265,12 @@ def side_workload(name, preset, layers, steps, event_overhead_s, check):
         "max_over_mean_load_topk": w.topk_imbalance(),
         "max_over_mean_load_loadonly": w.load_only_imbalance(min(w.layers, 1)),
     }
-    # Batches of 64 K tokens and more are pipelined (the walk over a segment's
+    # Batches of 96 K tokens and more are pipelined (the walk over a segment's
     # load-dependent tokens runs inside the projection kernel while later segments
     # stream): the same call with the pipeline switched off, for comparison.
     from paper_2510_03293_amd import binding as B
     from synth import workloads as wl
-    out["pipelined"] = bool(w.s.T >= 65280)
+    out["pipelined"] = bool(w.s.T >= 97920)   # (six rounds of 255 tiles of 64 tokens)
     if out["pipelined"]:
         off = [B.make_params(w.s.k, w.s.c, *wl.thresholds(name, layer, preset), dtype=w.s.dtype,
                              pipeline_tiles=1) for layer in range(w.layers)]

@@ -108,7 +108,7 @@ typedef struct laser_params {
                          /* 1 orders the tokens, so it needs nothing of later tokens) runs */
                          /* while the projection of the later segments still streams.      */
                          /* 0: the library decides (segments of about 32 K tokens for      */
-                         /* batches of 64 K tokens or more); 1: never; n >= 2: segments of */
+                         /* batches of 96 K tokens or more); 1: never; n >= 2: segments of */
                          /* n tiles of 64 tokens whenever the batch has more tiles.  The   */
                          /* results do not depend on it.                                   */
   uint32_t reserved;     /* 0                                                           */

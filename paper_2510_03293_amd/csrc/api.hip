@@ -135,9 +135,13 @@ static RandomArgs make_random(const laser_params_t* p) {
 
 // The segments of a pipelined call (a.seg_tiles == 0: the call is not pipelined), from
 // laser_params_t.pipeline_tiles.  Left to itself the library pipelines batches of at least
-// four rounds of the persistent grid (one workgroup per compute unit but one): a first
+// six rounds of the persistent grid (one workgroup per compute unit but one): a first
 // segment of one round, so that the chain starts early, then segments of two rounds -- a
-// segment is complete when its last round is, so whole rounds it is.
+// segment is complete when its last round is, so whole rounds it is.  (Measured on the
+// prefill shape: with many load-dependent tokens pipelining pays from three rounds on,
+// -12 % at four, -24 % at eight; with none it costs 15 % at four rounds -- the compute
+// unit given to the chain and the clearing launch -- and gains 5 % at eight, where the
+// prefix over the tiles leaves the tail kernel.)
 static void choose_segments(RouteArgs& a, uint32_t wanted) {
   a.seg_tiles = a.seg_first = a.nseg = 0;
   if (wanted == 1) return;
@@ -146,7 +150,7 @@ static void choose_segments(RouteArgs& a, uint32_t wanted) {
     a.seg_tiles = a.seg_first = (int)wanted;
   } else {
     const int round = pipeline_workgroups();
-    if (a.ntiles < 4 * round) return;
+    if (a.ntiles < 6 * round) return;
     a.seg_first = round;
     a.seg_tiles = 2 * round;
   }

@@ -127,18 +127,19 @@ def test_flexible_token_counts_around_word_boundaries(nflex):
 
 
 def test_default_segmentation_of_a_large_batch():
-    """65 536 tokens: pipelined by the library's own choice (two segments), compared with
-    the oracle and with the call in one piece."""
+    """98 304 tokens (six rounds of the persistent grid and a few tiles): pipelined by the
+    library's own choice -- a segment of one round, two of two, a short last one --
+    compared with the oracle and with the call in one piece."""
     u = _util()
-    T, H, E, k, c = 65536, 256, 64, 6, 8
+    T, H, E, k, c = 98304, 256, 64, 6, 8
     hidden, w, flat = _mixed_gate(5, T, H, E, 0.10)
     loads = np.zeros(E, dtype=np.int32)
     rows = np.random.default_rng(2).choice(T, size=2048, replace=False)
     gpu, ref = u.check_route(hidden, w, wl.DTYPE_BF16, k, c, 0.40, 0.80, loads,
-                             label="T65536 default", logit_rows=rows)
+                             label="T98304 default", logit_rows=rows)
     assert 0.05 < ref["expanded"].mean() < 0.2
     whole = u.run_route(hidden, w, wl.DTYPE_BF16, k, c, 0.40, 0.80, loads, pipeline_tiles=1)
-    _same(gpu, whole, "T65536 default")
+    _same(gpu, whole, "T98304 default")
 
 
 def test_segmented_call_twice_on_one_workspace():
