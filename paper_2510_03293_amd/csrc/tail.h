@@ -726,7 +726,8 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
     b[j] = kSpecInvalid;
   }
   unsigned sel = 0;
-  int cur_f = -1;  // token whose data this lane holds
+  int cur_f = -1;      // token whose data this lane holds
+  bool fresh = false;  // it came in after the last sweep: its first guess is not in the masks yet
 
   // ---- producer state: batch n of a producer is the tokens 128 n + 64 pw + lane ----------
   // in flight: the slot of batch nb + 2, slot and record of batch nb + 1, and for batch
@@ -755,27 +756,13 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
     const int head = done & 127;
     if (consumer) {
       // ---- this lane's token of the window [done, done + 128) -----------------------------
+      // (its data was fetched between the barriers of the sweep before, see below)
       const int pos = 64 * pw + lane;
       const int f_lane = done + ((pos - head) & 127);
-      const bool enters = f_lane < avail && cur_f != f_lane;
-      if (enters) {
-        const SpecTok<CP>* src = &ring[f_lane & (kRing2 - 1)];
-        const uint4 ids = src->ids;
-        const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
-        sel = 0;
-#pragma unroll
-        for (int j = 0; j < CP; ++j) {
-          ex[j] = (idw[j >> 2] >> (8 * (j & 3))) & 255;
-          b[j] = src->b[j];  // (bit 31, the guess, drops out of the key's shift below)
-        }
-        if (guess_on) {
-#pragma unroll
-          for (int j = 0; j < CP; ++j) sel |= (b[j] >> 31) << j;  // the producer's first guess
-        }
-        cur_f = f_lane;
-      }
       const bool valid = cur_f == f_lane;
       if (!valid) sel = 0;
+      const bool enters = fresh;  // a new token (sel: its first guess, if guesses are on)
+      fresh = false;
       bool met = true;
       if (guess_on) {
         // The guesses join the masks before anybody counts (the lane's bit is clear: the
@@ -880,8 +867,9 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
     }
     lds_barrier();
 
-    if (consumer) {
-      // ---- tokens up to the first changed one are final ------------------------------------
+    // ---- tokens up to the first changed one are final (every wave works it out) ------------
+    int fin;
+    {
       unsigned long long c0 = S.bal[par][0], c1 = S.bal[par][1];
       c0 = ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c0 >> 32)) << 32) |
            (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c0);
@@ -896,8 +884,11 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
       const unsigned long long r0 = sh ? (c0 >> sh) | (c1 << (64 - sh)) : c0;
       const unsigned long long r1 = sh ? (c1 >> sh) | (c0 << (64 - sh)) : c1;
       const int q = r0 ? __builtin_ctzll(r0) : r1 ? 64 + __builtin_ctzll(r1) : 128;
-      const int fin = min(min(q + 1, 128), avail - done);
-      // ---- lane = expert: this wave's half of the window positions head .. head + fin - 1
+      fin = min(min(q + 1, 128), avail - done);
+    }
+    if (!consumer) {
+      // ---- the producers retire them: lane = expert, wave 2 + pw the half pw of the window
+      // positions head .. head + fin - 1 (the consumers fetch their next tokens meanwhile)
       if (fin > 0) {
         unsigned long long lo0, hi0, lo1, hi1;
         below128(head, lo0, hi0);
@@ -928,6 +919,36 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
           const unsigned below_cut = (1u << cut) - 1u;
           atomicOr(&S.obits[first & (kSpecOutWords - 1)][lane], qb & ~below_cut);
           if (cut != 0) atomicOr(&S.obits[(first + 4) & (kSpecOutWords - 1)][lane], qb & below_cut);
+        }
+      }
+    } else {
+      // ---- the consumers fetch the tokens that take the freed positions --------------------
+      // (only their data: the masks belong to the producers until the barrier below; the
+      // first guesses join them at the start of the next sweep)
+      {
+        const int d2 = done + fin;
+        // (the switch for the first guesses, as wave 0 works it out for everybody below)
+        const bool g2 = sweeps + 1 == kSpecCheckSweeps ? d2 - done_mark >= kSpecGuessProgress : guess_on;
+        const int avail2 = min(nflex_tok, min(__builtin_amdgcn_readfirstlane(S.staged[par][0]),
+                                              __builtin_amdgcn_readfirstlane(S.staged[par][1])));
+        const int pos = 64 * pw + lane;
+        const int f2 = d2 + ((pos - (d2 & 127)) & 127);
+        if (f2 < avail2 && cur_f != f2) {
+          const SpecTok<CP>* src = &ring[f2 & (kRing2 - 1)];
+          const uint4 ids = src->ids;
+          const unsigned idw[4] = {ids.x, ids.y, ids.z, ids.w};
+          sel = 0;
+#pragma unroll
+          for (int j = 0; j < CP; ++j) {
+            ex[j] = (idw[j >> 2] >> (8 * (j & 3))) & 255;
+            b[j] = src->b[j];  // (bit 31, the guess, drops out of the key's shift)
+          }
+          if (g2) {
+#pragma unroll
+            for (int j = 0; j < CP; ++j) sel |= (b[j] >> 31) << j;  // the producer's first guess
+          }
+          cur_f = f2;
+          fresh = true;
         }
       }
       if (wave == 0) {
