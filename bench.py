@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # kernel sources it was taken on: the record carries their hash and `traffic` is
 # reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "a1cd1fd9f2dbb0b3",
+    "sources_sha256_16": "9586f3534e2a3bf4",
     "workload": "deepseek",
     "fetch_kib": 33902.35, "fetch_scale": 1.9997,
     "write_kib": 1024.23, "write_scale": 1.0,
