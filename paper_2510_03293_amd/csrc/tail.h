@@ -162,7 +162,8 @@ __device__ __forceinline__ void count_smaller4(unsigned key, unsigned w, int& cn
       "s_nop 1\n\t"
       : [cnt] "+v"(cnt), [e0] "=&s"(e0), [e1] "=&s"(e1), [e2] "=&s"(e2), [e3] "=&s"(e3),
         [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [cy] "=&s"(cy)
-      : [key] "v"(key), [w] "s"(w));
+      : [key] "v"(key), [w] "s"(w)
+      : "scc");  // (the scalar bit-field extracts and the shift set SCC)
 }
 
 // One flexible token: returns whether this lane's expert is chosen.
@@ -247,29 +248,48 @@ __device__ __forceinline__ void chain_walk(ChainBatch* buf, int ft0, int r_start
         if (r >= n) continue;
         const uint16_t* recp = cur->rec[tl] + (lane_ok ? mypos : 0);
         const uint4* cidp = cur->cids[tl];
-        unsigned rec_next = recp[r * EP];
-        uint4 ids_next = cidp[r];
+        // the record of token r is in (rec_a, ids_a) at the top of every round; the next
+        // record's LDS reads fly during a step.  Two tokens per round, so that the records
+        // alternate between two sets of registers instead of being copied.
+        unsigned rec_a = recp[r * EP], rec_b = 0;
+        uint4 ids_a = cidp[r], ids_b = make_uint4(0, 0, 0, 0);
+        auto step = [&](unsigned rec, const uint4 ids, int sh) {
+          const bool cand = lane_ok && rec != 0xFFFFu;
+          bool chosen;
+          if constexpr (CP == 0) {
+            chosen = chain_step_wide((unsigned)lsum + (rec >> 6), rec & 63u, cand, k);
+          } else {
+            const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
+            chosen = chain_step<CP>(key, cand, ids, k);
+          }
+          lsum += chosen ? 1 : 0;
+          hist |= (chosen ? 1u : 0u) << sh;
+        };
         while (r < n) {
           // up to the end of the tile or of the 32-token output word, whichever is first
           const int sh0 = f & 31;
           const int seg = min(n - r, 32 - sh0);
-          for (int sh = sh0; sh < sh0 + seg; ++sh, ++r) {
-            const unsigned rec = rec_next;
-            const uint4 ids = ids_next;
-            if (r + 1 < n) {  // next record's LDS reads fly during this step
-              rec_next = recp[(r + 1) * EP];
-              ids_next = cidp[r + 1];
+          const int end = sh0 + seg;
+          int sh = sh0;
+          for (; sh + 2 <= end; sh += 2, r += 2) {
+            rec_b = recp[(r + 1) * EP];  // (r + 1 < n: two tokens are left)
+            ids_b = cidp[r + 1];
+            step(rec_a, ids_a, sh);
+            if (r + 2 < n) {
+              rec_a = recp[(r + 2) * EP];
+              ids_a = cidp[r + 2];
             }
-            const bool cand = lane_ok && rec != 0xFFFFu;
-            bool chosen;
-            if constexpr (CP == 0) {
-              chosen = chain_step_wide((unsigned)lsum + (rec >> 6), rec & 63u, cand, k);
-            } else {
-              const unsigned key = cand ? (((unsigned)lsum << 4) + rec) : 0xFFFFFFFFu;
-              chosen = chain_step<CP>(key, cand, ids, k);
+            step(rec_b, ids_b, sh + 1);
+          }
+          if (sh < end) {
+            if (r + 1 < n) {
+              rec_b = recp[(r + 1) * EP];
+              ids_b = cidp[r + 1];
             }
-            lsum += chosen ? 1 : 0;
-            hist |= (chosen ? 1u : 0u) << sh;
+            step(rec_a, ids_a, sh);
+            rec_a = rec_b;
+            ids_a = ids_b;
+            ++r;
           }
           f += seg;
           if ((f & 31) == 0) {
