@@ -169,14 +169,15 @@ __device__ __forceinline__ void count_smaller4(unsigned key, unsigned w, int& cn
 // One flexible token: returns whether this lane's expert is chosen.
 template <int CP>
 __device__ __forceinline__ bool chain_step(unsigned key, bool cand, const uint4 ids, int k) {
-  int smaller = 0;
+  // (two counts: the second group's additions do not wait for the first group's)
+  int smaller = 0, more = 0;
   count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.x), smaller);
-  if (CP > 4) count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.y), smaller);
+  if (CP > 4) count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.y), more);
   if (CP > 8) {
     count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.z), smaller);
-    count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.w), smaller);
+    count_smaller4(key, __builtin_amdgcn_readfirstlane(ids.w), more);
   }
-  return cand && smaller < k;
+  return cand && smaller + more < k;
 }
 
 // Wave-wide minimum as a scalar: two exchanges inside the quads, the half-row and row
