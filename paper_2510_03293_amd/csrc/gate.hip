@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kGateThreads) void gate_analyse_bf16_kernel(
 //     and arrive while it runs, so the memory pipeline of the compute unit does not drain
 //     between tiles;
 //   - a tile is reported to the chain workgroup (every wavefront counts itself into the
-//     word of the tile's segment) one step into the next tile, when the stores of its
+//     tile's word) one step into the next tile, when the stores of its
 //     records have long been acknowledged: nobody waits for a store.
 // What the chain workgroup reads is stored write-through (store_for_chain); a wavefront
 // counts itself in only after all its stores are acknowledged, and the chain workgroup

@@ -1236,10 +1236,9 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   int decided = 0;
   unsigned hist0 = 0;
   if (use_spec) {
-    // First guesses (GUESS) where tokens rarely compete: many experts per candidate.
-    // With few experts every sweep ends at an early conflict and they only cost.
-    // (with few experts every sweep ends at an early conflict and the guesses only cost:
-    // one consumer wave, a window of 64)
+    // First guesses and the window of 128 where tokens rarely compete: many experts per
+    // candidate.  With few experts every sweep ends at an early conflict and the guesses
+    // only cost: one consumer wave, a window of 64.
 #define LASER_SPEC_WALK(CP_, KK_)                                                                   \
   (a.E >= 4 * CP_ ? spec_walk2<CP_, KK_>(lds, nflex_tok, a, ws, wave, lane, lin, gflex, hist0) \
                   : spec_walk<CP_, KK_, false>(lds, spec_sh, nflex_tok, a, ws, wave, lane, lin, gflex, hist0))
@@ -1285,11 +1284,13 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
 // of the tiles behind them.  A large call is therefore cut into segments of a.seg_tiles
 // tiles; the chain over a segment starts as soon as the gate kernel has analysed the
 // segment's tiles, inside that kernel (workgroup 0 of its grid), while the other
-// workgroups go on streaming the later tiles.  Every analysis workgroup counts itself into
-// its segment's word of ws.seg when its records are written (release); the chain workgroup
-// waits for a segment to be complete (acquire), bounded: if it ever gives up, or simply
-// has not come to the last segment when the gate kernel's tiles are done, the tail
-// kernel's chain workgroup takes over where it stopped, behind the kernel boundary.
+// workgroups go on streaming the later tiles.  Every wavefront of an analysis workgroup
+// counts itself into its tile's word of ws.seg when its records are written and
+// acknowledged (what the chain reads is stored write-through); the chain workgroup waits
+// for all tiles of a segment to be complete and then invalidates its caches (acquire).
+// The wait is bounded: should it ever give up, the tail kernel's chain workgroup takes
+// over where it stopped, behind the kernel boundary; otherwise the tail kernel's finds
+// every segment done and only writes the totals and raises the flags.
 // What is carried from segment to segment (ws.seg) is small: per expert the assignments
 // so far, and where the numbering of flexible tokens and tiles goes on.  A segment's
 // flexible tokens are numbered from a multiple of 32 (words of chain_bits / chain_cum
@@ -1325,7 +1326,7 @@ __device__ __forceinline__ void advance_view(Workspace& v, const RouteArgs& a, i
 // Polls of a segment's counter before the chain workgroup inside the gate kernel leaves
 // the rest to the tail kernel (a poll is a memory round trip plus a short sleep).
 constexpr long long kSegPollLimit = 1ll << 20;
-// Every wavefront of an analysis workgroup counts itself into its tile's segment.
+// Every wavefront of an analysis workgroup counts itself into its tile's word.
 constexpr int kGateSignals = 8;
 
 // The chain of a call, by the chain workgroup (kTailThreads threads) of the gate kernel
