@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblaser_route.so")
-SOURCES = ["api.hip", "gate.hip", "route.hip", "metrics.hip", "random.hip", "bench_helpers.hip"]
+SOURCES = ["api.hip", "gate.hip", "gate_pipeline.hip", "route.hip", "metrics.hip", "random.hip", "bench_helpers.hip"]
 
 # -ffp-contract=off: the routing decisions follow a fixed binary32 operation
 # order; fused multiply-adds appear only where the source writes them.
@@ -21,17 +21,34 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source into liblaser_route.so (always recompiles)."""
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = ["hipcc", *HIPCC_FLAGS, "-o", LIB_PATH, *srcs]
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+    return err
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source into liblaser_route.so (always recompiles).  The sources are
+    compiled side by side (one hipcc each, objects in a temporary folder), then linked."""
+    import concurrent.futures
+    import tempfile
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="laser_build_") as tmp:
+        jobs = []
+        for src in SOURCES:
+            obj = os.path.join(tmp, os.path.splitext(src)[0] + ".o")
+            jobs.append((["hipcc", *flags, "-c", os.path.join(CSRC, src), "-o", obj], obj))
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
+            errs = list(pool.map(_run, [cmd for cmd, _ in jobs]))
+        errs.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH,
+                          *[obj for _, obj in jobs]]))
+    if verbose:
+        text = "\n".join(e for e in errs if e.strip())
+        if text:
+            print(text)
     return LIB_PATH
 
 

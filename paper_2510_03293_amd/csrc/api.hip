@@ -212,8 +212,8 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   const bool general = wide || (random && !resample);
   if (resample && !a.st_pool) a.pool_in_ws = 1;
   // Pipelined: one problem through the fused bf16 kernel, nothing between it and the tail
-  // kernel, no statistics (the kernel variants with statistics are not built for it).
-  if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample && !wants_stats(a)) {
+  // kernel.
+  if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample) {
     choose_segments(a, params->pipeline_tiles);
   }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given

@@ -206,6 +206,10 @@ inline void clear_stale_error() { (void)hipGetLastError(); }
 hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
                                     const Workspace& ws, int32_t* expert_ids, float* weights,
                                     float* logits_out, size_t logits_stride, hipStream_t s);
+// the same for a pipelined call (a.nseg > 0, one problem): clearing kernel + persistent kernel
+hipError_t launch_gate_pipeline_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
+                                     const Workspace& ws, int32_t* expert_ids, float* weights,
+                                     float* logits_out, hipStream_t s);
 // (problem b of `nbatch`: hidden + b*T*H, w + b*E*H -> logits + b*logits_stride floats)
 hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E, int nbatch,
                            float* logits, size_t logits_stride, hipStream_t s);

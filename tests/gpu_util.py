@@ -31,9 +31,10 @@ def run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormaliz
     return _collect(buf, loads, buf.logits)
 
 
-def run_route_stats(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, which=(True, True, True)):
+def run_route_stats(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, which=(True, True, True),
+                    pipeline_tiles=0):
     """GPU laser_route_stats; routing outputs as run_route plus the requested statistics."""
-    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype)
+    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, pipeline_tiles=pipeline_tiles)
     hd, wd = to_device(hidden), to_device(w_gate)
     T, H = hd.shape
     E = wd.shape[0]

@@ -165,3 +165,22 @@ def test_segmented_call_twice_on_one_workspace():
         gpu = u._collect(buf, loads, buf.logits)
         ref = oracle.route(gpu["logits"], k, c, eps, tfix, np.zeros(E, dtype=np.int32), True)
         u.assert_discrete_equal(gpu, ref, f"second call eps {eps}")
+
+
+@pytest.mark.parametrize("T,H,E,k,c,seg", [(3000, 2048, 64, 6, 8, 5), (1500, 512, 8, 2, 4, 3), (2100, 4096, 33, 3, 9, 7)])
+def test_segmented_call_with_statistics(T, H, E, k, c, seg):
+    """laser_route_stats is pipelined like laser_route: routing against the oracle, the
+    statistics bit-equal to those of the call in one piece (which test_token_statistics
+    checks against the oracle's)."""
+    import oracle
+    u = _util()
+    hidden, w, flat = _mixed_gate(T + seg, T, H, E, 0.3)
+    loads = np.zeros(E, dtype=np.int32)
+    eps, tfix = 0.40, 0.80
+    gpu = u.run_route_stats(hidden, w, wl.DTYPE_BF16, k, c, eps, tfix, loads, pipeline_tiles=seg)
+    ref = oracle.route(gpu["logits"], k, c, eps, tfix, loads, True)
+    u.assert_discrete_equal(gpu, ref, f"stats seg{seg}")
+    whole = u.run_route_stats(hidden, w, wl.DTYPE_BF16, k, c, eps, tfix, loads, pipeline_tiles=1)
+    _same(gpu, whole, f"stats seg{seg}")
+    for key in ("topk_mass", "entropy", "pool_size"):
+        assert np.array_equal(gpu[key], whole[key]), key
