@@ -31,12 +31,13 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # kernel sources it was taken on: the record carries their hash and `traffic` is
 # reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "9586f3534e2a3bf4",
+    "sources_sha256_16": "b44368493fd68062",
     "workload": "deepseek",
     "fetch_kib": 33902.35, "fetch_scale": 1.9997,
     "write_kib": 1024.23, "write_scale": 1.0,
 }
-GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/analyse.h")
+GATE_SOURCES = ("paper_2510_03293_amd/csrc/gate.hip", "paper_2510_03293_amd/csrc/gate_tile.h",
+                "paper_2510_03293_amd/csrc/analyse.h")
 
 
 def measured_traffic_bytes(workload):
