@@ -184,3 +184,90 @@ def test_segmented_call_with_statistics(T, H, E, k, c, seg):
     _same(gpu, whole, f"stats seg{seg}")
     for key in ("topk_mass", "entropy", "pool_size"):
         assert np.array_equal(gpu[key], whole[key]), key
+
+
+def test_pipelined_calls_side_by_side_on_two_streams():
+    """Two pipelined calls at the same time: each brings a persistent grid that wants every
+    compute unit, and a chain workgroup that waits (bounded) for its own grid's tiles.
+    Whatever the hardware interleaves, both calls finish and give what they give alone."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    T, H, E, k, c = 20000, 256, 64, 6, 8          # 313 tiles: more than one round of workgroups
+    params = B.make_params(k, c, 0.40, 0.80, dtype=wl.DTYPE_BF16, pipeline_tiles=40)
+    prob = []
+    for i in range(4):
+        h, w, _ = _mixed_gate(300 + i, T, H, E, 0.2)
+        prob.append((u.to_device(h), u.to_device(w)))
+
+    def run(streams):
+        bufs = [B.RouteBuffers(T, H, E, params) for _ in prob]
+        loads = [torch.zeros(E, dtype=torch.int32, device="cuda") for _ in prob]
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for i, (hd, wd) in enumerate(prob):
+                st = streams[i % len(streams)]
+                B.laser_route(hd, wd, T, H, E, params, loads[i], bufs[i].expert_ids, bufs[i].weights,
+                              bufs[i].permutation, bufs[i].expert_offsets, None, bufs[i].workspace, st)
+        torch.cuda.synchronize()
+        for b in bufs:
+            assert B.laser_status(b.workspace) == B.STATUS_COMPLETE
+        return [(b.expert_ids.clone(), b.permutation.clone(), l.clone()) for b, l in zip(bufs, loads)]
+
+    one = run([torch.cuda.current_stream()])
+    two = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    for (i1, p1, l1), (i2, p2, l2) in zip(one, two):
+        assert torch.equal(i1, i2) and torch.equal(p1, p2) and torch.equal(l1, l2)
+
+
+def test_pipelined_call_replayed_from_a_hip_graph():
+    """A pipelined call is three launches (its counters are cleared by a kernel): captured
+    once, replayed on new inputs with eager work in between, every replay must give what
+    the eager call gives."""
+    import torch
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    T, H, E, k, c = 6000, 256, 64, 6, 8
+    params = B.make_params(k, c, 0.40, 0.80, dtype=wl.DTYPE_BF16, pipeline_tiles=13)
+    hid = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    inputs = [_mixed_gate(500 + i, T, H, E, 0.25) for i in range(4)]
+    wd = u.to_device(inputs[0][1])
+    buf = B.RouteBuffers(T, H, E, params)
+    loads = torch.zeros(E, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def enqueue(stream):
+        B.laser_route(hid, wd, T, H, E, params, loads, buf.expert_ids, buf.weights, buf.permutation,
+                      buf.expert_offsets, None, buf.workspace, stream)
+
+    def fill(rep):
+        hid.copy_(u.to_device(inputs[rep % len(inputs)][0]))
+        loads.zero_()
+
+    fill(0)
+    with torch.cuda.stream(side):
+        enqueue(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    fill(0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(side)
+    torch.cuda.synchronize()
+    for rep in range(1, 5):
+        fill(rep)
+        torch.cuda.synchronize()
+        enqueue(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        want = (buf.expert_ids.clone(), buf.weights.clone(), buf.permutation.clone(), buf.expert_offsets.clone(),
+                loads.clone())
+        buf.expert_ids.fill_(-1)
+        buf.permutation.fill_(-1)
+        fill(rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (buf.expert_ids, buf.weights, buf.permutation, buf.expert_offsets, loads)
+        for x, y in zip(want, got):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"replay {rep}"
+        assert B.laser_status(buf.workspace) == B.STATUS_COMPLETE
