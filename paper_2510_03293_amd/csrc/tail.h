@@ -87,6 +87,13 @@ __device__ __forceinline__ unsigned load_published(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Flips this lane's bit of a 64-bit mask of lanes in LDS.  As a 32-bit operation on the
+// word the bit is in: lanes 0..31 and 32..63 that flip bits of the same mask then work on
+// different addresses, and an LDS atomic on one address is served lane after lane.
+__device__ __forceinline__ void flip_lane_bit(unsigned long long* mask, int lane) {
+  atomicXor(reinterpret_cast<unsigned*>(mask) + (lane >> 5), 1u << (lane & 31));
+}
+
 // Orders this wavefront's LDS traffic (another lane's write before this lane's read)
 // without waiting for anything in flight to memory: a fence at workgroup scope would
 // also wait for the chain's output stores.
@@ -529,7 +536,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
   // are used while the last run of sweeps retired more than kSpecGuessProgress tokens.
   bool guess_on = GUESS;
   int decided = 0;
-  const unsigned long long lane_bit = 1ull << lane, lb = lanes_below(lane);
+  const unsigned long long lb = lanes_below(lane);
 
   const int nep = (nflex_tok + kSpecSeg - 1) / kSpecSeg;
   for (int ep = 0; ep < nep; ++ep) {
@@ -569,7 +576,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
           if (enters) {
 #pragma unroll
             for (int j = 0; j < CP; ++j)
-              if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
+              if ((sel >> j) & 1u) flip_lane_bit(&M[ex[j]].mask, lane);
           }
           lds_wave_fence();
           __builtin_amdgcn_wave_barrier();
@@ -592,7 +599,7 @@ __device__ __forceinline__ int spec_walk(uint8_t* lds, SpecShared& sp, int nflex
           // flip this lane's bit in the masks of the experts whose choice changed
 #pragma unroll
           for (int j = 0; j < CP; ++j)
-            if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask, lane_bit);
+            if ((diff >> j) & 1u) flip_lane_bit(&M[ex[j]].mask, lane);
         }
         sel = newsel;
         // tokens up to the first changed one are final
@@ -736,7 +743,7 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
 
   const bool consumer = wave < 2;
   const int pw = wave & 1;  // consumer: which half of the window; producer: which half of a batch
-  const unsigned long long lane_bit = 1ull << lane, lb = lanes_below(lane);
+  const unsigned long long lb = lanes_below(lane);
 
   // ---- consumer state ------------------------------------------------------------------
   int ex[CP];       // candidate experts by rank
@@ -794,7 +801,7 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
         if (enters) {
 #pragma unroll
           for (int j = 0; j < CP; ++j)
-            if ((sel >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
+            if ((sel >> j) & 1u) flip_lane_bit(&M[ex[j]].mask[pw], lane);
         }
         lds_wave_fence();
         __builtin_amdgcn_wave_barrier();
@@ -829,7 +836,7 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
         // flip this lane's bit in the masks of the experts whose choice changed
 #pragma unroll
         for (int j = 0; j < CP; ++j)
-          if ((diff >> j) & 1u) atomicXor(&M[ex[j]].mask[pw], lane_bit);
+          if ((diff >> j) & 1u) flip_lane_bit(&M[ex[j]].mask[pw], lane);
       }
       sel = newsel;
       // (should the other wave not have shown up in time, which does not happen while both
