@@ -541,6 +541,28 @@ def main():
 
         decode_figures(args.preset, extras)
 
+        # what a call costs as the batch shrinks: the first rows of the same layers
+        # (a prefix of a row-major [T, H] buffer is itself one), each with its own gate
+        by_tokens = {}
+        lsm = torch.zeros(E, dtype=torch.int32, device="cuda")
+        for Ts in (64, 256, 1024, 4096, 8192):
+            if Ts >= T:
+                continue
+            def small_calls(n):
+                for i in range(n):
+                    layer = i % layers
+                    B.laser_route(w.hidden[layer], w.wgate[layer], Ts, H, E, w.params[layer], lsm,
+                                  w.buf.expert_ids, w.buf.weights, w.buf.permutation, w.buf.expert_offsets,
+                                  None, w.buf.workspace, stream)
+            lsm.zero_()
+            small_calls(20)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            small_calls(200)
+            torch.cuda.synchronize()
+            by_tokens[str(Ts)] = (time.perf_counter() - t0) * 1e6 / 200
+        extras["us_per_call_by_tokens"] = by_tokens
+
         # all layers of the timed workload in one batched call -- possible only where
         # their inputs exist together (micro-batches in flight at different layers), so
         # it is context, never the headline
