@@ -1056,6 +1056,7 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
                                 int32_t* __restrict__ expert_offsets, const ChainSeg seg) {
   ChainBatch* buf = reinterpret_cast<ChainBatch*>(lds);
   __shared__ int wave_tot[kChainWaves][64];
+  __shared__ __align__(16) int tb_rows[kChainWaves][4 * 64];
   __shared__ int wave_flex[kChainWaves], wave_tok[kChainWaves];
   __shared__ SpecShared spec_sh;
   // (as a scalar: branches on the wave number are then uniform for the compiler, and
@@ -1097,11 +1098,14 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   const int gper = (groups + kChainWaves - 1) / kChainWaves;
   const int ga = min(wave * gper, groups), gb = min(ga + gper, groups);
   int nfl = 0, ntok = 0;
-  unsigned long long first_fm = 0ull;  // mask of this lane's tile in the wave's first group
+  // masks of this lane's tiles in the wave's first two groups (kept for the second pass
+  // over the groups below: a segment of a pipelined call has no more per wave)
+  unsigned long long first_fm = 0ull, second_fm = 0ull;
   for (int g = ga; g < gb; ++g) {
     const int tile = g * 64 + lane;
     const unsigned long long fm = tile < ntiles ? ws.flexmask[tile] : 0ull;
     if (g == ga) first_fm = fm;
+    if (g == ga + 1) second_fm = fm;
     nfl += __builtin_popcountll(__builtin_amdgcn_ballot_w64(fm != 0ull));
     ntok += __builtin_popcountll(fm);
   }
@@ -1154,13 +1158,30 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
       carry += v;
     }
     if (need_tile_base) {
-#pragma unroll 16
-      for (int tile = ta; tile < tb; ++tile) {
+      // Four tiles per store: a wavefront has at most 64 memory operations in flight, and
+      // with one store per tile a long run of tiles (a segment of a pipelined call: 128
+      // per wave) would wait for memory round trips.  The four rows meet in a wave-private
+      // piece of LDS, laid out like the rows of tile_base, and leave as 16 bytes per lane.
+      int* rows = tb_rows[wave];
+      int tile = ta;
+      for (; tile + 4 <= tb; tile += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          rows[u * 64 + lane] = run;
+          run += stage[(tile + u) * 64 + lane];
+        }
+        const int4 v = reinterpret_cast<const int4*>(rows)[lane];
+        reinterpret_cast<int4*>(ws.tile_base + (size_t)(sb0 + tile) * 64)[lane] = v;
+      }
+      for (; tile < tb; ++tile) {
         ws.tile_base[(size_t)(sb0 + tile) * 64 + lane] = run;
         run += stage[tile * 64 + lane];
       }
     }
-    __syncthreads();  // stage and wave_tot are reused by the next super-batch
+    // stage and wave_tot are reused by the next super-batch (after the last one nothing
+    // writes LDS before the next barrier, and that barrier then waits for the stores
+    // above once, together with those below)
+    if (sb0 + kChainStageTiles < ntiles) __syncthreads();
   }
   const int total_fixed = carry;
 
@@ -1172,7 +1193,8 @@ __device__ __forceinline__ void chain_workgroup(uint8_t* lds, const RouteArgs& a
   const int fbase = seg.on ? seg.fbase : 0;
   for (int g = ga; g < gb && (nflex_tiles > 0 || seg.on); ++g) {
     const int tile = g * 64 + lane;
-    const unsigned long long fm = g == ga ? first_fm : (tile < ntiles ? ws.flexmask[tile] : 0ull);
+    const unsigned long long fm =
+        g == ga ? first_fm : g == ga + 1 ? second_fm : (tile < ntiles ? ws.flexmask[tile] : 0ull);
     const bool f = fm != 0ull;
     const unsigned long long bal = __builtin_amdgcn_ballot_w64(f);
     const int ord = fbefore + __builtin_popcountll(bal & lanes_below(lane));
