@@ -809,7 +809,10 @@ __device__ __forceinline__ int spec_walk2(uint8_t* lds, int nflex_tok, const Rou
         met = false;
         for (int it = 0; it < kSpecMeetPolls && !met; ++it) {
           lds_wave_fence();
-          met = __builtin_amdgcn_readfirstlane(*(volatile int*)&S.met[pw ^ 1]) > total_sweeps;
+          // (read as LDS: through a plain volatile pointer the compiler emits a flat load,
+          // which takes the long way through the vector memory pipeline)
+          typedef __attribute__((address_space(3))) volatile int lds_volatile_int;
+          met = __builtin_amdgcn_readfirstlane(*(lds_volatile_int*)&S.met[pw ^ 1]) > total_sweeps;
         }
       }
       // the window positions before this one: from the head up to pos, cyclically
