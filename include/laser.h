@@ -111,7 +111,10 @@ typedef struct laser_params {
                          /* batches of 96 K tokens or more); 1: never; n >= 2: segments of */
                          /* n tiles of 64 tokens whenever the batch has more tiles.  The   */
                          /* results do not depend on it.                                   */
-  uint32_t reserved;     /* 0                                                           */
+  uint32_t split_k;      /* Small bf16 calls of laser_route (up to 2048 tokens): the        */
+                         /* contraction axis of the projection is cut over eight workgroups */
+                         /* per tile of 64 tokens.  0: the library decides; 1: never.  The  */
+                         /* results, logits included, do not depend on it.                  */
 } laser_params_t;
 
 /* Bytes of device workspace a call with these sizes needs (0 on bad arguments).

@@ -48,7 +48,7 @@ class LaserParams(ctypes.Structure):
         ("stream", ctypes.c_uint32),
         ("poll_budget", ctypes.c_uint32),
         ("pipeline_tiles", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("split_k", ctypes.c_uint32),
     ]
 
 
@@ -116,10 +116,10 @@ _lib = _load()
 def make_params(k: int, c: int, eps_high: float, t_fix: float, dtype: int = DTYPE_BF16,
                 renormalize: bool = True, trim_mode: int = TRIM_TOP, seed: int = 0,
                 stream: int = 0, token_offset: int = 0, poll_budget: int = 0,
-                pipeline_tiles: int = 0) -> LaserParams:
+                pipeline_tiles: int = 0, split_k: int = 0) -> LaserParams:
     return LaserParams(ctypes.sizeof(LaserParams), k, c, eps_high, t_fix, trim_mode,
                        1 if renormalize else 0, dtype, seed, token_offset, stream, poll_budget,
-                       pipeline_tiles, 0)
+                       pipeline_tiles, split_k)
 
 
 def laser_strerror(code: int) -> str:

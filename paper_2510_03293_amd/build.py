@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblaser_route.so")
-SOURCES = ["api.hip", "gate.hip", "gate_pipeline.hip", "route.hip", "metrics.hip", "random.hip", "bench_helpers.hip"]
+SOURCES = ["api.hip", "gate.hip", "gate_pipeline.hip", "gate_split.hip", "route.hip", "metrics.hip", "random.hip", "bench_helpers.hip"]
 
 # -ffp-contract=off: the routing decisions follow a fixed binary32 operation
 # order; fused multiply-adds appear only where the source writes them.

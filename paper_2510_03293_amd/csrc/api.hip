@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t status, logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
-      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, seg, total;
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, seg, split, total;
 };
 
 // cw: candidates per token record (record_width(c)).  The status words come first, so
@@ -51,6 +51,7 @@ static Layout layout(int T, int E, int cw) {
   L.lin_copy = off;   off += align_up(64 * 4);
   L.pool = off;       off += align_up((size_t)T * 4);
   L.seg = off;        off += align_up((kSegDone + ntiles) * 4);
+  L.split = off;      off += align_up(ntiles <= (size_t)kSplitMaxTiles ? ntiles * 8 * kTile * 64 * 4 : 0);
   L.total = off + 256;
   return L;
 }
@@ -83,6 +84,7 @@ Workspace carve_workspace(void* base, int T, int E, int cw) {
   w.pool = reinterpret_cast<int32_t*>(b + L.pool);
   w.status = reinterpret_cast<int32_t*>(b + L.status);
   w.seg = reinterpret_cast<int32_t*>(b + L.seg);
+  w.split_part = reinterpret_cast<float*>(b + L.split);
   return w;
 }
 
@@ -122,6 +124,8 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.seg_tiles = 0;
   a.seg_first = 0;
   a.nseg = 0;
+  a.split = 0;
+  a.split_cnt = nullptr;
   return a;
 }
 
@@ -215,6 +219,14 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   // kernel.
   if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample) {
     choose_segments(a, params->pipeline_tiles);
+    // Small calls: eight workgroups per tile share the contraction axis (gate_split.hip).
+    if (a.nseg == 0 && a.ntiles >= 1 && a.ntiles <= kSplitMaxTiles && params->split_k != 1) {
+      int32_t* counters = split_counters_for(workspace);
+      if (counters != nullptr) {
+        a.split = 8;
+        a.split_cnt = counters;
+      }
+    }
   }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given
   const size_t lstride = logits_out ? (size_t)T * E : ws_one / sizeof(float);

@@ -227,6 +227,7 @@ hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, co
                                     float* logits_out, size_t logits_stride, hipStream_t s) {
   if (a.ntiles == 0) return hipSuccess;
   if (a.nseg > 0) return launch_gate_pipeline_bf16(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  if (a.split > 0) return launch_gate_split_bf16(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
   switch (a.EP) {
     case 8: return launch_one<1, 1>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);
     case 16: return launch_one<1, 2>(hidden, w, H, a, ws, expert_ids, weights, logits_out, logits_stride, s);

@@ -13,6 +13,7 @@ constexpr int kMaxE = 64;        // experts: one lane of a wavefront per expert
 constexpr int kMaxC = 16;        // trimming size the fast kernels carry (candidate ranks fit 4 bits)
 constexpr int kWideC = 64;       // trimming sizes above kMaxC: records of kWideC candidates, general kernels
 constexpr int kMaxK = 16;        // experts per token
+constexpr int kSplitMaxTiles = 32;  // calls of up to this many tiles may cut the contraction axis over workgroups
 
 // Per-call scalars handed to every kernel by value.
 struct RouteArgs {
@@ -44,6 +45,10 @@ struct RouteArgs {
   int seg_tiles;       // tiles per segment; 0: the call is not pipelined
   int seg_first;       // tiles of segment 0 (a short one lets the chain start early)
   int nseg;            // segments: 1 + ceil((ntiles - seg_first) / seg_tiles); 0 when not pipelined
+  // small single problems through the fused bf16 kernel: the contraction axis of a tile cut
+  // over `split` workgroups (gate_split.hip)
+  int split;           // workgroups per tile (2, 4 or 8); 0: one workgroup per tile
+  int32_t* split_cnt;  // [ntiles] arrival counters, zero between calls (the library's own memory)
 };
 // First tile of segment j of a pipelined call (j <= nseg; segment nseg starts at ntiles or beyond).
 __host__ __device__ inline int segment_start(const RouteArgs& a, int j) {
@@ -90,6 +95,8 @@ struct Workspace {
                                //     first bytes of the workspace, so that a query needs no sizes)
   int32_t* seg;                // [kSegDone + ntiles] pipelined calls only, see kSeg*: how far the
                                //     chain has come, and per tile how much of its analysis is written
+  float* split_part;           // [ntiles,8,64,64] split calls only (ntiles <= kSplitMaxTiles): the partial
+                               //     logit tiles of the eight wavefront roles
 };
 
 // Problem b of a batched call.  All problems share the sizes; every array of problem
@@ -130,6 +137,7 @@ __device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size
   w.pool = shifted(w0.pool, bytes);
   w.status = shifted(w0.status, bytes);
   w.seg = shifted(w0.seg, bytes);
+  w.split_part = shifted(w0.split_part, bytes);
   return w;
 }
 
@@ -210,6 +218,13 @@ hipError_t launch_gate_analyse_bf16(const void* hidden, const void* w, int H, co
 hipError_t launch_gate_pipeline_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
                                      const Workspace& ws, int32_t* expert_ids, float* weights,
                                      float* logits_out, hipStream_t s);
+// the same for a split call (a.split > 0, one problem)
+hipError_t launch_gate_split_bf16(const void* hidden, const void* w, int H, const RouteArgs& a,
+                                  const Workspace& ws, int32_t* expert_ids, float* weights,
+                                  float* logits_out, hipStream_t s);
+// the arrival counters of split calls on this workspace (device memory of the current device;
+// NULL if none can be had: the call then runs without the split)
+int32_t* split_counters_for(const void* workspace);
 // (problem b of `nbatch`: hidden + b*T*H, w + b*E*H -> logits + b*logits_stride floats)
 hipError_t launch_gate_f32(const float* hidden, const float* w, int T, int H, int E, int nbatch,
                            float* logits, size_t logits_stride, hipStream_t s);

@@ -20,10 +20,10 @@ def to_device(arr: np.ndarray, dtype: int | None = None) -> torch.Tensor:
 
 
 def run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True,
-              pipeline_tiles=0):
+              pipeline_tiles=0, split_k=0):
     """GPU laser_route on numpy inputs; returns a dict of numpy outputs incl. logits."""
     params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, renormalize=renormalize,
-                           pipeline_tiles=pipeline_tiles)
+                           pipeline_tiles=pipeline_tiles, split_k=split_k)
     hd, wd = to_device(hidden), to_device(w_gate)
     loads = torch.from_numpy(np.ascontiguousarray(loads_in, dtype=np.int32)).cuda()
     buf = B.route(hd, wd, params, loads, want_logits=True)
@@ -32,9 +32,9 @@ def run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormaliz
 
 
 def run_route_stats(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, which=(True, True, True),
-                    pipeline_tiles=0):
+                    pipeline_tiles=0, split_k=0):
     """GPU laser_route_stats; routing outputs as run_route plus the requested statistics."""
-    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, pipeline_tiles=pipeline_tiles)
+    params = B.make_params(k, c, eps_high, t_fix, dtype=dtype, pipeline_tiles=pipeline_tiles, split_k=split_k)
     hd, wd = to_device(hidden), to_device(w_gate)
     T, H = hd.shape
     E = wd.shape[0]
@@ -123,11 +123,11 @@ def check_from_logits(logits, k, c, eps_high, t_fix, loads_in, renormalize=True,
 
 
 def check_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize=True,
-                label="", logit_rows=None, pipeline_tiles=0):
+                label="", logit_rows=None, pipeline_tiles=0, split_k=0):
     """Full path.  Logits against the fp64 gate (all rows, or a sample of rows);
     discrete outputs against the oracle routed on the GPU's own fp32 logits."""
     gpu = run_route(hidden, w_gate, dtype, k, c, eps_high, t_fix, loads_in, renormalize,
-                    pipeline_tiles)
+                    pipeline_tiles, split_k)
     tol = TOL_LOGIT[dtype]
     if logit_rows is None:
         z = oracle.gate(hidden, w_gate, dtype)

@@ -43,7 +43,7 @@ def test_product_header_holds_no_benchmark_helpers(B):
 def test_strerror_and_struct_size(B):
     assert B.laser_strerror(0) == "ok"
     assert "NULL" in B.laser_strerror(-1)
-    # 8 x 4 bytes, then seed, token_offset, stream, poll_budget, pipeline_tiles, reserved
+    # 8 x 4 bytes, then seed, token_offset, stream, poll_budget, pipeline_tiles, split_k
     assert ctypes.sizeof(B.LaserParams) == 64
 
 
