@@ -548,12 +548,14 @@ def main():
         for Ts in (64, 256, 1024, 4096, 8192):
             if Ts >= T:
                 continue
+            bs = B.RouteBuffers(Ts, H, E, w.params[0])   # (a workspace of the call's own size)
+
             def small_calls(n):
                 for i in range(n):
                     layer = i % layers
                     B.laser_route(w.hidden[layer], w.wgate[layer], Ts, H, E, w.params[layer], lsm,
-                                  w.buf.expert_ids, w.buf.weights, w.buf.permutation, w.buf.expert_offsets,
-                                  None, w.buf.workspace, stream)
+                                  bs.expert_ids, bs.weights, bs.permutation, bs.expert_offsets,
+                                  None, bs.workspace, stream)
             lsm.zero_()
             small_calls(20)
             torch.cuda.synchronize()

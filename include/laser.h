@@ -111,14 +111,18 @@ typedef struct laser_params {
                          /* batches of 96 K tokens or more); 1: never; n >= 2: segments of */
                          /* n tiles of 64 tokens whenever the batch has more tiles.  The   */
                          /* results do not depend on it.                                   */
-  uint32_t split_k;      /* Small bf16 calls of laser_route (up to 2048 tokens): the        */
+  uint32_t split_k;      /* Small bf16 calls of laser_route (up to 4096 tokens): the        */
                          /* contraction axis of the projection is cut over eight workgroups */
-                         /* per tile of 64 tokens.  0: the library decides; 1: never.  The  */
-                         /* results, logits included, do not depend on it.                  */
+                         /* per tile of 64 tokens (four beyond 2048 tokens).  0: the        */
+                         /* library decides; 1: never.  The results, logits included, do    */
+                         /* not depend on it.                                               */
 } laser_params_t;
 
 /* Bytes of device workspace a call with these sizes needs (0 on bad arguments).
- * H may be 0 when only laser_route_from_logits will be called. */
+ * H may be 0 when only laser_route_from_logits will be called.  A workspace of this size
+ * for T tokens also serves every call with fewer tokens (and the same E and params): for
+ * up to 4096 tokens the size includes 128 KiB per tile of 64 tokens that only the small-
+ * call split (split_k) uses, and a call that finds less room runs without the split. */
 size_t laser_workspace_bytes(int32_t T, int32_t H, int32_t E, const laser_params_t* params);
 
 /*
@@ -259,8 +263,8 @@ int laser_status(const void* workspace, void* hip_stream, int32_t* status);
  * laser_route for callers that cannot allocate device memory or carry a workspace
  * around: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The workspace is an array inside the library (one per GPU, held until the
- * process ends) of laser_static_workspace_bytes() bytes; a call whose
- * laser_workspace_bytes(T, H, E, params) exceeds that returns LASER_E_WORKSPACE.  The
+ * process ends) of laser_static_workspace_bytes() bytes; a call that needs more
+ * returns LASER_E_WORKSPACE.  The
  * call allocates nothing and otherwise behaves as laser_route.  All such calls on one
  * GPU share the array: they must be ordered (one stream, or events), calls that overlap
  * race.  laser_status_static() is laser_status() for the current device's array.

@@ -15,7 +15,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t status, logits, rec_cstar, rec_ids, rec_p, rec_Z, rec_lane, flexmask, fixed_cnt, tile_mask, base, chain_bits,
-      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, seg, split, total;
+      chain_cum, flex_list, flex_ord, flex_tok_base, flex_slot, rec_cids, rec_pref, lin_copy, pool, seg, split, needed, total;
 };
 
 // cw: candidates per token record (record_width(c)).  The status words come first, so
@@ -51,12 +51,15 @@ static Layout layout(int T, int E, int cw) {
   L.lin_copy = off;   off += align_up(64 * 4);
   L.pool = off;       off += align_up((size_t)T * 4);
   L.seg = off;        off += align_up((kSegDone + ntiles) * 4);
+  // (last, and optional: a call runs in `needed` bytes, without the split)
+  L.needed = off + 256;
   L.split = off;      off += align_up(ntiles <= (size_t)kSplitMaxTiles ? ntiles * 8 * kTile * 64 * 4 : 0);
   L.total = off + 256;
   return L;
 }
 
 size_t workspace_bytes(int T, int E, int cw) { return layout(T, E, cw).total; }
+size_t workspace_needed_bytes(int T, int E, int cw) { return layout(T, E, cw).needed; }
 
 Workspace carve_workspace(void* base, int T, int E, int cw) {
   const Layout L = layout(T, E, cw);
@@ -192,8 +195,12 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   }
   if ((uintptr_t)workspace & 255) return LASER_E_ALIGN;
   const int cw = record_width(params->c);
+  // (a single problem runs in the bytes it needs; what laser_workspace_bytes reports beyond
+  // them holds the partial tiles of a split call, so a workspace sized for a larger batch
+  // always serves a smaller one)
   const size_t ws_one = workspace_bytes(T, E, cw);  // a multiple of 256
-  if (workspace_bytes_given / (size_t)B < ws_one) return LASER_E_WORKSPACE;
+  const size_t ws_needed = B == 1 ? workspace_needed_bytes(T, E, cw) : ws_one;
+  if (workspace_bytes_given / (size_t)B < ws_needed) return LASER_E_WORKSPACE;
   if (timer && timer->used >= timer->capacity) return LASER_E_RANGE;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -219,11 +226,12 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   // kernel.
   if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample) {
     choose_segments(a, params->pipeline_tiles);
-    // Small calls: eight workgroups per tile share the contraction axis (gate_split.hip).
-    if (a.nseg == 0 && a.ntiles >= 1 && a.ntiles <= kSplitMaxTiles && params->split_k != 1) {
+    // Small calls: eight or four workgroups per tile share the contraction axis (gate_split.hip).
+    if (a.nseg == 0 && a.ntiles >= 1 && a.ntiles <= kSplitMaxTiles && params->split_k != 1 &&
+        workspace_bytes_given >= ws_one) {
       int32_t* counters = split_counters_for(workspace);
       if (counters != nullptr) {
-        a.split = 8;
+        a.split = a.ntiles <= kSplitEightTiles ? 8 : 4;
         a.split_cnt = counters;
       }
     }
@@ -302,7 +310,7 @@ int laser_route_static(const void* hidden, const void* w_gate, int32_t T, int32_
                        float* logits_out, void* hip_stream) {
   const int rc = check_params(T, E, params);
   if (rc != LASER_OK) return rc;
-  if (workspace_bytes(T, E, record_width(params->c)) > kStaticBytes) return LASER_E_WORKSPACE;
+  if (workspace_needed_bytes(T, E, record_width(params->c)) > kStaticBytes) return LASER_E_WORKSPACE;
   void* ws = static_workspace();
   if (!ws) return LASER_E_LAUNCH;
   return route_impl(hidden, w_gate, 1, T, H, E, params, loads_inout, expert_ids, weights, permutation,

@@ -25,11 +25,12 @@ namespace laser {
 // of the code object (zero when it is loaded) of which every workspace address gets a slice
 // on first sight.  The last workgroup of a tile sets the tile's counter back to zero.  Calls
 // that share a workspace must not overlap anyway, so a slice has one user at a time.
-template <int EB, int NE, bool STATS>
+template <int EB, int NE, int NR, bool STATS>  // NR: wavefront roles per workgroup, 1 or 2
 __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int H, const RouteArgs a0,
     const Workspace ws, int32_t* __restrict__ expert_ids, float* __restrict__ weights,
     float* __restrict__ logits_out) {
+  static_assert(NR == 1 || NR == 2, "one or two roles per workgroup");
   extern __shared__ __align__(16) unsigned char gate_lds[];
   __shared__ unsigned long long mask64[64];
   __shared__ unsigned long long flex_lds;
@@ -37,30 +38,39 @@ __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
   RouteArgs a = a0;
   if (STATS && a.pool_in_ws) a.st_pool = ws.pool;
   const int T = a.T, E = a.E;
-  const int split = a.split;  // workgroups per tile
-  constexpr int nroles = 1;   // wavefront roles of a workgroup (the launcher sees to split == kGateWaves)
+  constexpr int split = kGateWaves / NR;  // workgroups per tile (the launcher sees to a.split == split)
+  constexpr int nroles = NR;
   // (the workgroups of a tile are ntiles apart in the grid)
   const int tile = (int)blockIdx.x % a.ntiles;
-  const int role = (int)blockIdx.x / a.ntiles;
-  const int part_of_tile = role;
+  const int part_of_tile = (int)blockIdx.x / a.ntiles;
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-  // The role's chunks are those of wave `role` of the unsplit kernel, in its order:
-  // chunk i is (start + 8 i) mod nfull.  Here wave v of the workgroup loads and stages
-  // chunk v + 8 r in round r, so that all chunks of a round are in flight at once (a role
-  // of the projection shapes with 2048 or 4096 columns is one round); then every wave
-  // multiplies the round's chunks, in the role's order, into its own 16x16 blocks of the
-  // partial tile: block (eb, tb) accumulates exactly the products it accumulates in the
-  // unsplit kernel, in the same order, whoever runs the instructions.
-  constexpr int kBlocks = EB * 4;                 // 16x16 blocks of the partial tile
-  constexpr int kMine = (kBlocks + kGateWaves - 1) / kGateWaves;  // per wave: blocks wave, wave + 8
-  f32x4 acc[kMine];
+  // The chunks of role r are those of wave r of the unsplit kernel, in its order: chunk i
+  // is (start + 8 i) mod nfull.  Here the chunks of the workgroup's roles form one list
+  // (role by role); wave v of the workgroup loads and stages item v + 8 n in round n, so
+  // that all items of a round are in flight at once (the projection shapes with 2048 or
+  // 4096 columns are one or two rounds).  Then four waves per role multiply the round's
+  // chunks of that role, in the role's order, each into its own 16x16 blocks of the role's
+  // partial tile (a 2x2 patch of blocks for 64 experts: two operands of each kind per
+  // product step instead of three for two blocks).  Block (eb, tb) accumulates exactly the
+  // products it accumulates in the unsplit kernel, in the same order, whoever runs the
+  // instructions.
+  constexpr int EBW = EB >= 4 ? 2 : 1;  // expert blocks per multiplying wave
+  constexpr int TBW = EB >= 2 ? 2 : 1;  // token blocks per multiplying wave
+  const int mrole = NR == 2 ? wave_u >> 2 : 0;       // the role this wave multiplies for ...
+  const bool multiplies = NR == 2 || wave_u < 4;     // ... if it does
+  const int mq = wave_u & 3;
+  const int eb0 = EB >= 4 ? 2 * (mq >> 1) : EB == 2 ? (mq >> 1) : 0;
+  const int tb0 = EB >= 2 ? 2 * (mq & 1) : mq;
+  f32x4 acc[EBW][TBW];
 #pragma unroll
-  for (int m = 0; m < kMine; ++m)
+  for (int e = 0; e < EBW; ++e)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) acc[m][r] = 0.0f;
+    for (int t = 0; t < TBW; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[e][t][r] = 0.0f;
 
   const int lrow = lane >> 3, lpiece = lane & 7;
   const size_t row_bytes = (size_t)H * 2;
@@ -76,22 +86,29 @@ __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
   const unsigned rd_lane = (lane & 15) * kRowBytes + (lane >> 4) * 16;
 
   const int nfull = H >> 6;
-  const int nmine = (nfull - role + kGateWaves - 1) / kGateWaves;  // full chunks of the role
-  const int start = nfull > 0 ? (tile * 5 + role) % nfull : 0;
-  // the ragged end of the contraction axis (H % 64 != 0) goes, as in the unsplit kernel, to
-  // one role, after its full chunks: pieces past H are read from the start of the row
-  // instead and replaced by zeros
-  const bool ragged = (H & 63) != 0 && role == (nfull & (kGateWaves - 1));
-  const int nitems = nmine + (ragged ? 1 : 0);
+  // per role: its full chunks, where it starts, and whether the ragged end of the
+  // contraction axis (H % 64 != 0) is its to take, after its full chunks, as in the unsplit
+  // kernel (pieces past H are read from the start of the row instead and replaced by zeros)
+  int nmine[NR], start[NR], nitem[NR];
+#pragma unroll
+  for (int rr = 0; rr < NR; ++rr) {
+    const int role = part_of_tile * NR + rr;
+    nmine[rr] = (nfull - role + kGateWaves - 1) / kGateWaves;
+    start[rr] = nfull > 0 ? (tile * 5 + role) % nfull : 0;
+    nitem[rr] = nmine[rr] + (((H & 63) != 0 && role == (nfull & (kGateWaves - 1))) ? 1 : 0);
+  }
+  const int nitems = nitem[0] + (NR == 2 ? nitem[NR - 1] : 0);
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
   u32x4 rh[8], rw[2 * EB];
-  auto load_item = [&](int i) {  // chunk i of the role, or (i == nmine) the ragged end
-    if (i < nmine) {
-      const int koff = ((start + kGateWaves * i) % nfull) * 128;
+  auto load_item = [&](int it) {
+    const int rr = (NR == 2 && it >= nitem[0]) ? 1 : 0;
+    const int i = it - (rr ? nitem[0] : 0);
+    if (i < nmine[rr]) {  // chunk i of the role
+      const int koff = ((start[rr] + kGateWaves * i) % nfull) * 128;
       GATE_GH(rh, koff)
       GATE_GW(rw, koff)
-    } else {
+    } else {  // the ragged end
       const bool kin = nfull * 64 + lpiece * 8 < H;  // H % 8 == 0: a piece is all in or all out
       const int off = kin ? nfull * 128 : -lpiece * 16;
 #pragma unroll
@@ -106,6 +123,25 @@ __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
       }
     }
   };
+  // the item in strip j, if it is one of this wave's role
+  auto multiply = [&](int j) {
+    const unsigned char* st_rd = gate_lds + j * kStripBytes + rd_lane;
+#pragma unroll
+    for (int s_ = 0; s_ < 2; ++s_) {
+      u32x4 a_[EBW], b_[TBW];
+#pragma unroll
+      for (int t = 0; t < TBW; ++t) b_[t] = *(lds_u4_ptr)(st_rd + (tb0 + t) * 16 * kRowBytes + s_ * 64);
+#pragma unroll
+      for (int e = 0; e < EBW; ++e)
+        a_[e] = *(lds_u4_ptr)(st_rd + kTile * kRowBytes + (eb0 + e) * 16 * kRowBytes + s_ * 64);
+#pragma unroll
+      for (int e = 0; e < EBW; ++e)
+#pragma unroll
+        for (int t = 0; t < TBW; ++t)
+          acc[e][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_[e]),
+                                                              __builtin_bit_cast(bf16x8, b_[t]), acc[e][t], 0, 0, 0);
+    }
+  };
   if (wave_u < nitems) load_item(wave_u);
   for (int r0 = 0; r0 < nitems; r0 += kGateWaves) {
     if (r0 + wave_u < nitems) {
@@ -114,51 +150,37 @@ __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
     __syncthreads();
     // the next round's loads travel while this round is multiplied
     if (r0 + kGateWaves + wave_u < nitems) load_item(r0 + kGateWaves + wave_u);
-    const int nround = min(kGateWaves, nitems - r0);
-    // chunk j of the round, from strip j
-    auto multiply = [&](int j) {
-      const unsigned char* st_rd = gate_lds + j * kStripBytes + rd_lane;
+    if (multiplies) {
+      // strips [j0, j1) hold this wave's role's items of the round
+      const int lo = mrole == 0 ? 0 : nitem[0], hi = mrole == 0 ? nitem[0] : nitems;
+      const int j0 = max(lo - r0, 0), j1 = min(min(hi - r0, kGateWaves), nitems - r0);
+      // (written out for the usual sizes, so that the operand reads of a chunk do not wait
+      // for the products of the chunk before)
+      if (j1 - j0 == 4) {
 #pragma unroll
-      for (int s_ = 0; s_ < 2; ++s_) {
+        for (int j = 0; j < 4; ++j) multiply(j0 + j);
+      } else if (j1 - j0 == 8) {
 #pragma unroll
-        for (int m = 0; m < kMine; ++m) {
-          const int blk = wave_u + m * kGateWaves;  // block (eb, tb) = (blk / 4, blk % 4)
-          if (blk < kBlocks) {
-            const u32x4 b_ = *(lds_u4_ptr)(st_rd + (blk & 3) * 16 * kRowBytes + s_ * 64);
-            const u32x4 a_ = *(lds_u4_ptr)(st_rd + kTile * kRowBytes + (blk >> 2) * 16 * kRowBytes + s_ * 64);
-            acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_),
-                                                             __builtin_bit_cast(bf16x8, b_), acc[m], 0, 0, 0);
-          }
-        }
+        for (int j = 0; j < 8; ++j) multiply(j);
+      } else {
+        for (int j = j0; j < j1; ++j) multiply(j);
       }
-    };
-    // (written out for the usual round sizes, so that the operand reads of a chunk do not
-    // wait for the products of the chunk before)
-    if (nround == 4) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) multiply(j);
-    } else if (nround == 8) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) multiply(j);
-    } else {
-      for (int j = 0; j < nround; ++j) multiply(j);
     }
-    __syncthreads();  // the strips are free again (after the last round: dead, the partial tile reuses the space)
+    __syncthreads();  // the strips are free again (after the last round: dead, the partial tiles reuse the space)
   }
   if (nitems == 0) __syncthreads();
 
   float* part = reinterpret_cast<float*>(gate_lds);  // [roles][64][kPartStride]
-  {
+  if (multiplies) {
     const int n = lane & 15, kgrp = lane >> 4;
+    float* mine = part + (size_t)mrole * kTile * kPartStride;
 #pragma unroll
-    for (int m = 0; m < kMine; ++m) {
-      const int blk = wave_u + m * kGateWaves;
-      if (blk < kBlocks) {
-        const int eb = blk >> 2, tb = blk & 3;
-        const float4 v = make_float4(acc[m][0], acc[m][1], acc[m][2], acc[m][3]);
-        *reinterpret_cast<float4*>(part + (tb * 16 + n) * kPartStride + eb * 16 + 4 * kgrp) = v;
+    for (int e = 0; e < EBW; ++e)
+#pragma unroll
+      for (int t = 0; t < TBW; ++t) {
+        const float4 v = make_float4(acc[e][t][0], acc[e][t][1], acc[e][t][2], acc[e][t][3]);
+        *reinterpret_cast<float4*>(mine + ((tb0 + t) * 16 + n) * kPartStride + (eb0 + e) * 16 + 4 * kgrp) = v;
       }
-    }
   }
   __syncthreads();
 
@@ -268,16 +290,16 @@ int32_t* split_counters_for(const void* workspace) {
   return nullptr;  // the table is crowded: the call runs without the split
 }
 
-template <int EB, int NE, bool STATS>
+template <int EB, int NE, int NR, bool STATS>
 static hipError_t launch_split(const void* hidden, const void* w, int H, const RouteArgs& a, const Workspace& ws,
                                int32_t* expert_ids, float* weights, float* logits_out, hipStream_t s) {
   static LdsAttr allowed;
-  const void* fn = reinterpret_cast<const void*>(&gate_split_bf16_kernel<EB, NE, STATS>);
+  const void* fn = reinterpret_cast<const void*>(&gate_split_bf16_kernel<EB, NE, NR, STATS>);
   const hipError_t e = allow_dynamic_lds(fn, kGateLdsBytes, allowed);
   if (e != hipSuccess) return e;
-  if (a.split != kGateWaves) return hipErrorInvalidValue;  // (one wavefront role per workgroup)
+  if (a.split * NR != kGateWaves) return hipErrorInvalidValue;
   clear_stale_error();
-  hipLaunchKernelGGL((gate_split_bf16_kernel<EB, NE, STATS>), dim3(a.ntiles * a.split), dim3(kGateThreads),
+  hipLaunchKernelGGL((gate_split_bf16_kernel<EB, NE, NR, STATS>), dim3(a.ntiles * a.split), dim3(kGateThreads),
                      kGateLdsBytes, s, static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(w), H, a, ws,
                      expert_ids, weights, logits_out);
   return hipGetLastError();
@@ -286,8 +308,13 @@ static hipError_t launch_split(const void* hidden, const void* w, int H, const R
 template <int EB, int NE>
 static hipError_t launch_split_one(const void* hidden, const void* w, int H, const RouteArgs& a, const Workspace& ws,
                                    int32_t* expert_ids, float* weights, float* logits_out, hipStream_t s) {
-  if (wants_stats(a)) return launch_split<EB, NE, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
-  return launch_split<EB, NE, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  const bool st = wants_stats(a);
+  if (a.split == kGateWaves) {
+    if (st) return launch_split<EB, NE, 1, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+    return launch_split<EB, NE, 1, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  }
+  if (st) return launch_split<EB, NE, 2, true>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
+  return launch_split<EB, NE, 2, false>(hidden, w, H, a, ws, expert_ids, weights, logits_out, s);
 }
 
 hipError_t launch_gate_split_bf16(const void* hidden, const void* w, int H, const RouteArgs& a, const Workspace& ws,

@@ -13,7 +13,8 @@ constexpr int kMaxE = 64;        // experts: one lane of a wavefront per expert
 constexpr int kMaxC = 16;        // trimming size the fast kernels carry (candidate ranks fit 4 bits)
 constexpr int kWideC = 64;       // trimming sizes above kMaxC: records of kWideC candidates, general kernels
 constexpr int kMaxK = 16;        // experts per token
-constexpr int kSplitMaxTiles = 32;  // calls of up to this many tiles may cut the contraction axis over workgroups
+constexpr int kSplitMaxTiles = 64;  // calls of up to this many tiles may cut the contraction axis over workgroups
+constexpr int kSplitEightTiles = 32;  // ... over eight per tile up to here, over four beyond
 
 // Per-call scalars handed to every kernel by value.
 struct RouteArgs {
@@ -47,7 +48,7 @@ struct RouteArgs {
   int nseg;            // segments: 1 + ceil((ntiles - seg_first) / seg_tiles); 0 when not pipelined
   // small single problems through the fused bf16 kernel: the contraction axis of a tile cut
   // over `split` workgroups (gate_split.hip)
-  int split;           // workgroups per tile (2, 4 or 8); 0: one workgroup per tile
+  int split;           // workgroups per tile (4 or 8); 0: one workgroup per tile
   int32_t* split_cnt;  // [ntiles] arrival counters, zero between calls (the library's own memory)
 };
 // First tile of segment j of a pipelined call (j <= nseg; segment nseg starts at ntiles or beyond).
@@ -161,7 +162,8 @@ constexpr int kSegCarry = 4;    // [64] per expert: assignments in the finished 
 constexpr int kSegDone = 128;   // [ntiles] wavefronts of the tile's analysis workgroup that have written their records
 
 inline int record_width(int c) { return c > kMaxC ? kWideC : kMaxC; }
-size_t workspace_bytes(int T, int E, int cw);
+size_t workspace_bytes(int T, int E, int cw);         // what laser_workspace_bytes reports
+size_t workspace_needed_bytes(int T, int E, int cw);  // what a single problem cannot do without
 Workspace carve_workspace(void* base, int T, int E, int cw);
 
 inline int padded_experts(int E) { return E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64; }

@@ -1,7 +1,7 @@
-"""GPU tests of split calls: a small bf16 batch (up to 32 tiles of 64 tokens) has the
-contraction axis of its gate projection cut over eight workgroups per tile, whose partial
-logit tiles meet in the workspace; the workgroup that arrives last adds them in the order
-the unsplit kernel uses.  Nothing may depend on the split, the logits included: every case
+"""GPU tests of split calls: a small bf16 batch (up to 64 tiles of 64 tokens) has the
+contraction axis of its gate projection cut over eight workgroups per tile (four beyond 32
+tiles), whose partial logit tiles meet in the workspace; the workgroup that arrives last
+adds them in the order the unsplit kernel uses.  Nothing may depend on the split, the logits included: every case
 is compared with the oracle and, bit for bit, with the same call run with `split_k = 1`."""
 from __future__ import annotations
 
@@ -46,9 +46,18 @@ CASES = [
     (300, 1000, 33, 3, 9, 0.4),      # ragged contraction axis (1000 = 15 chunks + 40), odd expert count
     (257, 40, 8, 2, 4, 1.0),         # no full chunk at all
     (1000, 2048, 64, 6, 8, 0.1),
-    (2048, 2048, 64, 6, 8, 0.5),     # 32 tiles: the most a split call takes; window evaluation
+    (2048, 2048, 64, 6, 8, 0.5),     # 32 tiles: the most that eight workgroups per tile take; window evaluation
     (2048, 4096, 32, 4, 8, 0.3),
     (1500, 768, 24, 5, 16, 0.6),
+    # 33 to 64 tiles: four workgroups per tile, two wavefront roles each
+    (2049, 2048, 64, 6, 8, 0.3),
+    (4096, 2048, 64, 6, 8, 0.2),     # one round of eight chunks per workgroup
+    (4096, 4096, 8, 2, 4, 0.4),      # two rounds
+    (3000, 512, 16, 4, 12, 0.3),     # one chunk per role
+    (2500, 320, 64, 6, 8, 0.3),      # five chunks: roles with one chunk and with none
+    (2200, 1000, 33, 3, 9, 0.4),     # ragged contraction axis
+    (2100, 40, 32, 4, 8, 0.5),       # no full chunk at all
+    (4096, 3000, 64, 6, 8, 0.1),     # six rounds, the last one ragged
 ]
 
 
@@ -64,14 +73,14 @@ def test_split_call_equals_oracle_and_unsplit_call(T, H, E, k, c, frac):
 
 
 def test_above_the_limit_nothing_changes():
-    """33 tiles: the call is not split, with or without the switch."""
+    """65 tiles: the call is not split, with or without the switch."""
     u = _util()
-    T, H, E, k, c = 2049, 512, 64, 6, 8
+    T, H, E, k, c = 4097, 512, 64, 6, 8
     hidden, w = _gate(77, T, H, E, 0.2)
     loads = np.zeros(E, np.int32)
-    gpu, _ = u.check_route(hidden, w, wl.DTYPE_BF16, k, c, 0.40, 0.80, loads, label="33 tiles")
+    gpu, _ = u.check_route(hidden, w, wl.DTYPE_BF16, k, c, 0.40, 0.80, loads, label="65 tiles")
     whole = u.run_route(hidden, w, wl.DTYPE_BF16, k, c, 0.40, 0.80, loads, split_k=1)
-    _same(gpu, whole, "33 tiles")
+    _same(gpu, whole, "65 tiles")
 
 
 def test_calls_in_a_row_on_one_workspace():
@@ -83,7 +92,7 @@ def test_calls_in_a_row_on_one_workspace():
     from paper_2510_03293_amd import binding as B
     u = _util()
     H, E, k, c = 1024, 64, 6, 8
-    sizes = [2048, 64, 700, 1, 2048, 130, 64, 64]
+    sizes = [2048, 64, 4096, 700, 1, 2048, 2500, 130, 64, 64]
     Tmax = max(sizes)
     params = [B.make_params(k, c, 0.40, 0.80, dtype=wl.DTYPE_BF16),
               B.make_params(k, c, 0.40, 0.80, dtype=wl.DTYPE_BF16, split_k=1)]
@@ -116,3 +125,32 @@ def test_split_call_with_statistics():
     _same(a, b, "statistics")
     for key in ("topk_mass", "entropy", "pool_size"):
         assert np.array_equal(a[key], b[key]), key
+
+
+def test_a_workspace_for_a_large_batch_serves_small_ones():
+    """The room for the partial tiles is part of what laser_workspace_bytes reports for up to
+    4096 tokens, but a call does not insist on it: in a workspace sized for 16384 tokens a
+    call of 4096 tokens finds too little room and runs without the split, one of 2048 tokens
+    splits; both equal the oracle."""
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    H, E, k, c = 512, 64, 6, 8
+    params = B.make_params(k, c, 0.40, 0.80, dtype=wl.DTYPE_BF16)
+    big = B.RouteBuffers(16384, H, E, params, want_logits=True)
+    assert B.laser_workspace_bytes(4096, H, E, params) > big.workspace.numel() > B.laser_workspace_bytes(2048, H, E, params)
+    for T in (4096, 2048, 4000, 64):
+        hidden, w = _gate(5 + T, T, H, E, 0.3)
+        loads = torch.zeros(E, dtype=torch.int32, device="cuda")
+        B.laser_route(u.to_device(hidden), u.to_device(w), T, H, E, params, loads, big.expert_ids, big.weights,
+                      big.permutation, big.expert_offsets, big.logits, big.workspace)
+        torch.cuda.synchronize()
+        assert B.laser_status(big.workspace) == B.STATUS_COMPLETE
+        z = big.logits.cpu().numpy().reshape(-1)[:T * E].reshape(T, E)
+        ref = oracle.route(z, k, c, 0.40, 0.80, np.zeros(E, np.int32))
+        got = {"expert_ids": big.expert_ids.cpu().numpy()[:T], "loads": loads.cpu().numpy(),
+               "expert_offsets": big.expert_offsets.cpu().numpy(),
+               "permutation": big.permutation.cpu().numpy()[:T * k]}
+        u.assert_discrete_equal(got, ref, f"T{T} in a workspace for 16384 tokens")
+        assert np.abs(z.astype(np.float64) - oracle.gate(hidden, w, wl.DTYPE_BF16)).max() <= u.TOL_LOGIT[wl.DTYPE_BF16]
