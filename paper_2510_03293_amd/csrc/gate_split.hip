@@ -6,7 +6,7 @@
 
 namespace laser {
 
-// ---- small calls (fewer tiles than an eighth of the compute units) -------------------
+// ---- small calls (at most a quarter as many tiles as the chip has compute units) ------
 //
 // In gate_analyse_bf16_kernel one workgroup streams the 64 rows of its tile and all of W
 // through one compute unit; with a handful of tiles the rest of the chip idles while that
