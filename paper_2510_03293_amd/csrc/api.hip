@@ -226,14 +226,15 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
   // kernel.
   if (params->dtype == LASER_DTYPE_BF16 && B == 1 && !general && !resample) {
     choose_segments(a, params->pipeline_tiles);
-    // Small calls: eight or four workgroups per tile share the contraction axis (gate_split.hip).
-    if (a.nseg == 0 && a.ntiles >= 1 && a.ntiles <= kSplitMaxTiles && params->split_k != 1 &&
-        workspace_bytes_given >= ws_one) {
-      int32_t* counters = split_counters_for(workspace);
-      if (counters != nullptr) {
-        a.split = a.ntiles <= kSplitEightTiles ? 8 : 4;
-        a.split_cnt = counters;
-      }
+  }
+  // Small calls, one problem through the fused bf16 kernel (whatever follows it): eight or
+  // four workgroups per tile share the contraction axis (gate_split.hip).
+  if (params->dtype == LASER_DTYPE_BF16 && B == 1 && a.nseg == 0 && a.ntiles >= 1 &&
+      a.ntiles <= kSplitMaxTiles && params->split_k != 1 && workspace_bytes_given >= ws_one) {
+    int32_t* counters = split_counters_for(workspace);
+    if (counters != nullptr) {
+      a.split = a.ntiles <= kSplitEightTiles ? 8 : 4;
+      a.split_cnt = counters;
     }
   }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given

@@ -154,3 +154,36 @@ def test_a_workspace_for_a_large_batch_serves_small_ones():
                "permutation": big.permutation.cpu().numpy()[:T * k]}
         u.assert_discrete_equal(got, ref, f"T{T} in a workspace for 16384 tokens")
         assert np.abs(z.astype(np.float64) - oracle.gate(hidden, w, wl.DTYPE_BF16)).max() <= u.TOL_LOGIT[wl.DTYPE_BF16]
+
+
+@pytest.mark.parametrize("T,E,k,c,trim", [(900, 32, 4, 6, "random"), (3000, 64, 6, 8, "random"),
+                                          (700, 64, 4, 40, "wide"), (2500, 64, 6, 64, "wide"),
+                                          (640, 16, 4, 4, "random c = k")])
+def test_split_call_with_random_or_wide_trimming(T, E, k, c, trim):
+    """RANDOM trimming and trimming sizes above 16 run other kernels behind the fused one;
+    the split of the fused one changes nothing for them either."""
+    import torch
+    import oracle
+    from paper_2510_03293_amd import binding as B
+    u = _util()
+    H = 512
+    hidden, w = wl.make_gate(np.random.default_rng(T + E), T, H, E, wl.DTYPE_BF16)
+    hd, wd = u.to_device(hidden), u.to_device(w)
+    extra = dict(trim_mode=B.TRIM_RANDOM, seed=11, stream=2, token_offset=50) if trim.startswith("random") else {}
+    outs = []
+    for split_k in (0, 1):
+        params = B.make_params(k, c, 2.0, 0.05, dtype=wl.DTYPE_BF16, split_k=split_k, **extra)
+        loads = torch.zeros(E, dtype=torch.int32, device="cuda")
+        buf = B.route(hd, wd, params, loads, want_logits=True)
+        torch.cuda.synchronize()
+        assert B.laser_status(buf.workspace) == B.STATUS_COMPLETE
+        outs.append({"expert_ids": buf.expert_ids.cpu().numpy(), "weights": buf.weights.cpu().numpy(),
+                     "permutation": buf.permutation.cpu().numpy(), "expert_offsets": buf.expert_offsets.cpu().numpy(),
+                     "loads": loads.cpu().numpy(), "logits": buf.logits.cpu().numpy()})
+    _same(outs[0], outs[1], trim)
+    z = outs[0]["logits"]
+    if trim.startswith("random"):
+        ref = oracle.route_random(z, k, c, 2.0, 0.05, np.zeros(E, np.int32), 11, 2, 50)
+    else:
+        ref = oracle.route(z, k, c, 2.0, 0.05, np.zeros(E, np.int32))
+    u.assert_discrete_equal(outs[0], ref, trim)
