@@ -15,7 +15,10 @@
  *     allocates nothing, frees nothing, never synchronises and never prints:
  *     all work is enqueued on `hip_stream` (a hipStream_t, NULL = default
  *     stream) and the call returns at once.  The one exception is laser_status(),
- *     a query that waits for the stream.
+ *     a query that waits for the stream.  (The library's code object holds two
+ *     arrays of device memory of its own, there on every GPU from the moment it is
+ *     loaded: the workspace of laser_route_static and 256 KiB of counters that
+ *     small calls use, see split_k.)
  *   - Return value: LASER_OK (0) or a negative LASER_E_* code.  Arguments are
  *     validated on the host before anything is enqueued; on error nothing was
  *     enqueued and no buffer was touched.  laser_strerror() names a code.
