@@ -129,6 +129,9 @@ static RouteArgs make_args(int32_t T, int32_t E, const laser_params_t* p) {
   a.nseg = 0;
   a.split = 0;
   a.split_cnt = nullptr;
+  a.one_permutation = nullptr;
+  a.one_expert_offsets = nullptr;
+  a.one_loads = nullptr;
   return a;
 }
 
@@ -235,6 +238,11 @@ int route_impl(const void* hidden, const void* w_gate, int32_t B, int32_t T, int
     if (counters != nullptr) {
       a.split = a.ntiles <= kSplitEightTiles ? 8 : 4;
       a.split_cnt = counters;
+      if (a.ntiles == 1 && !general && !resample) {  // (nothing between the fused kernel and the tail kernel)
+        a.one_permutation = permutation;
+        a.one_expert_offsets = expert_offsets;
+        a.one_loads = loads_inout;
+      }
     }
   }
   const RouteArgs an = wide ? narrowed(a) : a;  // what the fast analysis kernels are given

@@ -250,6 +250,40 @@ __global__ __launch_bounds__(kGateThreads) void gate_split_bf16_kernel(
   __syncthreads();
   analyse_tile<NE, kGateWaves, STATS>(part, kPartStride, mask64, &flex_lds, tile, a, ws, expert_ids, weights,
                                       logits_out);
+
+  // ---- a call of one tile without load-dependent tokens ends here -----------------------
+  // Everything the dispatch tables need is in this workgroup: per expert the tokens
+  // assigned to it (mask64) and, just written, the tokens' experts in rank order.  The
+  // tables are those the tail kernel would write (a stable counting sort of the T k
+  // assignments); it finds the mark and returns at once.
+  if (NR == 1 && a.one_permutation != nullptr) {  // (a.ntiles == 1)
+    __shared__ int sh_off[64];
+    __syncthreads();  // the expert ids are stored, mask64 and flex_lds are final
+    if (flex_lds != 0ull) return;
+    if (wave == 0) {  // lane = expert
+      const int cnt = lane < E ? __builtin_popcountll(mask64[lane]) : 0;
+      int incl = cnt;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+      }
+      sh_off[lane] = incl - cnt;
+      if (lane < E) {
+        a.one_expert_offsets[lane] = incl - cnt;
+        a.one_loads[lane] += cnt;
+      }
+      if (lane == E - 1) a.one_expert_offsets[E] = incl;
+    }
+    __syncthreads();
+    const int k = a.k;
+    for (int slot = threadIdx.x; slot < T * k; slot += kGateThreads) {
+      const int t = slot / k;
+      const int e = expert_ids[slot];
+      a.one_permutation[sh_off[e] + __builtin_popcountll(mask64[e] & lanes_below(t))] = slot;
+    }
+    if (threadIdx.x == 0) ws.status[kStatusPhase] = kPhaseAllDone;
+  }
 }
 
 // ---- the counters ---------------------------------------------------------------------

@@ -50,6 +50,11 @@ struct RouteArgs {
   // over `split` workgroups (gate_split.hip)
   int split;           // workgroups per tile (4 or 8); 0: one workgroup per tile
   int32_t* split_cnt;  // [ntiles] arrival counters, zero between calls (the library's own memory)
+  // a split call of one tile without load-dependent tokens is finished by the workgroup
+  // that analyses it (the tail kernel then returns at once); NULL: never
+  int32_t* one_permutation;     // the call's permutation ...
+  int32_t* one_expert_offsets;  // ... expert_offsets ...
+  int32_t* one_loads;           // ... and loads_inout
 };
 // First tile of segment j of a pipelined call (j <= nseg; segment nseg starts at ntiles or beyond).
 __host__ __device__ inline int segment_start(const RouteArgs& a, int j) {
@@ -142,7 +147,8 @@ __device__ __forceinline__ Workspace problem_workspace(const Workspace& w0, size
   return w;
 }
 
-constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished
+constexpr int kStatusPhase = 0;      // 1: fixed prefix published, 2: chain finished, 3: nothing left for the tail kernel
+constexpr int kPhaseAllDone = 3;
 constexpr int kStatusFlexTiles = 1;  // number of tiles that hold flexible tokens
 constexpr int kStatusError = 2;      // 0, or why the outputs of the call are incomplete (kError*)
 constexpr int kErrorTimeout = 1;        // a bounded wait in the tail kernel ran out (LASER_STATUS_TIMEOUT)

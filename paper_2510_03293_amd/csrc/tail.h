@@ -1938,6 +1938,8 @@ __device__ __forceinline__ void tail_role(int block, uint8_t* tail_lds, const Ro
                                           int32_t* __restrict__ expert_offsets,
                                           int32_t* __restrict__ expert_ids, float* __restrict__ weights,
                                           int32_t* __restrict__ permutation) {
+  // (a split call of one tile may have been finished by the workgroup that analysed it)
+  if (a.one_permutation != nullptr && ws.status[kStatusPhase] == kPhaseAllDone) return;
   if (block == 0) {
     chain_segments<false>(tail_lds, a, ws, loads_inout, expert_offsets);
     return;

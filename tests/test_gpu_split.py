@@ -37,6 +37,11 @@ def _same(a, b, label):
 CASES = [
     # T, H, E, k, c, share of flat rows
     (1, 2048, 64, 6, 8, 0.0),
+    # one tile without a load-dependent token: the fused kernel writes the dispatch tables itself
+    (64, 2048, 64, 6, 8, 0.0),
+    (37, 512, 8, 2, 4, 0.0),
+    (64, 4096, 16, 4, 12, 0.0),
+    (50, 1000, 33, 3, 9, 0.0),
     (64, 2048, 64, 6, 8, 0.3),       # the decode shape: one tile, written-out loop of 4 chunks
     (64, 4096, 8, 2, 4, 0.5),        # written-out loop of 8 chunks, one expert block
     (65, 4096, 64, 6, 8, 0.3),       # a second tile of one token
